@@ -1,0 +1,510 @@
+/*
+ * CPU oracle for the Allgather schedules of the Sparbit paper.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It is a plain, slow,
+ * single-threaded p-rank message-passing simulation: every virtual rank runs
+ * the paper's per-process program, posts non-blocking single-block sends and
+ * receives, and a "wait-all" phase matches and delivers them.  It shares no
+ * code, header, table or helper with the HIP library and neither includes the
+ * other.  Only tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.
+ *
+ * What it simulates
+ *   - MPI_Allgather post-condition (Section II): block of rank j ends in slot
+ *     j of every rank's receive buffer.  oracle_naive_allgather() is that
+ *     definition written out.
+ *   - Sparbit, Algorithm 1 (Section III-B), executed literally per rank with
+ *     the variables data / ignore / d / last_ignore / ignore_steps.
+ *   - Ring, Recursive Doubling and Bruck as described in Section II-A
+ *     (context schedules).
+ *
+ * Readings of the paper taken here (the paper is silent or garbled there):
+ *   - Algorithm 1 tests "ignore_vector" but declares "ignore_steps": one and
+ *     the same mask.
+ *   - "rank + d % p" means (rank + d) mod p (Figure 3 text: wrap-around).
+ *   - The loop runs ceil(log2 p) times (loop header and cost formula), not
+ *     log2 p as one sentence of the prose says.
+ *   - Algorithm 1 never places the rank's own block: it is put into slot
+ *     `rank` before step 0 (required by the Allgather post-condition and by
+ *     the Figure 3 text, where step 0 sends the "original block").  With a
+ *     NULL send buffer the call is "in place": slot `rank` already holds it.
+ *   - p = 1: zero steps, the result is the own block.
+ *   - Displacements are reduced with a true mathematical modulo.
+ *   - Each Isend/Irecv carries one block (count argument 1); a step's
+ *     messages are all posted before any is delivered (Waitall), so sends see
+ *     the pre-step buffer.  The simulation stages every payload in a mailbox
+ *     between the two phases.
+ *   - Ring: in step s rank r sends slot (r - s) mod p to r + 1 and receives
+ *     slot (r - 1 - s) mod p from r - 1 (own block first, then the block
+ *     received in the previous step).
+ *   - Recursive Doubling: before step s rank r holds the aligned group of 2^s
+ *     slots that contains r and exchanges that whole group with r xor 2^s.
+ *   - Bruck: each rank works in a rotated buffer (working slot i holds block
+ *     (r + i) mod p); in step s it sends its first min(2^s, p - 2^s) working
+ *     slots to r - 2^s and appends what r + 2^s sends; a final local rotation
+ *     by r restores rank order.  The paper names only the partner, the volume
+ *     and the "memory shifts"; the layout is the textbook one: parity unpinned
+ *     for Bruck's intermediate working-buffer layout (its final state, step
+ *     count and per-step volume are pinned).
+ *
+ * Checks made while simulating (any violation aborts with an error code):
+ *   - every posted send is matched by exactly one posted receive and vice
+ *     versa, in posting order per (source, destination) pair;
+ *   - a send never reads a slot that was not yet written;
+ *   - a receive never lands in a slot that is already written or that is a
+ *     send source in the same step (each of the p*p slots is written once);
+ *   - for Sparbit the receiver's displacement equals the sender's.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_SPARBIT 0
+#define ORACLE_RING 1
+#define ORACLE_RECURSIVE_DOUBLING 2
+#define ORACLE_BRUCK 3
+#define ORACLE_NAIVE 4
+
+#define ORACLE_OK 0
+#define ORACLE_ERR_ARG (-1)
+#define ORACLE_ERR_NOMEM (-2)
+#define ORACLE_ERR_UNMATCHED (-3)      /* a send or receive found no counterpart */
+#define ORACLE_ERR_READ_UNWRITTEN (-4) /* a send read a slot nobody wrote yet */
+#define ORACLE_ERR_DOUBLE_WRITE (-5)   /* a receive hit a slot already written */
+#define ORACLE_ERR_READ_WRITE (-6)     /* slot both sent and received in one step */
+#define ORACLE_ERR_SLOT_MISMATCH (-7)  /* Sparbit: send and receive displacement differ */
+#define ORACLE_ERR_UNSUPPORTED (-8)    /* Recursive Doubling with p not a power of two */
+#define ORACLE_ERR_TRACE_FULL (-9)
+
+typedef struct {
+    int peer;
+    int slot;
+} post_t;
+
+typedef struct {
+    int p;
+    size_t B;
+    uint8_t *recv;    /* p * p * B, caller's memory */
+    uint8_t *written; /* p * p: 0 = poison, 1 = holds a block */
+    uint8_t *sent_now; /* p * p: slot is a send source in the current step */
+    post_t *sends;    /* [p][cap] in posting order */
+    post_t *recvs;    /* [p][cap] */
+    int *nsends, *nrecvs;
+    int cap;
+    int step;
+    /* optional trace, rows of 5 int32: step, src, dst, src_slot, dst_slot */
+    int32_t *trace;
+    size_t trace_cap, trace_len;
+} sim_t;
+
+static long long mod_ll(long long x, long long p)
+{
+    long long m = x % p;
+    return m < 0 ? m + p : m;
+}
+
+static int ceil_log2_int(int p)
+{
+    int l = 0;
+    while ((1LL << l) < (long long)p)
+        l++;
+    return l;
+}
+
+static int count_trailing_zeros_int(int p)
+{
+    int n = 0;
+    while (((p >> n) & 1) == 0)
+        n++;
+    return n;
+}
+
+static uint8_t *slot_ptr(sim_t *s, int rank, int slot)
+{
+    return s->recv + ((size_t)rank * (size_t)s->p + (size_t)slot) * s->B;
+}
+
+static void post_isend(sim_t *s, int rank, int peer, int slot)
+{
+    post_t *q = &s->sends[(size_t)rank * s->cap + s->nsends[rank]++];
+    q->peer = peer;
+    q->slot = slot;
+}
+
+static void post_irecv(sim_t *s, int rank, int peer, int slot)
+{
+    post_t *q = &s->recvs[(size_t)rank * s->cap + s->nrecvs[rank]++];
+    q->peer = peer;
+    q->slot = slot;
+}
+
+/* Wait-all: phase 1 stages every posted send's payload (reading the pre-step
+ * buffers), phase 2 delivers each posted receive from the oldest unconsumed
+ * send of that source addressed to this rank. */
+static int waitall(sim_t *s, int require_same_slot)
+{
+    const int p = s->p;
+    const size_t B = s->B;
+    size_t total = 0;
+    int r, j;
+    for (r = 0; r < p; r++)
+        total += (size_t)s->nsends[r];
+    if (total == 0) {
+        for (r = 0; r < p; r++)
+            if (s->nrecvs[r])
+                return ORACLE_ERR_UNMATCHED;
+        return ORACLE_OK;
+    }
+    uint8_t *mailbox = (uint8_t *)malloc(total * B);
+    size_t *base = (size_t *)malloc((size_t)p * sizeof(size_t));
+    uint8_t *consumed = (uint8_t *)calloc(total, 1);
+    int *cursor = (int *)calloc((size_t)p, sizeof(int));
+    int rc = ORACLE_OK;
+    if (!mailbox || !base || !consumed || !cursor) {
+        rc = ORACLE_ERR_NOMEM;
+        goto out;
+    }
+    memset(s->sent_now, 0, (size_t)p * p);
+    {
+        size_t k = 0;
+        for (r = 0; r < p; r++) {
+            base[r] = k;
+            for (j = 0; j < s->nsends[r]; j++, k++) {
+                post_t *q = &s->sends[(size_t)r * s->cap + j];
+                if (!s->written[(size_t)r * p + q->slot]) {
+                    rc = ORACLE_ERR_READ_UNWRITTEN;
+                    goto out;
+                }
+                s->sent_now[(size_t)r * p + q->slot] = 1;
+                memcpy(mailbox + k * B, slot_ptr(s, r, q->slot), B);
+            }
+        }
+    }
+    for (r = 0; r < p; r++) {
+        for (j = 0; j < s->nrecvs[r]; j++) {
+            post_t *rq = &s->recvs[(size_t)r * s->cap + j];
+            int src = rq->peer;
+            int k, found = -1;
+            while (cursor[src] < s->nsends[src] && consumed[base[src] + cursor[src]])
+                cursor[src]++;
+            for (k = cursor[src]; k < s->nsends[src]; k++) {
+                if (!consumed[base[src] + k] &&
+                    s->sends[(size_t)src * s->cap + k].peer == r) {
+                    found = k;
+                    break;
+                }
+            }
+            if (found < 0) {
+                rc = ORACLE_ERR_UNMATCHED;
+                goto out;
+            }
+            consumed[base[src] + found] = 1;
+            {
+                int src_slot = s->sends[(size_t)src * s->cap + found].slot;
+                if (require_same_slot && src_slot != rq->slot) {
+                    rc = ORACLE_ERR_SLOT_MISMATCH;
+                    goto out;
+                }
+                if (s->written[(size_t)r * p + rq->slot]) {
+                    rc = ORACLE_ERR_DOUBLE_WRITE;
+                    goto out;
+                }
+                if (s->sent_now[(size_t)r * p + rq->slot]) {
+                    rc = ORACLE_ERR_READ_WRITE;
+                    goto out;
+                }
+                memcpy(slot_ptr(s, r, rq->slot), mailbox + (base[src] + found) * B, B);
+                s->written[(size_t)r * p + rq->slot] = 1;
+                if (s->trace) {
+                    if (s->trace_len >= s->trace_cap) {
+                        rc = ORACLE_ERR_TRACE_FULL;
+                        goto out;
+                    }
+                    int32_t *t = s->trace + 5 * s->trace_len++;
+                    t[0] = s->step;
+                    t[1] = src;
+                    t[2] = r;
+                    t[3] = src_slot;
+                    t[4] = rq->slot;
+                }
+            }
+        }
+    }
+    {
+        size_t k;
+        for (k = 0; k < total; k++)
+            if (!consumed[k]) {
+                rc = ORACLE_ERR_UNMATCHED;
+                goto out;
+            }
+    }
+out:
+    free(mailbox);
+    free(base);
+    free(consumed);
+    free(cursor);
+    for (r = 0; r < p; r++)
+        s->nsends[r] = s->nrecvs[r] = 0;
+    return rc;
+}
+
+/* ---- Sparbit, Algorithm 1: per-rank variables exactly as the listing names them */
+typedef struct {
+    int data;
+    int ignore;
+    int d;
+    int last_ignore;
+    unsigned long long ignore_steps;
+} sparbit_rank_t;
+
+static void sparbit_rank_init(sparbit_rank_t *v, int p)
+{
+    v->data = 1;
+    v->ignore = 0;
+    v->d = 1 << (ceil_log2_int(p) - 1);
+    v->last_ignore = count_trailing_zeros_int(p);
+    v->ignore_steps = (~((unsigned long long)p >> v->last_ignore) | 1ULL) << v->last_ignore;
+}
+
+static void sparbit_rank_post(sparbit_rank_t *v, sim_t *s, int rank)
+{
+    const int p = s->p;
+    int j;
+    if ((unsigned long long)v->d & v->ignore_steps)
+        v->ignore = 1;
+    for (j = 0; j < v->data - v->ignore; j++) {
+        post_isend(s, rank, (int)mod_ll((long long)rank + v->d, p),
+                   (int)mod_ll((long long)rank - 2LL * j * v->d, p));
+        post_irecv(s, rank, (int)mod_ll((long long)rank - v->d, p),
+                   (int)mod_ll((long long)rank - (2LL * j + 1) * v->d, p));
+    }
+}
+
+static void sparbit_rank_advance(sparbit_rank_t *v)
+{
+    v->d = v->d >> 1;
+    v->data = (v->data << 1) - v->ignore;
+    v->ignore = 0;
+}
+
+/* Number of communication steps of a schedule (Section II-A cost formulas,
+ * Algorithm 1 loop bound).  -1 if the schedule does not support p. */
+int oracle_num_steps(int algo, int p)
+{
+    if (p < 1)
+        return -1;
+    switch (algo) {
+    case ORACLE_SPARBIT:
+    case ORACLE_BRUCK:
+        return ceil_log2_int(p);
+    case ORACLE_RING:
+        return p - 1;
+    case ORACLE_RECURSIVE_DOUBLING:
+        return (p & (p - 1)) ? -1 : ceil_log2_int(p);
+    case ORACLE_NAIVE:
+        return 0;
+    default:
+        return -1;
+    }
+}
+
+/* MPI_Allgather by definition (Section II): recv[r][k] = send[k]. */
+int oracle_naive_allgather(int p, size_t B, const void *send, void *recv)
+{
+    int r, k;
+    if (p < 1 || B == 0 || !send || !recv)
+        return ORACLE_ERR_ARG;
+    for (r = 0; r < p; r++)
+        for (k = 0; k < p; k++)
+            memcpy((uint8_t *)recv + ((size_t)r * p + k) * B, (const uint8_t *)send + (size_t)k * B, B);
+    return ORACLE_OK;
+}
+
+/*
+ * Run `algo` for p ranks with blocks of B bytes.
+ *   send      p blocks (rank r at byte r*B), or NULL for in-place: recv[r][r]
+ *             already holds rank r's block.
+ *   recv      p*p blocks, rank r's buffer at byte r*p*B.  Slots that are never
+ *             written keep whatever the caller put there (poison).
+ *   max_steps run only the first max_steps communication steps (negative =
+ *             all).  Bruck's final rotation happens only when all steps ran.
+ *   step_info optional, [num_steps][3] int32: per step the distance d, the
+ *             ignore flag (Sparbit; 0 otherwise) and the number of blocks rank
+ *             0 sent.
+ *   sent_per_rank optional, [p] int64: total blocks each rank sent.
+ *   trace     optional, rows of 5 int32 (step, src, dst, src_slot, dst_slot),
+ *             one per delivered message; trace_cap rows available, *trace_len
+ *             receives the number written.
+ * Returns ORACLE_OK or a negative ORACLE_ERR_* code.
+ */
+int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, int max_steps,
+                     int32_t *step_info, int64_t *sent_per_rank, int32_t *trace, size_t trace_cap,
+                     size_t *trace_len)
+{
+    sim_t s;
+    int rc = ORACLE_OK, r, step, nsteps;
+    sparbit_rank_t *sv = NULL;
+    int *bruck_have = NULL;
+
+    if (p < 1 || B == 0 || !recv)
+        return ORACLE_ERR_ARG;
+    if (algo == ORACLE_NAIVE)
+        return oracle_naive_allgather(p, B, send, recv);
+    nsteps = oracle_num_steps(algo, p);
+    if (nsteps < 0)
+        return (algo == ORACLE_RECURSIVE_DOUBLING) ? ORACLE_ERR_UNSUPPORTED : ORACLE_ERR_ARG;
+    if (algo == ORACLE_BRUCK && !send)
+        return ORACLE_ERR_ARG; /* the rotated working buffer has no in-place form */
+
+    memset(&s, 0, sizeof s);
+    s.p = p;
+    s.B = B;
+    s.recv = (uint8_t *)recv;
+    s.cap = p;
+    s.trace = trace;
+    s.trace_cap = trace_cap;
+    s.written = (uint8_t *)calloc((size_t)p * p, 1);
+    s.sent_now = (uint8_t *)calloc((size_t)p * p, 1);
+    s.sends = (post_t *)malloc((size_t)p * s.cap * sizeof(post_t));
+    s.recvs = (post_t *)malloc((size_t)p * s.cap * sizeof(post_t));
+    s.nsends = (int *)calloc((size_t)p, sizeof(int));
+    s.nrecvs = (int *)calloc((size_t)p, sizeof(int));
+    sv = (sparbit_rank_t *)calloc((size_t)p, sizeof(sparbit_rank_t));
+    bruck_have = (int *)calloc((size_t)p, sizeof(int));
+    if (!s.written || !s.sent_now || !s.sends || !s.recvs || !s.nsends || !s.nrecvs || !sv ||
+        !bruck_have) {
+        rc = ORACLE_ERR_NOMEM;
+        goto out;
+    }
+    if (sent_per_rank)
+        memset(sent_per_rank, 0, (size_t)p * sizeof(int64_t));
+
+    /* own block: slot `rank` (working slot 0 for Bruck) */
+    for (r = 0; r < p; r++) {
+        int own = (algo == ORACLE_BRUCK) ? 0 : r;
+        if (send)
+            memcpy(slot_ptr(&s, r, own), (const uint8_t *)send + (size_t)r * B, B);
+        s.written[(size_t)r * p + own] = 1;
+        bruck_have[r] = 1;
+        if (algo == ORACLE_SPARBIT && p > 1)
+            sparbit_rank_init(&sv[r], p);
+    }
+
+    if (max_steps < 0 || max_steps > nsteps)
+        max_steps = nsteps;
+    for (step = 0; step < max_steps; step++) {
+        s.step = step;
+        for (r = 0; r < p; r++) {
+            int j;
+            switch (algo) {
+            case ORACLE_SPARBIT:
+                sparbit_rank_post(&sv[r], &s, r);
+                break;
+            case ORACLE_RING:
+                post_isend(&s, r, (int)mod_ll(r + 1, p), (int)mod_ll((long long)r - step, p));
+                post_irecv(&s, r, (int)mod_ll(r - 1, p), (int)mod_ll((long long)r - 1 - step, p));
+                break;
+            case ORACLE_RECURSIVE_DOUBLING: {
+                int w = 1 << step, peer = r ^ w;
+                int mine = r & ~(w - 1), theirs = peer & ~(w - 1);
+                for (j = 0; j < w; j++) {
+                    post_isend(&s, r, peer, mine + j);
+                    post_irecv(&s, r, peer, theirs + j);
+                }
+                break;
+            }
+            case ORACLE_BRUCK: {
+                int w = 1 << step;
+                int n = (w < p - w) ? w : p - w; /* min(2^s, p - 2^s) */
+                for (j = 0; j < n; j++) {
+                    post_isend(&s, r, (int)mod_ll((long long)r - w, p), j);
+                    post_irecv(&s, r, (int)mod_ll((long long)r + w, p), bruck_have[r] + j);
+                }
+                bruck_have[r] += n;
+                break;
+            }
+            }
+            if (sent_per_rank)
+                sent_per_rank[r] += s.nsends[r];
+        }
+        if (step_info) {
+            int32_t *si = step_info + 3 * step;
+            si[1] = 0;
+            si[2] = s.nsends[0];
+            switch (algo) {
+            case ORACLE_SPARBIT:
+                si[0] = sv[0].d;
+                si[1] = sv[0].ignore;
+                break;
+            case ORACLE_RING:
+                si[0] = 1;
+                break;
+            default:
+                si[0] = 1 << step;
+                break;
+            }
+        }
+        rc = waitall(&s, algo == ORACLE_SPARBIT);
+        if (rc != ORACLE_OK)
+            goto out;
+        if (algo == ORACLE_SPARBIT)
+            for (r = 0; r < p; r++)
+                sparbit_rank_advance(&sv[r]);
+    }
+
+    if (algo == ORACLE_BRUCK && max_steps == nsteps) {
+        /* local memory shift: working slot i of rank r is block (r + i) mod p */
+        uint8_t *row = (uint8_t *)malloc((size_t)p * B);
+        if (!row) {
+            rc = ORACLE_ERR_NOMEM;
+            goto out;
+        }
+        for (r = 0; r < p; r++) {
+            int i;
+            memcpy(row, slot_ptr(&s, r, 0), (size_t)p * B);
+            for (i = 0; i < p; i++)
+                memcpy(slot_ptr(&s, r, (int)mod_ll((long long)r + i, p)), row + (size_t)i * B, B);
+        }
+        free(row);
+    }
+out:
+    if (trace_len)
+        *trace_len = s.trace_len;
+    free(s.written);
+    free(s.sent_now);
+    free(s.sends);
+    free(s.recvs);
+    free(s.nsends);
+    free(s.nrecvs);
+    free(sv);
+    free(bruck_have);
+    return rc;
+}
+
+const char *oracle_strerror(int code)
+{
+    switch (code) {
+    case ORACLE_OK:
+        return "ok";
+    case ORACLE_ERR_ARG:
+        return "bad argument";
+    case ORACLE_ERR_NOMEM:
+        return "out of host memory";
+    case ORACLE_ERR_UNMATCHED:
+        return "a send or receive has no counterpart";
+    case ORACLE_ERR_READ_UNWRITTEN:
+        return "a send reads a slot that was never written";
+    case ORACLE_ERR_DOUBLE_WRITE:
+        return "a receive lands in a slot that is already written";
+    case ORACLE_ERR_READ_WRITE:
+        return "a slot is sent and received in the same step";
+    case ORACLE_ERR_SLOT_MISMATCH:
+        return "Sparbit: receive displacement differs from send displacement";
+    case ORACLE_ERR_UNSUPPORTED:
+        return "schedule does not support this number of ranks";
+    case ORACLE_ERR_TRACE_FULL:
+        return "trace buffer too small";
+    default:
+        return "unknown oracle error";
+    }
+}
