@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the Sparbit Allgather hot path on one MI355X.
+
+One "step" is one whole Allgather call (own-block placement + all
+ceil(log2 p) schedule steps) over one batch of synthetic input that is already
+resident in HBM.  Prints ONE JSON line.  The headline workload is cfg4 (p=128
+virtual ranks, 1 MiB blocks, 16 GiB of receive buffers): the large-block,
+HBM-bound configuration the metric's bandwidth target is stated for.
+
+  value      effective Allgather GB/s = p*p*B / t   (bytes landed per second)
+  roofline   algorithmic HBM bytes (every delivered byte read once and written
+             once: 2*p*p*B per call) / time, against the 8 TB/s HBM peak; time
+             is taken with HIP events on the launch stream over the timed
+             region
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample of the
+             same workload (same p, smaller blocks)
+  per_config other configs, context schedules and a device memcpy ceiling,
+             5 warm-up + 20 timed calls each (protocol of the paper's Section
+             IV-A, shortened)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--mode", default="auto", choices=["auto", "per_step", "persistent"])
+    ap.add_argument("--skip-context", action="store_true", help="only the headline workload")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE")
+    return ap.parse_args()
+
+
+def time_calls(torch, fn, stream, warmup, steps):
+    """Average / min / max milliseconds per call; events sit on `stream`."""
+    with torch.cuda.stream(stream):
+        for _ in range(warmup):
+            fn()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t_wall = time.perf_counter()
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        evs[0].record(stream)
+        for i in range(steps):
+            fn()
+            evs[i + 1].record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t_wall) * 1e3
+    per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    total = evs[0].elapsed_time(evs[steps])
+    return {"avg_ms": total / steps, "min_ms": min(per), "max_ms": max(per), "wall_ms_per_call": wall_ms / steps}
+
+
+def make_device_send(torch, w, dev):
+    from paper_2109_08751_amd import workloads
+    return torch.from_numpy(workloads.make_send(w)).to(dev)
+
+
+def rates(p, B, ms):
+    landed = p * p * B
+    return {"effective_GBps": landed / ms / 1e6, "hbm_GBps": 2 * landed / ms / 1e6,
+            "hbm_frac": 2 * landed / ms / 1e6 / HBM_PEAK_GBPS}
+
+
+def cpu_baseline(w):
+    """Time the oracle (single-threaded C simulation) on the same p with smaller
+    blocks, sized from a short probe so that it costs roughly 10 s."""
+    import numpy as np
+    import oracle
+    from paper_2109_08751_amd import workloads
+
+    p = w.p
+
+    def run(B):
+        send = np.tile(workloads.make_send_raw(p, min(B, 4096), 1), (1, max(B // 4096, 1)))[:, :B].copy()
+        recv = np.full((p, p, B), workloads.POISON, dtype=np.uint8)
+        t = time.perf_counter()
+        oracle.allgather(oracle.SPARBIT, p, B, send, recv)
+        dt = time.perf_counter() - t
+        assert (recv[p - 1, 0] == send[0]).all()
+        return dt
+
+    B = max(16, min(w.block_bytes, 4096))
+    dt = run(B)
+    rate = p * p * B / dt
+    target = max(B, min(w.block_bytes, int(rate * 10.0 / (p * p))))
+    Bs = 1 << (target.bit_length() - 1)
+    while Bs > B and p * p * Bs > (8 << 30):
+        Bs >>= 1
+    if Bs > B:
+        dt, B = run(Bs), Bs
+    return {"value": p * p * B / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "seconds": dt,
+            "sample": f"Sparbit oracle, p={p}, block {B} B (workload block {w.block_bytes} B), "
+                      f"recv {p * p * B / 2**20:.0f} MiB, one pass"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (all virtual ranks share one HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    import paper_2109_08751_amd as sb
+    from paper_2109_08751_amd import workloads
+
+    for kv in args.tune:
+        k, v = kv.split("=")
+        sb.sparbit_tune(k, int(v))
+    mode = {"auto": sb.MODE_AUTO, "per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT}[args.mode]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.Stream()
+    w = workloads.WORKLOADS[args.workload]
+    p, B = w.p, w.block_bytes
+
+    # ---- headline: timed region of exactly --steps calls
+    d_send = make_device_send(torch, w, dev)
+    d_recv = torch.full((p, p, B), workloads.POISON, dtype=torch.uint8, device=dev)
+    call = lambda: sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, mode, stream)
+    head = time_calls(torch, call, stream, args.warmup, args.steps)
+    assert sb.sparbit_barrier_timeouts(stream) == 0
+    ok = all(bool(torch.equal(d_recv[r], d_send)) for r in (0, p // 2, p - 1))
+    if not ok:
+        print("bench.py: result check failed", file=sys.stderr)
+        sys.exit(1)
+    r = rates(p, B, head["avg_ms"])
+    nsteps = sb.Plan(p).num_steps
+    launches = 1 if (mode == sb.MODE_PERSISTENT) else nsteps + 1
+    out = {
+        "metric": "effective Allgather GB/s (p*p*block_bytes landed / time), Sparbit schedule",
+        "value": r["effective_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["avg_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}; recv {w.recv_bytes / 2**30:.2f} GiB; {nsteps} steps",
+                   "p": p, "block_bytes": B, "mode": args.mode},
+        "min_ms": head["min_ms"], "max_ms": head["max_ms"], "wall_ms_per_step": head["wall_ms_per_call"],
+        "roofline": {"bound": "hbm", "achieved": r["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": r["hbm_frac"], "traffic": None,
+                     "note": "algorithmic bytes 2*p*p*B per call over the event-timed region "
+                             f"({launches} launch(es) per call, gaps included)"},
+    }
+    del d_recv
+
+    # ---- context: other configs, other schedules, memcpy ceiling
+    if not args.skip_context:
+        per = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4", "cfg5"):
+            wc = workloads.WORKLOADS[name]
+            pc, Bc = wc.p, wc.block_bytes
+            s_ = d_send if name == w.name else make_device_send(torch, wc, dev)
+            r_ = torch.full((pc, pc, Bc), workloads.POISON, dtype=torch.uint8, device=dev)
+            row = {"p": pc, "block_bytes": Bc}
+            algos = [("sparbit", sb.SPARBIT), ("direct", sb.DIRECT)]
+            if name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+                algos += [("bruck", sb.BRUCK)]
+                if pc & (pc - 1) == 0:
+                    algos += [("recursive_doubling", sb.RECURSIVE_DOUBLING)]
+            if name in ("cfg1", "cfg2", "cfg3"):
+                algos += [("ring", sb.RING)]
+            for label, algo in algos:
+                fn = lambda a=algo: sb.sparbit_allgather_mode(s_, r_, pc, Bc, a, sb.MODE_AUTO, stream)
+                t = time_calls(torch, fn, stream, 5, 20)
+                row[label] = {**t, **rates(pc, Bc, t["avg_ms"])}
+                good = bool(torch.equal(r_[pc - 1], s_))
+                row[label]["ok"] = good
+                r_.fill_(workloads.POISON)
+            # ceiling: one device-to-device memcpy of the same p*p*B bytes
+            dst = torch.empty_like(r_)
+            t = time_calls(torch, lambda: dst.copy_(r_, non_blocking=True), stream, 3, 10)
+            row["memcpy_d2d"] = {**t, **rates(pc, Bc, t["avg_ms"])}
+            per[name] = row
+            del r_, dst, s_
+            torch.cuda.empty_cache()
+        out["per_config"] = per
+        assert sb.sparbit_barrier_timeouts(stream) == 0
+
+    if not args.skip_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    sb.sparbit_finalize()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,149 @@
+/*
+ * sparbit.h -- C ABI of the Sparbit Allgather hot path for one MI355X (gfx950).
+ *
+ * The library executes Allgather exchange schedules for p *virtual* ranks
+ * whose send and receive buffers all live in one GPU's HBM.  A point-to-point
+ * message of the paper (one Isend matched with one Irecv of one block) becomes
+ * one block_bytes-sized device copy; the per-step Waitall becomes a kernel
+ * boundary or a device-wide barrier inside one persistent kernel.
+ *
+ * Buffer layout (all pointers are DEVICE pointers, owned by the caller, never
+ * retained or freed by the library):
+ *   sendbufs  p blocks; rank r's block at byte offset r * block_bytes.
+ *   recvbufs  p * p blocks; rank r's receive buffer at byte r * p * block_bytes,
+ *             its slot k at + k * block_bytes.  On return (after the stream has
+ *             drained) slot k of every rank holds rank k's block: the
+ *             MPI_Allgather post-condition of Section II of the paper.
+ *   Blocks are opaque bytes; the MPI (count, datatype) pair collapses into
+ *   block_bytes.  Any block_bytes is accepted; copies use 16-byte
+ *   accesses when both base pointers and block_bytes are multiples of 16,
+ *   4-byte accesses when they are multiples of 4, single bytes otherwise.
+ *
+ * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
+ * never throws.  Work is enqueued on the caller's stream; the call returns
+ * without synchronising (the first call for a given (schedule, p) on a device
+ * builds and uploads its tables and does synchronise).
+ */
+#ifndef SPARBIT_H
+#define SPARBIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes ------------------------------------------------------- */
+#define SPARBIT_OK 0
+#define SPARBIT_ERR_ARG (-1)         /* p < 1, p > SPARBIT_MAX_P, NULL recvbufs, size overflow, bad step range, bad enum */
+#define SPARBIT_ERR_ALIAS (-2)       /* sendbufs range overlaps recvbufs range (MPI forbids it; use NULL for in-place) */
+#define SPARBIT_ERR_UNSUPPORTED (-3) /* Recursive Doubling with p not a power of two; Bruck in place */
+#define SPARBIT_ERR_HIP (-4)         /* a HIP call failed; see sparbit_last_hip_error() */
+#define SPARBIT_ERR_NOMEM (-5)       /* host allocation failed */
+
+#define SPARBIT_MAX_P 4096 /* the tables hold p * (p - 1) entries of 8 bytes */
+
+/* ---- schedules (Section II-A and Section III of the paper) --------------- */
+#define SPARBIT_ALGO_SPARBIT 0            /* Algorithm 1: distance halves, data doubles */
+#define SPARBIT_ALGO_RING 1               /* p - 1 steps of one block to rank + 1 */
+#define SPARBIT_ALGO_RECURSIVE_DOUBLING 2 /* log2 p pairwise steps, p a power of two */
+#define SPARBIT_ALGO_BRUCK 3              /* distance doubles, rotated working buffer + final shift */
+#define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
+
+/* ---- how the steps of one call are issued -------------------------------- */
+#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes */
+#define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
+#define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
+
+/*
+ * MPI_Allgather over p virtual ranks with the Sparbit schedule (Algorithm 1 of
+ * the paper: ceil(log2 p) dependent steps; in the step with distance d rank r
+ * forwards the blocks in slots (r - 2 j d) mod p, j < data - ignore, to rank
+ * (r + d) mod p, where they land in the same slots).
+ *   sendbufs    device, p * block_bytes bytes; NULL = in place (as MPI_IN_PLACE:
+ *               recvbufs slot r of rank r already holds rank r's block).
+ *   recvbufs    device, p * p * block_bytes bytes.
+ *   stream      a hipStream_t (NULL = the null stream).
+ * p = 1 is legal (no steps, the own block is placed).  block_bytes = 0 is legal
+ * and does nothing (MPI allows a zero count).
+ */
+int sparbit_allgather(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
+                      void *stream);
+
+/* Same call with the schedule chosen by `algo` (Section II-A schedules run
+ * through the same kernels, for comparison). */
+int sparbit_allgather_algo(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
+                           int algo, void *stream);
+
+/* Same call with the schedule and the issue mode chosen explicitly. */
+int sparbit_allgather_mode(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
+                           int algo, int mode, void *stream);
+
+/*
+ * Run only steps first_step .. last_step (inclusive) of a schedule, one launch
+ * per step: the state after each Waitall of Algorithm 1 can be inspected.
+ * first_step = -1 also places the own blocks (ignored when sendbufs is NULL);
+ * steps are numbered 0 .. num_steps - 1; last_step = -1 with first_step = -1
+ * places the own blocks only.  Bruck keeps its rotated working buffer inside
+ * the library, so for Bruck only the full range (-1 .. num_steps - 1) is
+ * accepted.  DIRECT has no steps: only the range -1 .. -1.
+ */
+int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
+                            int algo, int first_step, int last_step, void *stream);
+
+/* ---- schedule builder (host only; no GPU needed) -------------------------- */
+typedef struct sparbit_plan sparbit_plan_t;
+
+typedef struct {
+    int distance;             /* d of Algorithm 1; 1 for Ring; 2^s for Recursive Doubling and Bruck */
+    int nblocks;              /* blocks every rank sends (and receives) in this step: data - ignore */
+    int ignore;               /* 1 if Algorithm 1 drops its last stripe on this step, else 0 */
+    const int32_t *dst;       /* [p] rank that r sends to */
+    const int32_t *src;       /* [p] rank that r receives from */
+    const int32_t *send_slot; /* [p * nblocks], row r: slots of r's buffer it sends, in posting order j */
+    const int32_t *recv_slot; /* [p * nblocks], row r: slot of r's buffer where the j-th block from src[r] lands */
+} sparbit_step_t;
+
+/* Build the tables of `algo` for p ranks.  *out is owned by the caller until
+ * sparbit_plan_destroy.  For Bruck the slots are those of the rotated working
+ * buffer (working slot i of rank r holds block (r + i) mod p). */
+int sparbit_plan_create(int p, int algo, sparbit_plan_t **out);
+/* ceil(log2 p) for Sparbit and Bruck, p - 1 for Ring, log2 p for Recursive
+ * Doubling, 0 for DIRECT; negative error code for a NULL plan. */
+int sparbit_plan_num_steps(const sparbit_plan_t *plan);
+/* Fill *out with pointers into the plan (valid until the plan is destroyed). */
+int sparbit_plan_step(const sparbit_plan_t *plan, int step, sparbit_step_t *out);
+void sparbit_plan_destroy(sparbit_plan_t *plan);
+
+/* ---- housekeeping --------------------------------------------------------- */
+/* Frees the per-device table caches and Bruck's working buffer.  The caller
+ * must have synchronised every stream that still runs library work. */
+void sparbit_finalize(void);
+const char *sparbit_strerror(int code);
+/* hipError_t value of the last failed HIP call on this thread (0 if none). */
+int sparbit_last_hip_error(void);
+/*
+ * The persistent kernel's barrier waits are bounded (so that a grid that was
+ * not co-resident ends instead of hanging); a launch whose wait expired leaves
+ * wrong results and bumps a per-stream counter.  This call synchronises
+ * `stream` and stores that counter in *count (0 = every launch completed).
+ */
+int sparbit_barrier_timeouts(void *stream, uint64_t *count);
+/*
+ * Tuning knobs for experiments (process-wide; unknown keys or out-of-range
+ * values return SPARBIT_ERR_ARG):
+ *   "tile_bytes"           bytes a workgroup moves per loop trip: 4096, 8192, 16384 or 32768
+ *   "chunk_bytes"          contiguous bytes one workgroup owns (multiple of 4096, >= tile_bytes)
+ *   "flat_below_bytes"     blocks smaller than this use the flattened small-block kernel
+ *   "persistent_max_bytes" AUTO uses the persistent kernel when p*p*block_bytes is at most this
+ *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
+ *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
+ *   "spin_limit_ms"        bound of one barrier wait of the persistent kernel
+ */
+int sparbit_tune(const char *key, long long value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARBIT_H */

@@ -92,6 +92,8 @@ typedef struct {
     int *nsends, *nrecvs;
     int cap;
     int step;
+    uint8_t *mailbox; /* payload staging of the current step, grown on demand */
+    size_t mailbox_cap;
     /* optional trace, rows of 5 int32: step, src, dst, src_slot, dst_slot */
     int32_t *trace;
     size_t trace_cap, trace_len;
@@ -155,7 +157,13 @@ static int waitall(sim_t *s, int require_same_slot)
                 return ORACLE_ERR_UNMATCHED;
         return ORACLE_OK;
     }
-    uint8_t *mailbox = (uint8_t *)malloc(total * B);
+    uint8_t *mailbox;
+    if (s->mailbox_cap < total * B) {
+        free(s->mailbox);
+        s->mailbox = (uint8_t *)malloc(total * B);
+        s->mailbox_cap = s->mailbox ? total * B : 0;
+    }
+    mailbox = s->mailbox;
     size_t *base = (size_t *)malloc((size_t)p * sizeof(size_t));
     uint8_t *consumed = (uint8_t *)calloc(total, 1);
     int *cursor = (int *)calloc((size_t)p, sizeof(int));
@@ -239,7 +247,6 @@ static int waitall(sim_t *s, int require_same_slot)
             }
     }
 out:
-    free(mailbox);
     free(base);
     free(consumed);
     free(cursor);
@@ -470,6 +477,7 @@ int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, in
 out:
     if (trace_len)
         *trace_len = s.trace_len;
+    free(s.mailbox);
     free(s.written);
     free(s.sent_now);
     free(s.sends);

@@ -12,6 +12,7 @@ _BINDING_NAMES = {
     "SparbitError", "Plan", "lib", "lib_path",
     "sparbit_allgather", "sparbit_allgather_algo", "sparbit_allgather_steps",
     "sparbit_allgather_mode", "sparbit_finalize", "sparbit_strerror",
+    "sparbit_tune", "sparbit_barrier_timeouts", "ALGOS",
 }
 
 

@@ -1,0 +1,457 @@
+// C-ABI of the library: argument checks, per-device caches of the schedule
+// tables, and the launches.  See include/sparbit.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <atomic>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "../../include/sparbit.h"
+#include "kernels.hip.hpp"
+#include "plan.hpp"
+
+namespace sparbit {
+namespace {
+
+thread_local int tl_last_hip_error = 0;
+
+#define SB_HIP(expr)                                    \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) {                         \
+            tl_last_hip_error = int(e_);                \
+            (void)hipGetLastError();                    \
+            return SPARBIT_ERR_HIP;                     \
+        }                                               \
+    } while (0)
+
+// ---- tuning knobs ----------------------------------------------------------
+std::atomic<long long> g_tile_bytes{16384};                   // per workgroup per loop trip
+std::atomic<long long> g_chunk_bytes{65536};                  // per workgroup in total
+std::atomic<long long> g_persistent_max_bytes{512ll << 20};   // AUTO threshold on p*p*B
+std::atomic<long long> g_nontemporal{0};
+std::atomic<long long> g_wgs_per_cu{4};
+std::atomic<long long> g_spin_limit_ms{2000};
+std::atomic<long long> g_flat_below_bytes{4096};              // blocks smaller than this use the flat kernel
+
+struct DevicePlan {
+    Plan host;
+    Copy* d_copies = nullptr;
+    DevPhase* d_phases = nullptr;          // phases of an out-of-place call
+    DevPhase* d_phases_in_place = nullptr; // phases of an in-place call
+    std::vector<uint32_t> first_copy;      // per host phase
+    std::vector<DevPhase> out_of_place, in_place;
+};
+
+struct DeviceState {
+    int device = -1;
+    int num_cus = 0;
+    std::map<std::pair<int, int>, std::unique_ptr<DevicePlan>> plans;  // (algo, p)
+    std::map<hipStream_t, BarrierState*> barriers;
+    void* work = nullptr;  // Bruck's rotated working buffer
+    size_t work_bytes = 0;
+};
+
+std::mutex g_mutex;
+std::map<int, std::unique_ptr<DeviceState>> g_devices;
+
+int get_device_state(DeviceState** out)
+{
+    int dev = 0;
+    SB_HIP(hipGetDevice(&dev));
+    auto it = g_devices.find(dev);
+    if (it == g_devices.end()) {
+        auto st = std::make_unique<DeviceState>();
+        st->device = dev;
+        hipDeviceProp_t prop;
+        SB_HIP(hipGetDeviceProperties(&prop, dev));
+        st->num_cus = prop.multiProcessorCount;
+        it = g_devices.emplace(dev, std::move(st)).first;
+    }
+    *out = it->second.get();
+    return SPARBIT_OK;
+}
+
+int get_plan(DeviceState* ds, int algo, int p, DevicePlan** out)
+{
+    auto key = std::make_pair(algo, p);
+    auto it = ds->plans.find(key);
+    if (it != ds->plans.end()) {
+        *out = it->second.get();
+        return SPARBIT_OK;
+    }
+    auto dp = std::make_unique<DevicePlan>();
+    int rc = build_plan(p, algo, dp->host);
+    if (rc != SPARBIT_OK) return rc;
+    std::vector<Copy> all;
+    for (const Phase& ph : dp->host.phases) {
+        dp->first_copy.push_back(uint32_t(all.size()));
+        all.insert(all.end(), ph.copies.begin(), ph.copies.end());
+        DevPhase d{dp->first_copy.back(), uint32_t(ph.copies.size()), int32_t(ph.src_buf), int32_t(ph.dst_buf)};
+        if (d.ncopies == 0) continue;
+        if (!ph.only_in_place) dp->out_of_place.push_back(d);
+        if (!ph.skip_in_place) dp->in_place.push_back(d);
+    }
+    if (!all.empty()) {
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&dp->d_copies), all.size() * sizeof(Copy)));
+        SB_HIP(hipMemcpy(dp->d_copies, all.data(), all.size() * sizeof(Copy), hipMemcpyHostToDevice));
+    }
+    auto upload = [](const std::vector<DevPhase>& v, DevPhase** d) -> int {
+        if (v.empty()) return SPARBIT_OK;
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(d), v.size() * sizeof(DevPhase)));
+        SB_HIP(hipMemcpy(*d, v.data(), v.size() * sizeof(DevPhase), hipMemcpyHostToDevice));
+        return SPARBIT_OK;
+    };
+    if ((rc = upload(dp->out_of_place, &dp->d_phases)) != SPARBIT_OK) return rc;
+    if ((rc = upload(dp->in_place, &dp->d_phases_in_place)) != SPARBIT_OK) return rc;
+    *out = dp.get();
+    ds->plans.emplace(key, std::move(dp));
+    return SPARBIT_OK;
+}
+
+int get_barrier(DeviceState* ds, hipStream_t stream, BarrierState** out)
+{
+    auto it = ds->barriers.find(stream);
+    if (it == ds->barriers.end()) {
+        BarrierState* b = nullptr;
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&b), sizeof(BarrierState)));
+        SB_HIP(hipMemset(b, 0, sizeof(BarrierState)));
+        SB_HIP(hipDeviceSynchronize());
+        it = ds->barriers.emplace(stream, b).first;
+    }
+    *out = it->second;
+    return SPARBIT_OK;
+}
+
+int get_work(DeviceState* ds, size_t bytes, void** out)
+{
+    if (ds->work_bytes < bytes) {
+        if (ds->work) {
+            SB_HIP(hipDeviceSynchronize());
+            SB_HIP(hipFree(ds->work));
+            ds->work = nullptr;
+            ds->work_bytes = 0;
+        }
+        SB_HIP(hipMalloc(&ds->work, bytes));
+        ds->work_bytes = bytes;
+    }
+    *out = ds->work;
+    return SPARBIT_OK;
+}
+
+// Widest access the pointers and the block size allow.
+int access_width(const void* a, const void* b, const void* c, size_t block_bytes)
+{
+    uintptr_t bits = uintptr_t(a) | uintptr_t(b) | uintptr_t(c) | uintptr_t(block_bytes);
+    if ((bits & 15) == 0) return 16;
+    if ((bits & 3) == 0) return 4;
+    return 1;
+}
+
+template <typename V, typename Index>
+int launch_flat_t(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B,
+                  bool nt, hipStream_t stream)
+{
+    constexpr int U = 4;
+    const uint64_t vpb = B / sizeof(V);
+    const uint64_t total = vpb * ncopies;
+    const uint64_t ntiles = (total + WG * U - 1) / (WG * U);
+    if (ntiles > 0x7fffffffull) return SPARBIT_ERR_ARG;
+    if (nt)
+        hipLaunchKernelGGL((copy_flat_kernel<V, Index, U, true>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
+                           dst, copies, uint64_t(B), Index(vpb), Index(total));
+    else
+        hipLaunchKernelGGL((copy_flat_kernel<V, Index, U, false>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
+                           dst, copies, uint64_t(B), Index(vpb), Index(total));
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+template <typename V>
+int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                hipStream_t stream)
+{
+    const uint64_t total = (B / sizeof(V)) * uint64_t(ncopies);
+    if (total + WG * 8 <= 0xffffffffull) return launch_flat_t<V, uint32_t>(src, dst, copies, ncopies, B, nt, stream);
+    return launch_flat_t<V, uint64_t>(src, dst, copies, ncopies, B, nt, stream);
+}
+
+template <int U>
+int launch_chunks_u(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                    uint32_t chunks_per_block, uint32_t chunk_vecs, hipStream_t stream)
+{
+    const uint64_t grid = uint64_t(ncopies) * chunks_per_block;
+    if (grid > 0x7fffffffull) return SPARBIT_ERR_ARG;
+    if (nt)
+        hipLaunchKernelGGL((copy_chunks_kernel<U, true>), dim3(uint32_t(grid)), dim3(WG), 0, stream, src, dst, copies,
+                           uint64_t(B), chunks_per_block, chunk_vecs);
+    else
+        hipLaunchKernelGGL((copy_chunks_kernel<U, false>), dim3(uint32_t(grid)), dim3(WG), 0, stream, src, dst, copies,
+                           uint64_t(B), chunks_per_block, chunk_vecs);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+// One phase as one launch.
+int launch_phase(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, int width,
+                 hipStream_t stream)
+{
+    if (ncopies == 0) return SPARBIT_OK;
+    const bool nt = g_nontemporal.load() != 0;
+    if (width == 16 && B >= size_t(g_flat_below_bytes.load()) && (B >> 4) <= 0x7fffffffull) {
+        const long long tile = g_tile_bytes.load();
+        long long chunk = g_chunk_bytes.load();
+        if (chunk < tile) chunk = tile;
+        const uint64_t vpb = B >> 4;
+        const uint64_t chunk_vecs = uint64_t(chunk) >> 4;
+        const uint64_t cpb = (vpb + chunk_vecs - 1) / chunk_vecs;
+        if (cpb <= 0xffffffffull) {
+            switch (tile) {
+            case 4096: return launch_chunks_u<1>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
+            case 8192: return launch_chunks_u<2>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
+            case 32768: return launch_chunks_u<8>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
+            default: return launch_chunks_u<4>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
+            }
+        }
+    }
+    switch (width) {
+    case 16: return launch_flat<u32x4>(src, dst, copies, ncopies, B, nt, stream);
+    case 4: return launch_flat<uint32_t>(src, dst, copies, ncopies, B, nt, stream);
+    default: return launch_flat<uint8_t>(src, dst, copies, ncopies, B, nt, stream);
+    }
+}
+
+template <typename V>
+int launch_persistent_v(const PersistentArgs& a, int num_cus, uint64_t max_tiles, hipStream_t stream)
+{
+    constexpr int U = 4;
+    const bool nt = g_nontemporal.load() != 0;
+    int per_cu = 0;
+    if (nt)
+        SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_kernel<V, U, true>, WG, 0));
+    else
+        SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_kernel<V, U, false>, WG, 0));
+    long long want = g_wgs_per_cu.load();
+    if (want < 1) want = 1;
+    if (per_cu < 1) return SPARBIT_ERR_HIP;
+    if (want > per_cu) want = per_cu;
+    uint64_t grid = uint64_t(num_cus) * uint64_t(want);
+    if (grid > max_tiles) grid = max_tiles ? max_tiles : 1;  // no more workgroups than the largest phase has tiles
+    if (nt)
+        hipLaunchKernelGGL((persistent_kernel<V, U, true>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    else
+        hipLaunchKernelGGL((persistent_kernel<V, U, false>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb)
+{
+    const uintptr_t a0 = uintptr_t(a), b0 = uintptr_t(b);
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// first_step / last_step as in sparbit_allgather_steps; `whole` = full call.
+int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mode, bool whole, int first_step,
+        int last_step, void* stream_v)
+{
+    if (p < 1 || p > SPARBIT_MAX_P || !recvbufs) return SPARBIT_ERR_ARG;
+    if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
+    if (mode < SPARBIT_MODE_AUTO || mode > SPARBIT_MODE_PERSISTENT) return SPARBIT_ERR_ARG;
+    const unsigned __int128 total128 = (unsigned __int128)(uint64_t(p) * uint64_t(p)) * B;
+    if (total128 > (unsigned __int128)0x7fffffffffffffffull) return SPARBIT_ERR_ARG;
+    const size_t recv_bytes = size_t(p) * size_t(p) * B;
+    const bool in_place = sendbufs == nullptr;
+    if (!in_place && ranges_overlap(sendbufs, size_t(p) * B, recvbufs, recv_bytes)) return SPARBIT_ERR_ALIAS;
+    if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING && (p & (p - 1))) return SPARBIT_ERR_UNSUPPORTED;
+    if (algo == SPARBIT_ALGO_BRUCK && in_place) return SPARBIT_ERR_UNSUPPORTED;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (B == 0) {  // zero-size blocks: only the step range is still validated
+        if (!whole) {
+            const int nsteps = (algo == SPARBIT_ALGO_RING) ? p - 1 : (algo == SPARBIT_ALGO_DIRECT) ? 0 : ceil_log2(p);
+            if (first_step < -1 || last_step < -1 || first_step > last_step || last_step >= nsteps) return SPARBIT_ERR_ARG;
+        }
+        return SPARBIT_OK;
+    }
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* ds = nullptr;
+    int rc = get_device_state(&ds);
+    if (rc != SPARBIT_OK) return rc;
+    DevicePlan* dp = nullptr;
+    if ((rc = get_plan(ds, algo, p, &dp)) != SPARBIT_OK) return rc;
+    const int nsteps = int(dp->host.steps.size());
+    if (!whole) {
+        if (first_step < -1 || last_step < -1 || first_step > last_step || last_step >= nsteps) return SPARBIT_ERR_ARG;
+        if (algo == SPARBIT_ALGO_BRUCK && !(first_step == -1 && last_step == nsteps - 1)) return SPARBIT_ERR_ARG;
+    } else {
+        first_step = -1;
+        last_step = nsteps - 1;
+    }
+
+    void* work = nullptr;
+    if (algo == SPARBIT_ALGO_BRUCK && (rc = get_work(ds, recv_bytes, &work)) != SPARBIT_OK) return rc;
+    const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs),
+                              static_cast<const uint8_t*>(work)};
+    const int width = access_width(sendbufs, recvbufs, work, B);
+
+    if (mode == SPARBIT_MODE_AUTO)
+        mode = (recv_bytes <= size_t(g_persistent_max_bytes.load())) ? SPARBIT_MODE_PERSISTENT : SPARBIT_MODE_PER_STEP;
+    const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
+
+    if (whole && mode == SPARBIT_MODE_PERSISTENT && !phases.empty()) {
+        PersistentArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.base[0] = base[0];
+        a.base[1] = base[1];
+        a.base[2] = base[2];
+        a.copies = dp->d_copies;
+        a.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
+        a.block_bytes = B;
+        a.nphases = uint32_t(phases.size());
+        a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;  // 100 MHz counter
+        if ((rc = get_barrier(ds, stream, &a.bar)) != SPARBIT_OK) return rc;
+        uint64_t max_tiles = 1;
+        for (const DevPhase& ph : phases) {
+            const uint64_t t = ((B / size_t(width)) * ph.ncopies + WG * 4 - 1) / (WG * 4);
+            if (t > max_tiles) max_tiles = t;
+        }
+        switch (width) {
+        case 16: return launch_persistent_v<u32x4>(a, ds->num_cus, max_tiles, stream);
+        case 4: return launch_persistent_v<uint32_t>(a, ds->num_cus, max_tiles, stream);
+        default: return launch_persistent_v<uint8_t>(a, ds->num_cus, max_tiles, stream);
+        }
+    }
+
+    // One launch per phase; stream order is the Waitall.
+    for (size_t i = 0; i < dp->host.phases.size(); ++i) {
+        const Phase& ph = dp->host.phases[i];
+        if (in_place ? ph.skip_in_place : ph.only_in_place) continue;
+        const int step = (ph.step >= nsteps) ? nsteps - 1 : ph.step;  // Bruck's rotation rides with the last step
+        if (step < first_step || step > last_step) continue;
+        rc = launch_phase(base[ph.src_buf], const_cast<uint8_t*>(base[ph.dst_buf]), dp->d_copies + dp->first_copy[i],
+                          uint32_t(ph.copies.size()), B, width, stream);
+        if (rc != SPARBIT_OK) return rc;
+    }
+    return SPARBIT_OK;
+}
+
+}  // namespace
+}  // namespace sparbit
+
+extern "C" {
+
+int sparbit_allgather(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, void* stream)
+{
+    return sparbit::run(sendbufs, recvbufs, p, block_bytes, SPARBIT_ALGO_SPARBIT, SPARBIT_MODE_AUTO, true, 0, 0,
+                        stream);
+}
+
+int sparbit_allgather_algo(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, void* stream)
+{
+    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_AUTO, true, 0, 0, stream);
+}
+
+int sparbit_allgather_mode(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, int mode,
+                           void* stream)
+{
+    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, mode, true, 0, 0, stream);
+}
+
+int sparbit_allgather_steps(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, int first_step,
+                            int last_step, void* stream)
+{
+    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_PER_STEP, false, first_step, last_step,
+                        stream);
+}
+
+void sparbit_finalize(void)
+{
+    std::lock_guard<std::mutex> lock(sparbit::g_mutex);
+    int current = 0;
+    const bool have_dev = hipGetDevice(&current) == hipSuccess;
+    for (auto& kv : sparbit::g_devices) {
+        sparbit::DeviceState* ds = kv.second.get();
+        if (hipSetDevice(ds->device) != hipSuccess) continue;
+        for (auto& pk : ds->plans) {
+            (void)hipFree(pk.second->d_copies);
+            (void)hipFree(pk.second->d_phases);
+            (void)hipFree(pk.second->d_phases_in_place);
+        }
+        for (auto& bk : ds->barriers) (void)hipFree(bk.second);
+        if (ds->work) (void)hipFree(ds->work);
+    }
+    sparbit::g_devices.clear();
+    if (have_dev) (void)hipSetDevice(current);
+}
+
+const char* sparbit_strerror(int code)
+{
+    switch (code) {
+    case SPARBIT_OK: return "success";
+    case SPARBIT_ERR_ARG: return "invalid argument";
+    case SPARBIT_ERR_ALIAS: return "send and receive buffers overlap (pass NULL sendbufs for in-place)";
+    case SPARBIT_ERR_UNSUPPORTED: return "schedule does not support this call";
+    case SPARBIT_ERR_HIP: return "HIP runtime error";
+    case SPARBIT_ERR_NOMEM: return "out of host memory";
+    default: return "unknown error";
+    }
+}
+
+int sparbit_last_hip_error(void) { return sparbit::tl_last_hip_error; }
+
+int sparbit_barrier_timeouts(void* stream_v, uint64_t* count)
+{
+    using namespace sparbit;
+    if (!count) return SPARBIT_ERR_ARG;
+    *count = 0;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* ds = nullptr;
+    int rc = get_device_state(&ds);
+    if (rc != SPARBIT_OK) return rc;
+    SB_HIP(hipStreamSynchronize(stream));
+    auto it = ds->barriers.find(stream);
+    if (it == ds->barriers.end()) return SPARBIT_OK;  // no persistent launch on this stream yet
+    BarrierState host;
+    SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
+    *count = host.errors;
+    return SPARBIT_OK;
+}
+
+int sparbit_tune(const char* key, long long value)
+{
+    using namespace sparbit;
+    if (!key) return SPARBIT_ERR_ARG;
+    if (!std::strcmp(key, "tile_bytes")) {
+        if (value != 4096 && value != 8192 && value != 16384 && value != 32768) return SPARBIT_ERR_ARG;
+        g_tile_bytes = value;
+    } else if (!std::strcmp(key, "chunk_bytes")) {
+        if (value < 4096 || (value & 4095)) return SPARBIT_ERR_ARG;
+        g_chunk_bytes = value;
+    } else if (!std::strcmp(key, "persistent_max_bytes")) {
+        if (value < 0) return SPARBIT_ERR_ARG;
+        g_persistent_max_bytes = value;
+    } else if (!std::strcmp(key, "nontemporal")) {
+        g_nontemporal = value ? 1 : 0;
+    } else if (!std::strcmp(key, "wgs_per_cu")) {
+        if (value < 1 || value > 16) return SPARBIT_ERR_ARG;
+        g_wgs_per_cu = value;
+    } else if (!std::strcmp(key, "spin_limit_ms")) {
+        if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;
+        g_spin_limit_ms = value;
+    } else if (!std::strcmp(key, "flat_below_bytes")) {
+        if (value < 16) return SPARBIT_ERR_ARG;
+        g_flat_below_bytes = value;
+    } else {
+        return SPARBIT_ERR_ARG;
+    }
+    return SPARBIT_OK;
+}
+
+}  // extern "C"

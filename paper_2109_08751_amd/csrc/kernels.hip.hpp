@@ -1,0 +1,214 @@
+// gfx950 copy kernels: every phase of a schedule is a batch of independent
+// block copies  dst_base[dst_block * B ..] <- src_base[src_block * B ..].
+// Nothing here is a contraction: the kernels are plain HBM streams built from
+// 16-byte (or 4- / 1-byte) global loads and stores, several in flight per lane.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "plan.hpp"
+
+namespace sparbit {
+
+constexpr int WG = 256;  // 4 wavefronts of 64 lanes
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <typename V, bool NT>
+__device__ __forceinline__ V ld(const V* p)
+{
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <typename V, bool NT>
+__device__ __forceinline__ void st(V* p, V v)
+{
+    if constexpr (NT)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+// ---------------------------------------------------------------------------
+// Large blocks (B a multiple of 16, pointers 16-aligned).  One workgroup owns
+// one contiguous chunk of one block copy, so the table entry, both base
+// addresses and the bounds are wave-uniform (scalar registers); lanes only add
+// their own offset.  Consecutive workgroups take consecutive chunks of the
+// same block, so at any moment the resident workgroups cover a few long
+// contiguous address runs.  Each trip issues UNROLL 16-byte loads per lane
+// before the first store.
+// ---------------------------------------------------------------------------
+template <int UNROLL, bool NT>
+__global__ __launch_bounds__(WG) void copy_chunks_kernel(const uint8_t* __restrict__ src_base,
+                                                         uint8_t* __restrict__ dst_base,
+                                                         const Copy* __restrict__ copies,
+                                                         uint64_t block_bytes,
+                                                         uint32_t chunks_per_block,
+                                                         uint32_t chunk_vecs)
+{
+    const uint32_t c = blockIdx.x / chunks_per_block;
+    const uint32_t q = blockIdx.x - c * chunks_per_block;
+    const Copy cp = copies[c];
+    const u32x4* __restrict__ s = reinterpret_cast<const u32x4*>(src_base + uint64_t(cp.src_block) * block_bytes);
+    u32x4* __restrict__ d = reinterpret_cast<u32x4*>(dst_base + uint64_t(cp.dst_block) * block_bytes);
+    const uint32_t vpb = uint32_t(block_bytes >> 4);
+    const uint32_t v0 = q * chunk_vecs;
+    const uint32_t v1 = (vpb - v0 < chunk_vecs) ? vpb : v0 + chunk_vecs;
+
+    for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * UNROLL) {
+        u32x4 x[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = v + u * WG;
+            if (i < v1) x[u] = ld<u32x4, NT>(s + i);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const uint32_t i = v + u * WG;
+            if (i < v1) st<u32x4, NT>(d + i, x[u]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Small or odd-sized blocks: the (copy, element) space is flattened and every
+// lane finds its copy by one division, so a workgroup's tile may span many
+// short blocks.  V is the access width the alignment allows.
+// ---------------------------------------------------------------------------
+template <typename V, typename Index, int UNROLL, bool NT>
+__device__ __forceinline__ void copy_flat_tile(const uint8_t* __restrict__ src_base,
+                                               uint8_t* __restrict__ dst_base,
+                                               const Copy* __restrict__ copies, uint64_t block_bytes,
+                                               Index vpb, Index total, Index tile)
+{
+    V x[UNROLL];
+    const V* sp[UNROLL];
+    V* dp[UNROLL];
+    bool ok[UNROLL];
+    const Index g0 = tile * Index(WG * UNROLL) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+        const Index g = g0 + Index(u * WG);
+        ok[u] = g < total;
+        if (ok[u]) {
+            const Index c = g / vpb;
+            const Index o = g - c * vpb;
+            const Copy cp = copies[c];
+            sp[u] = reinterpret_cast<const V*>(src_base + uint64_t(cp.src_block) * block_bytes) + o;
+            dp[u] = reinterpret_cast<V*>(dst_base + uint64_t(cp.dst_block) * block_bytes) + o;
+            x[u] = ld<V, NT>(sp[u]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+        if (ok[u]) st<V, NT>(dp[u], x[u]);
+}
+
+template <typename V, typename Index, int UNROLL, bool NT>
+__global__ __launch_bounds__(WG) void copy_flat_kernel(const uint8_t* __restrict__ src_base,
+                                                       uint8_t* __restrict__ dst_base,
+                                                       const Copy* __restrict__ copies,
+                                                       uint64_t block_bytes, Index vpb, Index total)
+{
+    copy_flat_tile<V, Index, UNROLL, NT>(src_base, dst_base, copies, block_bytes, vpb, total,
+                                         Index(blockIdx.x));
+}
+
+// ---------------------------------------------------------------------------
+// Persistent form: all phases of one call in one launch.  The Waitall between
+// steps is a device-wide barrier: thread 0 of every workgroup releases its
+// workgroup's stores at agent scope (write-back of this XCD's L2), counts in,
+// and acquires (invalidate) once all workgroups of the grid have arrived.  The
+// grid is sized by the host so that every workgroup is resident.
+// ---------------------------------------------------------------------------
+struct DevPhase {
+    uint32_t first_copy;  // offset into the plan's copy array
+    uint32_t ncopies;
+    int32_t src_buf;  // Buffer
+    int32_t dst_buf;
+};
+
+struct BarrierState {
+    uint32_t arrived;  // monotonic within a launch; reset by the last workgroup to leave
+    uint32_t left;
+    uint32_t abort;   // set when a bounded wait expired in this launch; reset like `arrived`
+    uint32_t errors;  // sticky count of launches that aborted (read by the host on request)
+};
+
+struct PersistentArgs {
+    const uint8_t* base[3];  // BUF_SEND, BUF_RECV, BUF_WORK (const cast away for dst)
+    const Copy* copies;
+    const DevPhase* phases;
+    BarrierState* bar;
+    uint64_t block_bytes;
+    uint64_t spin_limit_ticks;  // bounded wait, in 100 MHz wall-clock ticks
+    uint32_t nphases;
+};
+
+__device__ __forceinline__ bool grid_barrier(BarrierState* bar, uint32_t target, uint64_t limit)
+{
+    __shared__ uint32_t failed;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t f = 0;
+        __hip_atomic_fetch_add(&bar->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t t0 = wall_clock64();
+        while (__hip_atomic_load(&bar->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(2);
+            if (uint64_t(wall_clock64()) - t0 > limit ||
+                __hip_atomic_load(&bar->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                __hip_atomic_store(&bar->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                f = 1;
+                break;
+            }
+        }
+        failed = f;
+    }
+    __syncthreads();
+    return failed == 0;
+}
+
+template <typename V, int UNROLL, bool NT>
+__global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
+{
+    const uint32_t nwg = gridDim.x;
+    bool ok = true;
+    for (uint32_t ph = 0; ph < a.nphases && ok; ++ph) {
+        const DevPhase P = a.phases[ph];
+        const uint8_t* src = a.base[P.src_buf];
+        uint8_t* dst = const_cast<uint8_t*>(a.base[P.dst_buf]);
+        const uint64_t vpb = a.block_bytes / sizeof(V);
+        const uint64_t total = vpb * P.ncopies;
+        const uint64_t ntiles = (total + WG * UNROLL - 1) / (WG * UNROLL);
+        if (total + WG * UNROLL <= 0xffffffffull) {  // lane indices of the last tile stay below 2^32
+            for (uint32_t t = blockIdx.x; t < uint32_t(ntiles); t += nwg)
+                copy_flat_tile<V, uint32_t, UNROLL, NT>(src, dst, a.copies + P.first_copy, a.block_bytes,
+                                                        uint32_t(vpb), uint32_t(total), t);
+        } else {
+            for (uint64_t t = blockIdx.x; t < ntiles; t += nwg)
+                copy_flat_tile<V, uint64_t, UNROLL, NT>(src, dst, a.copies + P.first_copy, a.block_bytes,
+                                                        vpb, total, t);
+        }
+        if (ph + 1 < a.nphases) ok = grid_barrier(a.bar, (ph + 1) * nwg, a.spin_limit_ticks);
+    }
+    // Leave: the last workgroup out puts the counters back to zero for the next
+    // launch on this stream (nobody waits on `arrived` any more by then).
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t n = __hip_atomic_fetch_add(&a.bar->left, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        if (n == nwg - 1) {
+            if (__hip_atomic_load(&a.bar->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                __hip_atomic_fetch_add(&a.bar->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&a.bar->abort, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            __hip_atomic_store(&a.bar->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&a.bar->left, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+}  // namespace sparbit
