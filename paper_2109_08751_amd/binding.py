@@ -45,6 +45,14 @@ def lib_path() -> str:
 
 
 def _load() -> ctypes.CDLL:
+    # A process must hold ONE HIP runtime.  torch ships its own copy under the
+    # same soname; loading torch first makes the dynamic linker hand that copy
+    # to libsparbit.so too, so streams and device pointers mean the same thing
+    # on both sides.  Without torch the system runtime is used.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(_build.LIB_PATH):
         _build.build_library()  # raises if hipcc is missing: no silent fallback
     L = ctypes.CDLL(_build.LIB_PATH)

@@ -68,9 +68,10 @@ int get_device_state(DeviceState** out)
     if (it == g_devices.end()) {
         auto st = std::make_unique<DeviceState>();
         st->device = dev;
-        hipDeviceProp_t prop;
-        SB_HIP(hipGetDeviceProperties(&prop, dev));
-        st->num_cus = prop.multiProcessorCount;
+        // Attribute query, not hipGetDeviceProperties: the property struct's
+        // layout differs between HIP releases and the process may carry another
+        // runtime version than the headers this file was compiled with.
+        SB_HIP(hipDeviceGetAttribute(&st->num_cus, hipDeviceAttributeMultiprocessorCount, dev));
         it = g_devices.emplace(dev, std::move(st)).first;
     }
     *out = it->second.get();
