@@ -133,8 +133,9 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
 /*
  * Tuning knobs for experiments (process-wide; unknown keys or out-of-range
  * values return SPARBIT_ERR_ARG):
- *   "tile_bytes"           bytes a workgroup moves per loop trip: 4096, 8192, 16384 or 32768
- *   "chunk_bytes"          contiguous bytes one workgroup owns (multiple of 4096, >= tile_bytes)
+ *   "wg_threads"           lanes per workgroup of the large-block kernel: 64, 128, 256, 512, 1024
+ *   "unroll"               16-byte vectors each lane of that kernel moves: 1, 2 or 4
+ *   "interleave_log2"      log2 of the block copies dealt round-robin to consecutive workgroups (3 = one per XCD)
  *   "flat_below_bytes"     blocks smaller than this use the flattened small-block kernel
  *   "persistent_max_bytes" AUTO uses the persistent kernel when p*p*block_bytes is at most this
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint

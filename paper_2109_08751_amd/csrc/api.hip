@@ -31,10 +31,11 @@ thread_local int tl_last_hip_error = 0;
     } while (0)
 
 // ---- tuning knobs ----------------------------------------------------------
-std::atomic<long long> g_tile_bytes{16384};                   // per workgroup per loop trip
-std::atomic<long long> g_chunk_bytes{65536};                  // per workgroup in total
+std::atomic<long long> g_wg_threads{256};                     // lanes per workgroup of the tile kernel
+std::atomic<long long> g_unroll{1};                           // 16-byte vectors per lane of the tile kernel
+std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
 std::atomic<long long> g_persistent_max_bytes{512ll << 20};   // AUTO threshold on p*p*B
-std::atomic<long long> g_nontemporal{0};
+std::atomic<long long> g_nontemporal{1};
 std::atomic<long long> g_wgs_per_cu{4};
 std::atomic<long long> g_spin_limit_ms{2000};
 std::atomic<long long> g_flat_below_bytes{4096};              // blocks smaller than this use the flat kernel
@@ -182,20 +183,38 @@ int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t n
     return launch_flat_t<V, uint64_t>(src, dst, copies, ncopies, B, nt, stream);
 }
 
-template <int U>
-int launch_chunks_u(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
-                    uint32_t chunks_per_block, uint32_t chunk_vecs, hipStream_t stream)
+template <int T, int U>
+int launch_tiles_tu(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                    hipStream_t stream)
 {
-    const uint64_t grid = uint64_t(ncopies) * chunks_per_block;
-    if (grid > 0x7fffffffull) return SPARBIT_ERR_ARG;
+    const uint64_t vpb = B >> 4;
+    const uint64_t tiles = (vpb + T * U - 1) / (T * U);
+    uint32_t lg_g = uint32_t(g_interleave_log2.load());
+    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
+    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
+    const uint32_t gy = groups < 32768u ? groups : 32768u;
+    const uint32_t gz = (groups + gy - 1) / gy;
+    if ((tiles << lg_g) > 0x7fffffffull / T || gz > 65535u) return SPARBIT_ERR_ARG;
+    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
     if (nt)
-        hipLaunchKernelGGL((copy_chunks_kernel<U, true>), dim3(uint32_t(grid)), dim3(WG), 0, stream, src, dst, copies,
-                           uint64_t(B), chunks_per_block, chunk_vecs);
+        hipLaunchKernelGGL((copy_tiles_kernel<T, U, true>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
+                           uint64_t(B), lg_g);
     else
-        hipLaunchKernelGGL((copy_chunks_kernel<U, false>), dim3(uint32_t(grid)), dim3(WG), 0, stream, src, dst, copies,
-                           uint64_t(B), chunks_per_block, chunk_vecs);
+        hipLaunchKernelGGL((copy_tiles_kernel<T, U, false>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
+                           uint64_t(B), lg_g);
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
+}
+
+template <int T>
+int launch_tiles_t(int unroll, const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B,
+                   bool nt, hipStream_t stream)
+{
+    switch (unroll) {
+    case 4: return launch_tiles_tu<T, 4>(src, dst, copies, ncopies, B, nt, stream);
+    case 2: return launch_tiles_tu<T, 2>(src, dst, copies, ncopies, B, nt, stream);
+    default: return launch_tiles_tu<T, 1>(src, dst, copies, ncopies, B, nt, stream);
+    }
 }
 
 // One phase as one launch.
@@ -204,20 +223,14 @@ int launch_phase(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t 
 {
     if (ncopies == 0) return SPARBIT_OK;
     const bool nt = g_nontemporal.load() != 0;
-    if (width == 16 && B >= size_t(g_flat_below_bytes.load()) && (B >> 4) <= 0x7fffffffull) {
-        const long long tile = g_tile_bytes.load();
-        long long chunk = g_chunk_bytes.load();
-        if (chunk < tile) chunk = tile;
-        const uint64_t vpb = B >> 4;
-        const uint64_t chunk_vecs = uint64_t(chunk) >> 4;
-        const uint64_t cpb = (vpb + chunk_vecs - 1) / chunk_vecs;
-        if (cpb <= 0xffffffffull) {
-            switch (tile) {
-            case 4096: return launch_chunks_u<1>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
-            case 8192: return launch_chunks_u<2>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
-            case 32768: return launch_chunks_u<8>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
-            default: return launch_chunks_u<4>(src, dst, copies, ncopies, B, nt, uint32_t(cpb), uint32_t(chunk_vecs), stream);
-            }
+    if (width == 16 && B >= size_t(g_flat_below_bytes.load()) && (B >> 4) <= 0x3fffffffull) {
+        const int u = int(g_unroll.load());
+        switch (g_wg_threads.load()) {
+        case 64: return launch_tiles_t<64>(u, src, dst, copies, ncopies, B, nt, stream);
+        case 128: return launch_tiles_t<128>(u, src, dst, copies, ncopies, B, nt, stream);
+        case 512: return launch_tiles_t<512>(u, src, dst, copies, ncopies, B, nt, stream);
+        case 1024: return launch_tiles_t<1024>(u, src, dst, copies, ncopies, B, nt, stream);
+        default: return launch_tiles_t<256>(u, src, dst, copies, ncopies, B, nt, stream);
         }
     }
     switch (width) {
@@ -429,12 +442,15 @@ int sparbit_tune(const char* key, long long value)
 {
     using namespace sparbit;
     if (!key) return SPARBIT_ERR_ARG;
-    if (!std::strcmp(key, "tile_bytes")) {
-        if (value != 4096 && value != 8192 && value != 16384 && value != 32768) return SPARBIT_ERR_ARG;
-        g_tile_bytes = value;
-    } else if (!std::strcmp(key, "chunk_bytes")) {
-        if (value < 4096 || (value & 4095)) return SPARBIT_ERR_ARG;
-        g_chunk_bytes = value;
+    if (!std::strcmp(key, "wg_threads")) {
+        if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return SPARBIT_ERR_ARG;
+        g_wg_threads = value;
+    } else if (!std::strcmp(key, "interleave_log2")) {
+        if (value < 0 || value > 8) return SPARBIT_ERR_ARG;
+        g_interleave_log2 = value;
+    } else if (!std::strcmp(key, "unroll")) {
+        if (value != 1 && value != 2 && value != 4) return SPARBIT_ERR_ARG;
+        g_unroll = value;
     } else if (!std::strcmp(key, "persistent_max_bytes")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_persistent_max_bytes = value;

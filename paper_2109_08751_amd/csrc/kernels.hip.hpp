@@ -34,44 +34,42 @@ __device__ __forceinline__ void st(V* p, V v)
 }
 
 // ---------------------------------------------------------------------------
-// Large blocks (B a multiple of 16, pointers 16-aligned).  One workgroup owns
-// one contiguous chunk of one block copy, so the table entry, both base
-// addresses and the bounds are wave-uniform (scalar registers); lanes only add
-// their own offset.  Consecutive workgroups take consecutive chunks of the
-// same block, so at any moment the resident workgroups cover a few long
-// contiguous address runs.  Each trip issues UNROLL 16-byte loads per lane
-// before the first store.
+// Large blocks (B a multiple of 16, pointers 16-aligned).  One workgroup of T
+// lanes moves one tile of T * U 16-byte vectors of one block copy and exits:
+// no loop, and the table entry, both base addresses and the bound are
+// wave-uniform (scalar registers).  On MI355X the best rate comes from the
+// smallest footprint per wave (U = 1: one load and one store per lane) with
+// the parallelism left to the dispatcher.
+//
+// XCD-aware mapping.  The dispatcher deals consecutive workgroups round-robin
+// to the 8 XCDs, each with its own L2 and its own address-translation caches.
+// The copies of a phase are far apart (stripes of 1 block every 2d blocks), so
+// if the tiles of one block were dealt to all XCDs, every XCD would have to
+// translate every block's pages and would see only every 8th tile.  Instead
+// blockIdx.x interleaves G = 2^lg_g copies: copy = group * G + (x mod G),
+// tile = x / G.  With G = 8 each XCD streams one whole block by itself.
 // ---------------------------------------------------------------------------
-template <int UNROLL, bool NT>
-__global__ __launch_bounds__(WG) void copy_chunks_kernel(const uint8_t* __restrict__ src_base,
-                                                         uint8_t* __restrict__ dst_base,
-                                                         const Copy* __restrict__ copies,
-                                                         uint64_t block_bytes,
-                                                         uint32_t chunks_per_block,
-                                                         uint32_t chunk_vecs)
+template <int T, int U, bool NT>
+__global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict__ src_base,
+                                                       uint8_t* __restrict__ dst_base,
+                                                       const Copy* __restrict__ copies, uint32_t ncopies,
+                                                       uint64_t block_bytes, uint32_t lg_g)
 {
-    const uint32_t c = blockIdx.x / chunks_per_block;
-    const uint32_t q = blockIdx.x - c * chunks_per_block;
+    const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
+    const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
+    if (c >= ncopies) return;
     const Copy cp = copies[c];
     const u32x4* __restrict__ s = reinterpret_cast<const u32x4*>(src_base + uint64_t(cp.src_block) * block_bytes);
     u32x4* __restrict__ d = reinterpret_cast<u32x4*>(dst_base + uint64_t(cp.dst_block) * block_bytes);
     const uint32_t vpb = uint32_t(block_bytes >> 4);
-    const uint32_t v0 = q * chunk_vecs;
-    const uint32_t v1 = (vpb - v0 < chunk_vecs) ? vpb : v0 + chunk_vecs;
-
-    for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * UNROLL) {
-        u32x4 x[UNROLL];
+    const uint32_t v = (blockIdx.x >> lg_g) * (T * U) + threadIdx.x;
+    u32x4 x[U];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t i = v + u * WG;
-            if (i < v1) x[u] = ld<u32x4, NT>(s + i);
-        }
+    for (int u = 0; u < U; ++u)
+        if (v + u * T < vpb) x[u] = ld<u32x4, NT>(s + v + u * T);
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            const uint32_t i = v + u * WG;
-            if (i < v1) st<u32x4, NT>(d + i, x[u]);
-        }
-    }
+    for (int u = 0; u < U; ++u)
+        if (v + u * T < vpb) st<u32x4, NT>(d + v + u * T, x[u]);
 }
 
 // ---------------------------------------------------------------------------

@@ -67,7 +67,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     with pytest.raises(sb.SparbitError):
         sb.sparbit_tune("no_such_knob", 1)
     with pytest.raises(sb.SparbitError):
-        sb.sparbit_tune("tile_bytes", 1000)
+        sb.sparbit_tune("wg_threads", 1000)
 
 
 ORACLE_ALGO = {sb.SPARBIT: oracle.SPARBIT, sb.RING: oracle.RING,
