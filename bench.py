@@ -43,6 +43,9 @@ def parse_args():
     ap.add_argument("--skip-context", action="store_true", help="only the headline workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the benchmark: --steps plain 1 GiB copies (p=1 own-block placement), "
+                         "the known-size kernel that scales the rocprofv3 HBM counters")
     return ap.parse_args()
 
 
@@ -131,6 +134,15 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.Stream()
+    if args.calibrate_copy:
+        nbytes = 1 << 30
+        src = torch.full((nbytes,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        t = time_calls(torch, lambda: sb.sparbit_allgather_mode(src, dst, 1, nbytes, sb.SPARBIT, sb.MODE_PER_STEP, stream),
+                       stream, args.warmup, args.steps)
+        print(json.dumps({"calibrate_copy_bytes_each_way": nbytes, "launches": args.warmup + args.steps,
+                          "ok": bool(torch.equal(src, dst)), **t, **rates(1, nbytes, t["avg_ms"])}))
+        return
     w = workloads.WORKLOADS[args.workload]
     p, B = w.p, w.block_bytes
 

@@ -34,9 +34,9 @@ thread_local int tl_last_hip_error = 0;
 std::atomic<long long> g_wg_threads{256};                     // lanes per workgroup of the tile kernel
 std::atomic<long long> g_unroll{1};                           // 16-byte vectors per lane of the tile kernel
 std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
-std::atomic<long long> g_persistent_max_bytes{512ll << 20};   // AUTO threshold on p*p*B
+std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO threshold on p*p*B
 std::atomic<long long> g_nontemporal{1};
-std::atomic<long long> g_wgs_per_cu{4};
+std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
 std::atomic<long long> g_flat_below_bytes{4096};              // blocks smaller than this use the flat kernel
 

@@ -155,8 +155,9 @@ __device__ __forceinline__ bool grid_barrier(BarrierState* bar, uint32_t target,
         uint32_t f = 0;
         __hip_atomic_fetch_add(&bar->arrived, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         const uint64_t t0 = wall_clock64();
-        while (__hip_atomic_load(&bar->arrived, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(2);
+        // Spin on relaxed loads (no cache maintenance per poll); one acquire fence at the end.
+        while (__hip_atomic_load(&bar->arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(1);
             if (uint64_t(wall_clock64()) - t0 > limit ||
                 __hip_atomic_load(&bar->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
                 __hip_atomic_store(&bar->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -164,6 +165,7 @@ __device__ __forceinline__ bool grid_barrier(BarrierState* bar, uint32_t target,
                 break;
             }
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         failed = f;
     }
     __syncthreads();
