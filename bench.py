@@ -32,6 +32,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
+# HBM bytes per launch of the step kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (one run each,
+# scaled by a plain 1 GiB copy through the same kernel); figures and commands: profiles/copy_tiles_kernel_cfg4.md.
+# Only meaningful for the default tuning and issue mode of that workload.
+MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16779072 + 16763447) * 1024}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -104,7 +109,15 @@ def cpu_baseline(w):
     rate = p * p * B / dt
     target = max(B, min(w.block_bytes, int(rate * 10.0 / (p * p))))
     Bs = 1 << (target.bit_length() - 1)
-    while Bs > B and p * p * Bs > (8 << 30):
+    avail = 0
+    try:
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemAvailable:"):
+                avail = int(line.split()[1]) * 1024
+    except OSError:
+        pass
+    # the oracle holds the receive buffers plus a mailbox of up to half their size
+    while Bs > B and 2 * p * p * Bs > max(avail // 2, 1 << 30):
         Bs >>= 1
     if Bs > B:
         dt, B = run(Bs), Bs
@@ -158,7 +171,7 @@ def main():
         sys.exit(1)
     r = rates(p, B, head["avg_ms"])
     nsteps = sb.Plan(p).num_steps
-    launches = 1 if (mode == sb.MODE_PERSISTENT) else nsteps + 1
+    launches = 1 if (mode == sb.MODE_PERSISTENT) else nsteps  # own blocks + step 0 share the first launch
     out = {
         "metric": "effective Allgather GB/s (p*p*block_bytes landed / time), Sparbit schedule",
         "value": r["effective_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -168,9 +181,16 @@ def main():
                    "p": p, "block_bytes": B, "mode": args.mode},
         "min_ms": head["min_ms"], "max_ms": head["max_ms"], "wall_ms_per_step": head["wall_ms_per_call"],
         "roofline": {"bound": "hbm", "achieved": r["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": r["hbm_frac"], "traffic": None,
-                     "note": "algorithmic bytes 2*p*p*B per call over the event-timed region "
-                             f"({launches} launch(es) per call, gaps included)"},
+                     "frac": r["hbm_frac"],
+                     "traffic": (MEASURED_TRAFFIC_BYTES_PER_CALL[w.name] / launches
+                                 if w.name in MEASURED_TRAFFIC_BYTES_PER_CALL and not args.tune and args.mode == "auto"
+                                 else None),
+                     "kernel": "sparbit::copy_tiles_kernel<256, 1, true>", "launches_per_call": launches,
+                     "algorithmic_bytes_per_launch": 2 * p * p * B / launches,
+                     "avg_launch_ms": head["avg_ms"] / launches,
+                     "note": "achieved = algorithmic bytes per launch (2*p*p*B / launches) / average launch "
+                             "duration, the latter from HIP events on the launch stream over the timed region "
+                             "(launch gaps included); traffic = measured HBM bytes per launch"},
     }
     del d_recv
 

@@ -96,7 +96,7 @@ int get_plan(DeviceState* ds, int algo, int p, DevicePlan** out)
         all.insert(all.end(), ph.copies.begin(), ph.copies.end());
         DevPhase d{dp->first_copy.back(), uint32_t(ph.copies.size()), int32_t(ph.src_buf), int32_t(ph.dst_buf)};
         if (d.ncopies == 0) continue;
-        if (!ph.only_in_place) dp->out_of_place.push_back(d);
+        if (!ph.only_in_place && !ph.covered_by_fused) dp->out_of_place.push_back(d);
         if (!ph.skip_in_place) dp->in_place.push_back(d);
     }
     if (!all.empty()) {
@@ -346,6 +346,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     for (size_t i = 0; i < dp->host.phases.size(); ++i) {
         const Phase& ph = dp->host.phases[i];
         if (in_place ? ph.skip_in_place : ph.only_in_place) continue;
+        if (whole && !in_place ? ph.covered_by_fused : ph.fused_first) continue;
         const int step = (ph.step >= nsteps) ? nsteps - 1 : ph.step;  // Bruck's rotation rides with the last step
         if (step < first_step || step > last_step) continue;
         rc = launch_phase(base[ph.src_buf], const_cast<uint8_t*>(base[ph.dst_buf]), dp->d_copies + dp->first_copy[i],

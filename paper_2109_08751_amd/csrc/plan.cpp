@@ -194,6 +194,34 @@ static void build_direct(int p, Plan& out)
     out.phases.push_back(std::move(b));
 }
 
+// Step 0 of every schedule sends each rank's own block.  For a whole
+// out-of-place call that block can be read from the send buffer, which makes
+// step 0 independent of the own-block placement: both become one batch (one
+// launch less).  The state after the fused phase is the state after step 0.
+static void add_fused_first_phase(int p, Plan& out)
+{
+    if (out.steps.empty() || out.phases.size() < 2) return;
+    Phase& own = out.phases[0];
+    Phase& first = out.phases[1];
+    if (own.step != -1 || first.step != 0 || own.src_buf != BUF_SEND || own.dst_buf != first.src_buf) return;
+    std::vector<int64_t> owner(size_t(p) * size_t(p), -1);  // block index in the working buffer -> rank whose own block it is
+    for (const Copy& c : own.copies) owner[c.dst_block] = c.src_block;
+    Phase fused;
+    fused.step = 0;
+    fused.src_buf = BUF_SEND;
+    fused.dst_buf = own.dst_buf;
+    fused.skip_in_place = true;
+    fused.fused_first = true;
+    fused.copies = own.copies;
+    for (const Copy& c : first.copies) {
+        if (owner[c.src_block] < 0) return;  // step 0 forwards something else: leave the plan unfused
+        fused.copies.push_back(Copy{uint32_t(owner[c.src_block]), c.dst_block});
+    }
+    own.covered_by_fused = true;
+    first.covered_by_fused = true;
+    out.phases.insert(out.phases.begin(), std::move(fused));  // runs first where it is used
+}
+
 int build_plan(int p, int algo, Plan& out)
 {
     if (p < 1 || p > SPARBIT_MAX_P) return SPARBIT_ERR_ARG;
@@ -211,6 +239,7 @@ int build_plan(int p, int algo, Plan& out)
     case SPARBIT_ALGO_DIRECT: build_direct(p, out); break;
     default: return SPARBIT_ERR_ARG;
     }
+    if (algo != SPARBIT_ALGO_DIRECT) add_fused_first_phase(p, out);
     return SPARBIT_OK;
 }
 

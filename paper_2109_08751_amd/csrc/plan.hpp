@@ -32,6 +32,8 @@ struct Phase {
     Buffer src_buf = BUF_RECV, dst_buf = BUF_RECV;
     bool skip_in_place = false;      // phase is dropped when sendbufs == NULL
     bool only_in_place = false;      // phase exists only when sendbufs == NULL
+    bool fused_first = false;        // own-block placement and step 0 in one batch, step 0 reading the send buffer
+    bool covered_by_fused = false;   // own-block and step-0 phases: dropped where the fused phase runs
     std::vector<Copy> copies;
 };
 
