@@ -48,6 +48,10 @@ def parse_args():
     ap.add_argument("--skip-context", action="store_true", help="only the headline workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE")
+    ap.add_argument("--sweep", metavar="OUT.jsonl", default=None,
+                    help="instead of the benchmark: time every schedule over the block-size ladder 1 B .. 1 MiB "
+                         "(doubling, as OSU's osu_allgather in the paper's Section IV-A) for process counts on the "
+                         "paper's two progressions, one JSON line per case into OUT.jsonl")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="instead of the benchmark: --steps plain 1 GiB copies (p=1 own-block placement), "
                          "the known-size kernel that scales the rocprofv3 HBM counters")
@@ -127,6 +131,44 @@ def cpu_baseline(w):
                       f"recv {p * p * B / 2**20:.0f} MiB, one pass"}
 
 
+def sweep(torch, sb, workloads, stream, path):
+    """Latency/bandwidth ladder in the shape of the paper's test matrix (Section IV-A): block sizes 1 B .. 1 MiB by
+    doubling; p from the even/power-of-two progression (8, 16, ..., 256) and the odd one (5, 13, ..., 253), thinned."""
+    dev = torch.device("cuda:0")
+    ps = [8, 16, 32, 64, 128, 256, 5, 13, 29, 61, 125, 253]
+    sizes = [1 << k for k in range(0, 21)]
+    algos = [("sparbit", sb.SPARBIT), ("ring", sb.RING), ("recursive_doubling", sb.RECURSIVE_DOUBLING),
+             ("bruck", sb.BRUCK), ("direct", sb.DIRECT)]
+    n = 0
+    with open(path, "w") as out:
+        for p in ps:
+            for B in sizes:
+                if p * p * B > (32 << 30):
+                    continue
+                send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev)
+                recv = torch.full((p, p, B), workloads.POISON, dtype=torch.uint8, device=dev)
+                for label, algo in algos:
+                    if algo == sb.RECURSIVE_DOUBLING and p & (p - 1):
+                        continue
+                    if algo == sb.RING and p * p * B > (1 << 30):
+                        continue  # p - 1 launches of tiny kernels each: skipped where it only burns time
+                    fn = lambda: sb.sparbit_allgather_mode(send, recv, p, B, algo, sb.MODE_AUTO, stream)
+                    t = time_calls(torch, fn, stream, 3, 10)
+                    ok = bool(torch.equal(recv, send.unsqueeze(0).expand(p, p, B))) if p * p * B <= (1 << 28) \
+                        else bool(torch.equal(recv[p - 1], send))
+                    out.write(json.dumps({"p": p, "block_bytes": B, "algo": label, "ok": ok,
+                                          "avg_us": t["avg_ms"] * 1e3, "min_us": t["min_ms"] * 1e3,
+                                          "max_us": t["max_ms"] * 1e3,
+                                          "effective_GBps": p * p * B / t["avg_ms"] / 1e6}) + "\n")
+                    out.flush()
+                    n += 1
+                    recv.fill_(workloads.POISON)
+                del send, recv
+            print(f"sweep: p={p} done ({n} cases)", file=sys.stderr, flush=True)
+            torch.cuda.empty_cache()
+    return n
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -147,6 +189,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.Stream()
+    if args.sweep:
+        n = sweep(torch, sb, workloads, stream, args.sweep)
+        assert sb.sparbit_barrier_timeouts(stream) == 0
+        print(json.dumps({"sweep_cases": n, "file": args.sweep}))
+        return
     if args.calibrate_copy:
         nbytes = 1 << 30
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device=dev)

@@ -55,6 +55,12 @@ extern "C" {
 #define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes */
 #define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
 #define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
+#define SPARBIT_MODE_DATAFLOW 3   /* one launch; no barrier: a copy starts when the chunk it forwards has landed
+                                     (ready flag per chunk of a receive slot); in-place calls use PER_STEP.
+                                     PERSISTENT and DATAFLOW grids wait on themselves and need all their
+                                     workgroups resident: they take at most half of the GPU's wave slots, their
+                                     waits are bounded (see sparbit_barrier_timeouts), and AUTO picks them only
+                                     for jobs of a few workgroups.  PER_STEP never waits on the device. */
 
 /*
  * MPI_Allgather over p virtual ranks with the Sparbit schedule (Algorithm 1 of
@@ -124,9 +130,10 @@ const char *sparbit_strerror(int code);
 /* hipError_t value of the last failed HIP call on this thread (0 if none). */
 int sparbit_last_hip_error(void);
 /*
- * The persistent kernel's barrier waits are bounded (so that a grid that was
- * not co-resident ends instead of hanging); a launch whose wait expired leaves
- * wrong results and bumps a per-stream counter.  This call synchronises
+ * The waits of the persistent kernel (barrier) and of the dataflow kernel (ready
+ * flags) are bounded, so that a launch that cannot make progress ends instead
+ * of hanging; a launch whose wait expired leaves wrong results and bumps a
+ * per-stream counter.  This call synchronises
  * `stream` and stores that counter in *count (0 = every launch completed).
  */
 int sparbit_barrier_timeouts(void *stream, uint64_t *count);
@@ -138,9 +145,12 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "interleave_log2"      log2 of the block copies dealt round-robin to consecutive workgroups (3 = one per XCD)
  *   "flat_below_bytes"     blocks smaller than this use the flattened small-block kernel
  *   "persistent_max_bytes" AUTO uses the persistent kernel when p*p*block_bytes is at most this
+ *   "dataflow_max_bytes"   AUTO uses the dataflow kernel when p*p*block_bytes is at most this (and above the former)
+ *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16)
+ *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
  *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
- *   "spin_limit_ms"        bound of one barrier wait of the persistent kernel
+ *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  */
 int sparbit_tune(const char *key, long long value);
 

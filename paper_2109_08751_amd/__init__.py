@@ -8,7 +8,7 @@ import importlib
 
 _BINDING_NAMES = {
     "SPARBIT", "RING", "RECURSIVE_DOUBLING", "BRUCK", "DIRECT",
-    "MODE_AUTO", "MODE_PER_STEP", "MODE_PERSISTENT",
+    "MODE_AUTO", "MODE_PER_STEP", "MODE_PERSISTENT", "MODE_DATAFLOW",
     "SparbitError", "Plan", "lib", "lib_path",
     "sparbit_allgather", "sparbit_allgather_algo", "sparbit_allgather_steps",
     "sparbit_allgather_mode", "sparbit_finalize", "sparbit_strerror",

@@ -19,7 +19,7 @@ import numpy as np
 from . import build as _build
 
 SPARBIT, RING, RECURSIVE_DOUBLING, BRUCK, DIRECT = 0, 1, 2, 3, 4
-MODE_AUTO, MODE_PER_STEP, MODE_PERSISTENT = 0, 1, 2
+MODE_AUTO, MODE_PER_STEP, MODE_PERSISTENT, MODE_DATAFLOW = 0, 1, 2, 3
 ALGOS = {"sparbit": SPARBIT, "ring": RING, "recursive_doubling": RECURSIVE_DOUBLING,
          "bruck": BRUCK, "direct": DIRECT}
 

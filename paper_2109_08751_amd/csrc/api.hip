@@ -36,6 +36,9 @@ std::atomic<long long> g_unroll{1};                           // 16-byte vectors
 std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
 std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO threshold on p*p*B
 std::atomic<long long> g_nontemporal{1};
+std::atomic<long long> g_dataflow_max_bytes{64ll << 10};      // AUTO threshold on p*p*B for the dataflow kernel
+std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
+std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
 std::atomic<long long> g_flat_below_bytes{4096};              // blocks smaller than this use the flat kernel
@@ -49,9 +52,17 @@ struct DevicePlan {
     std::vector<DevPhase> out_of_place, in_place;
 };
 
+struct FlowStream {  // per-stream state of the dataflow kernel
+    FlowState* state = nullptr;
+    uint32_t* flags = nullptr;
+    size_t flag_capacity = 0;
+    uint32_t epoch = 0;  // last call number handed out (0 is never used: fresh flags are 0)
+};
+
 struct DeviceState {
     int device = -1;
     int num_cus = 0;
+    std::map<hipStream_t, FlowStream> flows;
     std::map<std::pair<int, int>, std::unique_ptr<DevicePlan>> plans;  // (algo, p)
     std::map<hipStream_t, BarrierState*> barriers;
     void* work = nullptr;  // Bruck's rotated working buffer
@@ -94,10 +105,14 @@ int get_plan(DeviceState* ds, int algo, int p, DevicePlan** out)
     for (const Phase& ph : dp->host.phases) {
         dp->first_copy.push_back(uint32_t(all.size()));
         all.insert(all.end(), ph.copies.begin(), ph.copies.end());
-        DevPhase d{dp->first_copy.back(), uint32_t(ph.copies.size()), int32_t(ph.src_buf), int32_t(ph.dst_buf)};
+        DevPhase d{dp->first_copy.back(), uint32_t(ph.copies.size()), int32_t(ph.src_buf), int32_t(ph.dst_buf), 0u, 0u};
         if (d.ncopies == 0) continue;
-        if (!ph.only_in_place && !ph.covered_by_fused) dp->out_of_place.push_back(d);
-        if (!ph.skip_in_place) dp->in_place.push_back(d);
+        auto append = [&d](std::vector<DevPhase>& list) {
+            d.copies_before = list.empty() ? 0u : list.back().copies_before + list.back().ncopies;
+            list.push_back(d);
+        };
+        if (!ph.only_in_place && !ph.covered_by_fused) append(dp->out_of_place);
+        if (!ph.skip_in_place) append(dp->in_place);
     }
     if (!all.empty()) {
         SB_HIP(hipMalloc(reinterpret_cast<void**>(&dp->d_copies), all.size() * sizeof(Copy)));
@@ -127,6 +142,31 @@ int get_barrier(DeviceState* ds, hipStream_t stream, BarrierState** out)
         it = ds->barriers.emplace(stream, b).first;
     }
     *out = it->second;
+    return SPARBIT_OK;
+}
+
+int get_flow(DeviceState* ds, hipStream_t stream, size_t nflags, FlowStream** out)
+{
+    FlowStream& fs = ds->flows[stream];
+    if (!fs.state) {
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&fs.state), sizeof(FlowState)));
+        SB_HIP(hipMemset(fs.state, 0, sizeof(FlowState)));
+        SB_HIP(hipDeviceSynchronize());
+    }
+    if (fs.flag_capacity < nflags) {
+        if (fs.flags) {
+            SB_HIP(hipStreamSynchronize(stream));
+            SB_HIP(hipFree(fs.flags));
+            fs.flags = nullptr;
+            fs.flag_capacity = 0;
+        }
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&fs.flags), nflags * sizeof(uint32_t)));
+        SB_HIP(hipMemset(fs.flags, 0, nflags * sizeof(uint32_t)));
+        SB_HIP(hipDeviceSynchronize());
+        fs.flag_capacity = nflags;
+        fs.epoch = 0;
+    }
+    *out = &fs;
     return SPARBIT_OK;
 }
 
@@ -264,6 +304,21 @@ int launch_persistent_v(const PersistentArgs& a, int num_cus, uint64_t max_tiles
     return SPARBIT_OK;
 }
 
+template <typename V>
+int launch_dataflow_v(const FlowArgs& a, int num_cus, hipStream_t stream)
+{
+    int per_cu = 0;
+    SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dataflow_kernel<V>, WG, 0));
+    if (per_cu < 1) return SPARBIT_ERR_HIP;
+    long long want = g_flow_wgs_per_cu.load();
+    if (want > per_cu) want = per_cu;  // every workgroup must be resident
+    uint64_t grid = uint64_t(num_cus) * uint64_t(want);
+    if (grid > a.total_items) grid = a.total_items;
+    hipLaunchKernelGGL((dataflow_kernel<V>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb)
 {
     const uintptr_t a0 = uintptr_t(a), b0 = uintptr_t(b);
@@ -276,7 +331,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
 {
     if (p < 1 || p > SPARBIT_MAX_P || !recvbufs) return SPARBIT_ERR_ARG;
     if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
-    if (mode < SPARBIT_MODE_AUTO || mode > SPARBIT_MODE_PERSISTENT) return SPARBIT_ERR_ARG;
+    if (mode < SPARBIT_MODE_AUTO || mode > SPARBIT_MODE_DATAFLOW) return SPARBIT_ERR_ARG;
     const unsigned __int128 total128 = (unsigned __int128)(uint64_t(p) * uint64_t(p)) * B;
     if (total128 > (unsigned __int128)0x7fffffffffffffffull) return SPARBIT_ERR_ARG;
     const size_t recv_bytes = size_t(p) * size_t(p) * B;
@@ -314,9 +369,59 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
                               static_cast<const uint8_t*>(work)};
     const int width = access_width(sendbufs, recvbufs, work, B);
 
-    if (mode == SPARBIT_MODE_AUTO)
-        mode = (recv_bytes <= size_t(g_persistent_max_bytes.load())) ? SPARBIT_MODE_PERSISTENT : SPARBIT_MODE_PER_STEP;
+    if (mode == SPARBIT_MODE_AUTO) {
+        // Single-launch forms only where the whole job is a handful of workgroups: a grid that waits on
+        // itself while it holds most of the machine starves whatever else runs on the GPU (and is starved
+        // by it), so anything larger goes out as one launch per step, which never waits on the device.
+        if (recv_bytes <= size_t(g_dataflow_max_bytes.load()) && !in_place)
+            mode = SPARBIT_MODE_DATAFLOW;
+        else if (recv_bytes <= size_t(g_persistent_max_bytes.load()))
+            mode = SPARBIT_MODE_PERSISTENT;
+        else
+            mode = SPARBIT_MODE_PER_STEP;
+    }
     const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
+
+    // Dataflow form: flags instead of barriers.  In-place calls have no item that
+    // would publish the flags of the own slots, so they take the per-step path.
+    if (whole && mode == SPARBIT_MODE_DATAFLOW && !in_place && !phases.empty()) {
+        const size_t unit = width == 16 ? 8 : size_t(width);  // widest single-copy atomic access is 8 bytes
+        size_t chunk = size_t(g_flow_chunk_bytes.load());
+        chunk -= chunk % 16;
+        if (chunk < 16) chunk = 16;
+        const uint64_t cpb = (B + chunk - 1) / chunk;
+        const uint64_t ncopies_total = phases.back().copies_before + phases.back().ncopies;
+        const uint64_t items = ncopies_total * cpb;
+        const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
+        if (items <= 0x7fffffffull && flags_per_buf <= 0x3fffffffull && chunk / unit <= 0xffffffffull) {
+            FlowStream* fs = nullptr;
+            if ((rc = get_flow(ds, stream, size_t(2 * flags_per_buf), &fs)) != SPARBIT_OK) return rc;
+            FlowArgs a;
+            std::memset(&a, 0, sizeof a);
+            a.base[0] = base[0];
+            a.base[1] = base[1];
+            a.base[2] = base[2];
+            a.copies = dp->d_copies;
+            a.phases = dp->d_phases;
+            a.state = fs->state;
+            a.flags = fs->flags;
+            a.block_bytes = B;
+            a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
+            a.nphases = uint32_t(phases.size());
+            a.chunks_per_block = uint32_t(cpb);
+            a.chunk_vecs = uint32_t(chunk / unit);
+            a.flags_per_buf = uint32_t(flags_per_buf);
+            if (++fs->epoch == 0) fs->epoch = 1;  // wrapped: 0 stays reserved for "never filled"
+            a.epoch = fs->epoch;
+            a.total_items = uint32_t(items);
+            switch (width) {
+            case 16: return launch_dataflow_v<uint64_t>(a, ds->num_cus, stream);
+            case 4: return launch_dataflow_v<uint32_t>(a, ds->num_cus, stream);
+            default: return launch_dataflow_v<uint8_t>(a, ds->num_cus, stream);
+            }
+        }
+        mode = SPARBIT_MODE_PER_STEP;  // too many items for one grid
+    }
 
     if (whole && mode == SPARBIT_MODE_PERSISTENT && !phases.empty()) {
         PersistentArgs a;
@@ -399,6 +504,10 @@ void sparbit_finalize(void)
             (void)hipFree(pk.second->d_phases_in_place);
         }
         for (auto& bk : ds->barriers) (void)hipFree(bk.second);
+        for (auto& fk : ds->flows) {
+            (void)hipFree(fk.second.state);
+            (void)hipFree(fk.second.flags);
+        }
         if (ds->work) (void)hipFree(ds->work);
     }
     sparbit::g_devices.clear();
@@ -432,10 +541,17 @@ int sparbit_barrier_timeouts(void* stream_v, uint64_t* count)
     if (rc != SPARBIT_OK) return rc;
     SB_HIP(hipStreamSynchronize(stream));
     auto it = ds->barriers.find(stream);
-    if (it == ds->barriers.end()) return SPARBIT_OK;  // no persistent launch on this stream yet
-    BarrierState host;
-    SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
-    *count = host.errors;
+    if (it != ds->barriers.end()) {
+        BarrierState host;
+        SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
+        *count += host.errors;
+    }
+    auto jt = ds->flows.find(stream);
+    if (jt != ds->flows.end() && jt->second.state) {
+        FlowState host;
+        SB_HIP(hipMemcpy(&host, jt->second.state, sizeof host, hipMemcpyDeviceToHost));
+        *count += host.errors;
+    }
     return SPARBIT_OK;
 }
 
@@ -455,6 +571,15 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "persistent_max_bytes")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_persistent_max_bytes = value;
+    } else if (!std::strcmp(key, "dataflow_max_bytes")) {
+        if (value < 0) return SPARBIT_ERR_ARG;
+        g_dataflow_max_bytes = value;
+    } else if (!std::strcmp(key, "flow_wgs_per_cu")) {
+        if (value < 1 || value > 16) return SPARBIT_ERR_ARG;
+        g_flow_wgs_per_cu = value;
+    } else if (!std::strcmp(key, "flow_chunk_bytes")) {
+        if (value < 16 || (value & 15)) return SPARBIT_ERR_ARG;
+        g_flow_chunk_bytes = value;
     } else if (!std::strcmp(key, "nontemporal")) {
         g_nontemporal = value ? 1 : 0;
     } else if (!std::strcmp(key, "wgs_per_cu")) {

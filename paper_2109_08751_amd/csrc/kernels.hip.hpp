@@ -128,6 +128,8 @@ struct DevPhase {
     uint32_t ncopies;
     int32_t src_buf;  // Buffer
     int32_t dst_buf;
+    uint32_t copies_before;  // copies of the earlier phases of the same call (dataflow item numbering)
+    uint32_t pad;
 };
 
 struct BarrierState {
@@ -208,6 +210,122 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
             __hip_atomic_store(&a.bar->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&a.bar->left, 0u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Dataflow form (the non-blocking variant the paper names as future work in
+// its conclusion): one launch, no device-wide barrier.  The unit of work is
+// one chunk (<= chunk_bytes) of one block copy; every chunk of a receive slot
+// has a ready flag that holds the number of the call that last filled it.
+// Items are numbered in phase order and dealt round-robin to the workgroups of
+// a grid that the host sizes to be fully resident; a workgroup takes its items
+// in increasing order, waits for the flag of the item's source chunk (unless
+// the source is the send buffer), copies, and publishes the flag of the
+// destination chunk.  An item only waits for an
+// item of an earlier phase, i.e. a lower number, so the lowest unfinished item
+// can always run: no deadlock while all workgroups are resident.  Waits are
+// bounded all the same.
+//
+// What this machine makes expensive, and how the kernel avoids it:
+//  - a device-scope atomic read-modify-write on one address costs ~70 ns and
+//    serialises, so there is no ticket or arrival counter on the fast path;
+//  - an agent-scope release / acquire is a write-back / invalidate of the whole
+//    L2 of the XCD (~300 ns each, serialised per XCD), far too much per chunk.
+//    Instead every data access is itself coherent at agent scope (relaxed
+//    atomic loads and stores of 8, 4 or 1 bytes: they go past the XCD's L2 to
+//    the memory side), so no cache maintenance is needed: a wave waits for its
+//    own stores to be acknowledged (s_waitcnt vmcnt(0)), the workgroup meets at
+//    a barrier, and one lane stores the flag.
+// ---------------------------------------------------------------------------
+template <typename V>
+__device__ __forceinline__ V coherent_ld(const V* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <typename V>
+__device__ __forceinline__ void coherent_st(V* p, V v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct FlowState {
+    uint32_t abort;   // number of the last call in which a bounded wait expired
+    uint32_t errors;  // sticky count of such calls
+};
+
+struct FlowArgs {
+    const uint8_t* base[3];
+    const Copy* copies;
+    const DevPhase* phases;
+    FlowState* state;
+    uint32_t* flags;         // [2][p * p * chunks_per_block]: receive buffer, then the working buffer
+    uint64_t block_bytes;
+    uint64_t spin_limit_ticks;
+    uint32_t nphases;
+    uint32_t chunks_per_block;
+    uint32_t chunk_vecs;     // chunk size in units of sizeof(V)
+    uint32_t flags_per_buf;
+    uint32_t epoch;          // number of this call on its stream, never 0
+    uint32_t total_items;
+};
+
+template <typename V>
+__global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
+{
+    __shared__ uint32_t s_ok;
+    const uint32_t vpb = uint32_t(a.block_bytes / sizeof(V));
+    uint32_t ph = 0;  // items come in phase order, so the phase index only moves forward
+    for (uint32_t item = blockIdx.x; item < a.total_items; item += gridDim.x) {
+        const uint32_t k = item / a.chunks_per_block;  // copy ordinal within the call
+        const uint32_t q = item - k * a.chunks_per_block;
+        while (ph + 1 < a.nphases && a.phases[ph + 1].copies_before <= k) ++ph;
+        const DevPhase P = a.phases[ph];
+        const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
+        const uint32_t v0 = q * a.chunk_vecs;
+        const uint32_t v1 = (vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
+        if (P.src_buf != BUF_SEND) {
+            if (threadIdx.x == 0) {
+                const uint32_t* f = a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) +
+                                    cp.src_block * a.chunks_per_block + q;
+                uint32_t good = 1;
+                const uint64_t t0 = wall_clock64();
+                while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
+                    __builtin_amdgcn_s_sleep(1);
+                    const bool expired = uint64_t(wall_clock64()) - t0 > a.spin_limit_ticks;
+                    if (expired || __hip_atomic_load(&a.state->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch) {
+                        if (expired && __hip_atomic_exchange(&a.state->abort, a.epoch, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
+                            __hip_atomic_fetch_add(&a.state->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        good = 0;
+                        break;
+                    }
+                }
+                s_ok = good;
+            }
+            __syncthreads();
+            if (s_ok == 0) break;  // uniform: the whole workgroup leaves
+        }
+        const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
+        V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
+        constexpr int U = 8;
+        for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
+            V x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (v + u * WG < v1) x[u] = coherent_ld<V>(s + v + u * WG);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
+        }
+        // Own stores acknowledged by the memory side, then the workgroup meets, then the flag.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0)
+            coherent_st<uint32_t>(a.flags + (P.dst_buf == BUF_WORK ? a.flags_per_buf : 0u) +
+                                      cp.dst_block * a.chunks_per_block + q,
+                                  a.epoch);
     }
 }
 

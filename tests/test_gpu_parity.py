@@ -11,7 +11,8 @@ from paper_2109_08751_amd import workloads
 pytestmark = pytest.mark.gpu
 
 POISON = workloads.POISON
-MODES = {"per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT, "auto": sb.MODE_AUTO}
+MODES = {"per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT, "auto": sb.MODE_AUTO,
+         "dataflow": sb.MODE_DATAFLOW}
 ORACLE_ALGO = {sb.SPARBIT: oracle.SPARBIT, sb.RING: oracle.RING,
                sb.RECURSIVE_DOUBLING: oracle.RECURSIVE_DOUBLING, sb.BRUCK: oracle.BRUCK,
                sb.DIRECT: oracle.NAIVE}
@@ -66,7 +67,7 @@ def gpu_result(torch, algo, p, B, send, mode, in_place=False, misalign=0):
 
 
 # ------------------------------------------------------------------ the configs
-@pytest.mark.parametrize("mode", ["per_step", "persistent", "auto"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "auto"])
 @pytest.mark.parametrize("cfg", ["cfg1", "cfg3", "cfg2"])
 def test_config_matches_oracle_element_by_element(torch, cfg, mode):
     w = workloads.WORKLOADS[cfg]
@@ -95,7 +96,7 @@ def test_every_step_boundary_matches_oracle(torch, cfg):
 
 
 # ------------------------------------------------------------------ sweeps
-@pytest.mark.parametrize("mode", ["per_step", "persistent"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
 def test_every_p_up_to_33_and_ragged_block_sizes(torch, mode):
     for p in list(range(1, 34)) + [63, 65, 100]:
         for B in (1, 3, 20, 100, 4096 + 16):
@@ -108,7 +109,7 @@ def test_every_p_up_to_33_and_ragged_block_sizes(torch, mode):
             assert np.array_equal(got, want), (p, B)
 
 
-@pytest.mark.parametrize("mode", ["per_step", "persistent"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
 @pytest.mark.parametrize("misalign", [1, 4, 16])
 def test_misaligned_base_pointers(torch, mode, misalign):
     for p, B in ((6, 1024), (21, 48), (5, 70000), (33, 4100)):
@@ -119,7 +120,7 @@ def test_misaligned_base_pointers(torch, mode, misalign):
         assert np.array_equal(got, want), (p, B)
 
 
-@pytest.mark.parametrize("mode", ["per_step", "persistent"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
 def test_in_place(torch, mode):
     for p, B in ((1, 64), (6, 1024), (21, 48), (64, 4096), (257, 16)):
         announce("in place", mode, p, B)
@@ -134,7 +135,7 @@ def test_large_rank_count(torch):
     announce("p=1000")
     send = workloads.make_send_raw(p, B, seed=5)
     want = np.broadcast_to(send[None], (p, p, B))  # oracle pinned to this at p=1000 in the CPU tests
-    for mode in ("per_step", "persistent"):
+    for mode in ("per_step", "persistent", "dataflow"):
         got = gpu_result(torch, sb.SPARBIT, p, B, send, MODES[mode])
         assert np.array_equal(got, want)
 
@@ -149,25 +150,30 @@ def test_zero_size_blocks_and_single_rank(torch):
     assert np.array_equal(got, send[None])
 
 
-def test_repeated_calls_on_two_streams(torch):
-    """Back-to-back persistent launches reuse the per-stream barrier state."""
+@pytest.mark.parametrize("mode", ["persistent", "dataflow"])
+def test_repeated_calls_on_two_streams(torch, mode):
+    """Back-to-back single-launch calls reuse the per-stream barrier / flag state
+    (also across different p and block sizes on one stream)."""
     w = workloads.WORKLOADS["cfg3"]
     send = workloads.make_send(w)
     want = oracle_result(sb.SPARBIT, w.p, w.block_bytes, send)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     bufs = [gpu_buffers(torch, w.p, w.block_bytes, send) for _ in range(2)]
     torch.cuda.synchronize()
+    small = gpu_buffers(torch, 21, 48, workloads.make_send_raw(21, 48, seed=2))
     for it in range(5):
         for st, (d_send, d_recv, _) in zip((s1, s2), bufs):
-            sb.sparbit_allgather_mode(d_send, d_recv, w.p, w.block_bytes, sb.SPARBIT, sb.MODE_PERSISTENT, st)
+            sb.sparbit_allgather_mode(d_send, d_recv, w.p, w.block_bytes, sb.SPARBIT, MODES[mode], st)
+            sb.sparbit_allgather_mode(small[0], small[1], 21, 48, sb.SPARBIT, MODES[mode], st)
     torch.cuda.synchronize()
+    assert bool((small[1].view(21, 21, 48) == small[0].view(1, 21, 48)).all())
     assert sb.sparbit_barrier_timeouts(s1) == 0 and sb.sparbit_barrier_timeouts(s2) == 0
     for _, d_recv, _ in bufs:
         assert np.array_equal(d_recv.cpu().numpy().reshape(want.shape), want)
 
 
 # ------------------------------------------------------------------ context schedules
-@pytest.mark.parametrize("mode", ["per_step", "persistent"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
 @pytest.mark.parametrize("algo", [sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT])
 def test_context_schedules_match_oracle(torch, algo, mode):
     for p, B in ((1, 32), (6, 1024), (8, 100), (64, 4096), (96, 4096), (33, 20)):
