@@ -98,6 +98,28 @@ int sparbit_allgather_mode(const void *sendbufs, void *recvbufs, int p, size_t b
 int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
                             int algo, int first_step, int last_step, void *stream);
 
+/*
+ * MPI_Allgatherv over the same schedules -- the extension to blocks of
+ * different sizes that the paper's conclusion (Section VII) names as future
+ * work; the schedule is unchanged, every message just has its slot's length.
+ *   counts, displs  HOST arrays of p entries, read during the call and not kept:
+ *               rank k contributes counts[k] bytes (0 allowed), which land at
+ *               byte displs[k] of every rank's receive buffer.  Blocks must lie
+ *               inside row_bytes and must not overlap each other.
+ *   recvbufs    device; rank r's receive buffer starts at byte r * row_bytes.
+ *               Bytes that belong to no block are left untouched.
+ *   sendbufs    device, laid out like ONE receive buffer (rank r's block at
+ *               displs[r], row_bytes in all); NULL = in place.
+ *   algo        SPARBIT, RING, RECURSIVE_DOUBLING (p a power of two) or DIRECT;
+ *               BRUCK returns SPARBIT_ERR_UNSUPPORTED (its rotated working
+ *               buffer is defined for equal blocks).
+ * One launch per step.  The copy lists of the last few (algo, p, counts, displs,
+ * row_bytes) geometries are cached per device; a new geometry costs O(p^2) host
+ * work and one upload.
+ */
+int sparbit_allgatherv(const void *sendbufs, void *recvbufs, int p, const size_t *counts,
+                       const size_t *displs, size_t row_bytes, int algo, void *stream);
+
 /* ---- schedule builder (host only; no GPU needed) -------------------------- */
 typedef struct sparbit_plan sparbit_plan_t;
 

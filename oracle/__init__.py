@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     OracleError,
     OracleRun,
     allgather,
+    allgatherv,
     build,
     naive_allgather,
     num_steps,

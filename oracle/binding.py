@@ -62,6 +62,11 @@ def _load():
             ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
             ctypes.POINTER(ctypes.c_size_t)]
         lib.oracle_allgather.restype = ctypes.c_int
+        lib.oracle_allgatherv.argtypes = [
+            ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_size_t)]
+        lib.oracle_allgatherv.restype = ctypes.c_int
         lib.oracle_strerror.argtypes = [ctypes.c_int]
         lib.oracle_strerror.restype = ctypes.c_char_p
         _lib = lib
@@ -122,6 +127,38 @@ def allgather(algo: int, p: int, block_bytes: int, send: Optional[np.ndarray], r
     n = ctypes.c_size_t(0)
     rc = lib.oracle_allgather(
         algo, p, block_bytes,
+        None if send is None else send.ctypes.data, recv.ctypes.data, max_steps,
+        step_info.ctypes.data if total else None, sent.ctypes.data,
+        None if trace is None else trace.ctypes.data, cap, ctypes.byref(n))
+    _check(rc)
+    ran = total if max_steps < 0 else min(max_steps, total)
+    return OracleRun(ran, step_info[:ran].copy(), sent,
+                     None if trace is None else trace[: n.value].copy())
+
+
+def allgatherv(algo: int, p: int, counts, displs, row_bytes: int, send: Optional[np.ndarray],
+               recv: np.ndarray, max_steps: int = -1, want_trace: bool = False) -> OracleRun:
+    """MPI_Allgatherv simulation: rank k contributes counts[k] bytes that land at
+    byte displs[k] of every receive buffer; `recv` holds p buffers row_bytes apart,
+    `send` is laid out like one receive buffer (or None for in place)."""
+    lib = _load()
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    d = np.ascontiguousarray(displs, dtype=np.uint64)
+    if c.shape != (p,) or d.shape != (p,):
+        raise ValueError("counts and displs need p entries")
+    if send is not None:
+        _as_bytes(send, row_bytes, "send")
+    _as_bytes(recv, p * row_bytes, "recv")
+    total = max(lib.oracle_num_steps(algo, p), 0)
+    step_info = np.zeros((total, 3), dtype=np.int32)
+    sent = np.zeros(p, dtype=np.int64)
+    trace, cap = None, 0
+    if want_trace:
+        cap = p * p
+        trace = np.zeros((cap, 5), dtype=np.int32)
+    n = ctypes.c_size_t(0)
+    rc = lib.oracle_allgatherv(
+        algo, p, c.ctypes.data, d.ctypes.data, row_bytes,
         None if send is None else send.ctypes.data, recv.ctypes.data, max_steps,
         step_info.ctypes.data if total else None, sent.ctypes.data,
         None if trace is None else trace.ctypes.data, cap, ctypes.byref(n))

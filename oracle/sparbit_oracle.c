@@ -12,7 +12,9 @@
  * What it simulates
  *   - MPI_Allgather post-condition (Section II): block of rank j ends in slot
  *     j of every rank's receive buffer.  oracle_naive_allgather() is that
- *     definition written out.
+ *     definition written out.  oracle_allgatherv() is the same simulation with
+ *     per-rank block sizes and displacements (MPI_Allgatherv, the extension
+ *     named in the paper's conclusion).
  *   - Sparbit, Algorithm 1 (Section III-B), executed literally per rank with
  *     the variables data / ignore / d / last_ignore / ignore_steps.
  *   - Ring, Recursive Doubling and Bruck as described in Section II-A
@@ -83,8 +85,10 @@ typedef struct {
 
 typedef struct {
     int p;
-    size_t B;
-    uint8_t *recv;    /* p * p * B, caller's memory */
+    size_t row_bytes;      /* distance between two ranks' receive buffers */
+    const size_t *off;     /* [p] byte offset of slot k inside a receive buffer */
+    const size_t *len;     /* [p] bytes of slot k (uniform B for MPI_Allgather) */
+    uint8_t *recv;         /* p receive buffers, caller's memory */
     uint8_t *written; /* p * p: 0 = poison, 1 = holds a block */
     uint8_t *sent_now; /* p * p: slot is a send source in the current step */
     post_t *sends;    /* [p][cap] in posting order */
@@ -123,7 +127,7 @@ static int count_trailing_zeros_int(int p)
 
 static uint8_t *slot_ptr(sim_t *s, int rank, int slot)
 {
-    return s->recv + ((size_t)rank * (size_t)s->p + (size_t)slot) * s->B;
+    return s->recv + (size_t)rank * s->row_bytes + s->off[slot];
 }
 
 static void post_isend(sim_t *s, int rank, int peer, int slot)
@@ -146,11 +150,13 @@ static void post_irecv(sim_t *s, int rank, int peer, int slot)
 static int waitall(sim_t *s, int require_same_slot)
 {
     const int p = s->p;
-    const size_t B = s->B;
-    size_t total = 0;
+    size_t total = 0, payload = 0;
     int r, j;
-    for (r = 0; r < p; r++)
+    for (r = 0; r < p; r++) {
         total += (size_t)s->nsends[r];
+        for (j = 0; j < s->nsends[r]; j++)
+            payload += s->len[s->sends[(size_t)r * s->cap + j].slot];
+    }
     if (total == 0) {
         for (r = 0; r < p; r++)
             if (s->nrecvs[r])
@@ -158,23 +164,24 @@ static int waitall(sim_t *s, int require_same_slot)
         return ORACLE_OK;
     }
     uint8_t *mailbox;
-    if (s->mailbox_cap < total * B) {
+    if (s->mailbox_cap < payload + 1) {
         free(s->mailbox);
-        s->mailbox = (uint8_t *)malloc(total * B);
-        s->mailbox_cap = s->mailbox ? total * B : 0;
+        s->mailbox = (uint8_t *)malloc(payload + 1);
+        s->mailbox_cap = s->mailbox ? payload + 1 : 0;
     }
     mailbox = s->mailbox;
     size_t *base = (size_t *)malloc((size_t)p * sizeof(size_t));
+    size_t *where = (size_t *)malloc(total * sizeof(size_t)); /* mailbox offset of each staged message */
     uint8_t *consumed = (uint8_t *)calloc(total, 1);
     int *cursor = (int *)calloc((size_t)p, sizeof(int));
     int rc = ORACLE_OK;
-    if (!mailbox || !base || !consumed || !cursor) {
+    if (!mailbox || !base || !where || !consumed || !cursor) {
         rc = ORACLE_ERR_NOMEM;
         goto out;
     }
     memset(s->sent_now, 0, (size_t)p * p);
     {
-        size_t k = 0;
+        size_t k = 0, at = 0;
         for (r = 0; r < p; r++) {
             base[r] = k;
             for (j = 0; j < s->nsends[r]; j++, k++) {
@@ -184,7 +191,9 @@ static int waitall(sim_t *s, int require_same_slot)
                     goto out;
                 }
                 s->sent_now[(size_t)r * p + q->slot] = 1;
-                memcpy(mailbox + k * B, slot_ptr(s, r, q->slot), B);
+                where[k] = at;
+                memcpy(mailbox + at, slot_ptr(s, r, q->slot), s->len[q->slot]);
+                at += s->len[q->slot];
             }
         }
     }
@@ -221,7 +230,11 @@ static int waitall(sim_t *s, int require_same_slot)
                     rc = ORACLE_ERR_READ_WRITE;
                     goto out;
                 }
-                memcpy(slot_ptr(s, r, rq->slot), mailbox + (base[src] + found) * B, B);
+                if (s->len[src_slot] != s->len[rq->slot]) {
+                    rc = ORACLE_ERR_SLOT_MISMATCH;
+                    goto out;
+                }
+                memcpy(slot_ptr(s, r, rq->slot), mailbox + where[base[src] + found], s->len[rq->slot]);
                 s->written[(size_t)r * p + rq->slot] = 1;
                 if (s->trace) {
                     if (s->trace_len >= s->trace_cap) {
@@ -248,6 +261,7 @@ static int waitall(sim_t *s, int require_same_slot)
     }
 out:
     free(base);
+    free(where);
     free(consumed);
     free(cursor);
     for (r = 0; r < p; r++)
@@ -327,45 +341,34 @@ int oracle_naive_allgather(int p, size_t B, const void *send, void *recv)
     return ORACLE_OK;
 }
 
-/*
- * Run `algo` for p ranks with blocks of B bytes.
- *   send      p blocks (rank r at byte r*B), or NULL for in-place: recv[r][r]
- *             already holds rank r's block.
- *   recv      p*p blocks, rank r's buffer at byte r*p*B.  Slots that are never
- *             written keep whatever the caller put there (poison).
- *   max_steps run only the first max_steps communication steps (negative =
- *             all).  Bruck's final rotation happens only when all steps ran.
- *   step_info optional, [num_steps][3] int32: per step the distance d, the
- *             ignore flag (Sparbit; 0 otherwise) and the number of blocks rank
- *             0 sent.
- *   sent_per_rank optional, [p] int64: total blocks each rank sent.
- *   trace     optional, rows of 5 int32 (step, src, dst, src_slot, dst_slot),
- *             one per delivered message; trace_cap rows available, *trace_len
- *             receives the number written.
- * Returns ORACLE_OK or a negative ORACLE_ERR_* code.
- */
-int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, int max_steps,
-                     int32_t *step_info, int64_t *sent_per_rank, int32_t *trace, size_t trace_cap,
-                     size_t *trace_len)
+/* The simulation proper.  Slot k of every receive buffer sits at byte off[k]
+ * and holds len[k] bytes; rank r's receive buffer starts at r * row_bytes; the
+ * send buffer is laid out like one receive buffer (rank r's block at off[r]).
+ * `uniform_block` is the common block size when all slots have one (needed by
+ * Bruck's rotated working buffer), else 0. */
+static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, const size_t *len,
+                        size_t uniform_block, const void *send, void *recv, int max_steps,
+                        int32_t *step_info, int64_t *sent_per_rank, int32_t *trace,
+                        size_t trace_cap, size_t *trace_len)
 {
     sim_t s;
     int rc = ORACLE_OK, r, step, nsteps;
     sparbit_rank_t *sv = NULL;
     int *bruck_have = NULL;
 
-    if (p < 1 || B == 0 || !recv)
-        return ORACLE_ERR_ARG;
-    if (algo == ORACLE_NAIVE)
-        return oracle_naive_allgather(p, B, send, recv);
     nsteps = oracle_num_steps(algo, p);
     if (nsteps < 0)
         return (algo == ORACLE_RECURSIVE_DOUBLING) ? ORACLE_ERR_UNSUPPORTED : ORACLE_ERR_ARG;
     if (algo == ORACLE_BRUCK && !send)
         return ORACLE_ERR_ARG; /* the rotated working buffer has no in-place form */
+    if (algo == ORACLE_BRUCK && !uniform_block)
+        return ORACLE_ERR_UNSUPPORTED; /* rotated layout is defined for equal blocks only */
 
     memset(&s, 0, sizeof s);
     s.p = p;
-    s.B = B;
+    s.row_bytes = row_bytes;
+    s.off = off;
+    s.len = len;
     s.recv = (uint8_t *)recv;
     s.cap = p;
     s.trace = trace;
@@ -390,7 +393,7 @@ int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, in
     for (r = 0; r < p; r++) {
         int own = (algo == ORACLE_BRUCK) ? 0 : r;
         if (send)
-            memcpy(slot_ptr(&s, r, own), (const uint8_t *)send + (size_t)r * B, B);
+            memcpy(slot_ptr(&s, r, own), (const uint8_t *)send + off[r], len[r]);
         s.written[(size_t)r * p + own] = 1;
         bruck_have[r] = 1;
         if (algo == ORACLE_SPARBIT && p > 1)
@@ -461,6 +464,7 @@ int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, in
 
     if (algo == ORACLE_BRUCK && max_steps == nsteps) {
         /* local memory shift: working slot i of rank r is block (r + i) mod p */
+        const size_t B = uniform_block;
         uint8_t *row = (uint8_t *)malloc((size_t)p * B);
         if (!row) {
             rc = ORACLE_ERR_NOMEM;
@@ -487,6 +491,83 @@ out:
     free(sv);
     free(bruck_have);
     return rc;
+}
+
+/*
+ * MPI_Allgather: run `algo` for p ranks with blocks of B bytes.
+ *   send      p blocks (rank r at byte r*B), or NULL for in-place: recv[r][r]
+ *             already holds rank r's block.
+ *   recv      p*p blocks, rank r's buffer at byte r*p*B.  Slots that are never
+ *             written keep whatever the caller put there (poison).
+ *   max_steps run only the first max_steps communication steps (negative =
+ *             all).  Bruck's final rotation happens only when all steps ran.
+ *   step_info optional, [num_steps][3] int32: per step the distance d, the
+ *             ignore flag (Sparbit; 0 otherwise) and the number of blocks rank
+ *             0 sent.
+ *   sent_per_rank optional, [p] int64: total blocks each rank sent.
+ *   trace     optional, rows of 5 int32 (step, src, dst, src_slot, dst_slot),
+ *             one per delivered message; trace_cap rows available, *trace_len
+ *             receives the number written.
+ * Returns ORACLE_OK or a negative ORACLE_ERR_* code.
+ */
+int oracle_allgather(int algo, int p, size_t B, const void *send, void *recv, int max_steps,
+                     int32_t *step_info, int64_t *sent_per_rank, int32_t *trace, size_t trace_cap,
+                     size_t *trace_len)
+{
+    size_t *off, *len;
+    int k, rc;
+    if (p < 1 || B == 0 || !recv)
+        return ORACLE_ERR_ARG;
+    if (algo == ORACLE_NAIVE)
+        return oracle_naive_allgather(p, B, send, recv);
+    off = (size_t *)malloc((size_t)p * sizeof(size_t));
+    len = (size_t *)malloc((size_t)p * sizeof(size_t));
+    if (!off || !len) {
+        free(off);
+        free(len);
+        return ORACLE_ERR_NOMEM;
+    }
+    for (k = 0; k < p; k++) {
+        off[k] = (size_t)k * B;
+        len[k] = B;
+    }
+    rc = run_schedule(algo, p, (size_t)p * B, off, len, B, send, recv, max_steps, step_info,
+                      sent_per_rank, trace, trace_cap, trace_len);
+    free(off);
+    free(len);
+    return rc;
+}
+
+/*
+ * MPI_Allgatherv over the same schedules (the extension the paper's
+ * conclusion names): rank k contributes counts[k] bytes (zero allowed), which
+ * land at byte displs[k] of every receive buffer; receive buffers are
+ * row_bytes apart; the send buffer is laid out like one receive buffer (rank
+ * r's block at displs[r]) or NULL for in place.  Bytes of a receive buffer
+ * that belong to no block are never touched.  Bruck is not defined here (its
+ * rotated buffer assumes equal blocks).  ORACLE_NAIVE gives the definition.
+ */
+int oracle_allgatherv(int algo, int p, const size_t *counts, const size_t *displs, size_t row_bytes,
+                      const void *send, void *recv, int max_steps, int32_t *step_info,
+                      int64_t *sent_per_rank, int32_t *trace, size_t trace_cap, size_t *trace_len)
+{
+    int r, k;
+    if (p < 1 || !counts || !displs || !recv)
+        return ORACLE_ERR_ARG;
+    for (k = 0; k < p; k++)
+        if (displs[k] + counts[k] > row_bytes)
+            return ORACLE_ERR_ARG;
+    if (algo == ORACLE_NAIVE) {
+        if (!send)
+            return ORACLE_ERR_ARG;
+        for (r = 0; r < p; r++)
+            for (k = 0; k < p; k++)
+                memcpy((uint8_t *)recv + (size_t)r * row_bytes + displs[k],
+                       (const uint8_t *)send + displs[k], counts[k]);
+        return ORACLE_OK;
+    }
+    return run_schedule(algo, p, row_bytes, displs, counts, 0, send, recv, max_steps, step_info,
+                        sent_per_rank, trace, trace_cap, trace_len);
 }
 
 const char *oracle_strerror(int code)

@@ -11,7 +11,7 @@ _BINDING_NAMES = {
     "MODE_AUTO", "MODE_PER_STEP", "MODE_PERSISTENT", "MODE_DATAFLOW",
     "SparbitError", "Plan", "lib", "lib_path",
     "sparbit_allgather", "sparbit_allgather_algo", "sparbit_allgather_steps",
-    "sparbit_allgather_mode", "sparbit_finalize", "sparbit_strerror",
+    "sparbit_allgather_mode", "sparbit_allgatherv", "sparbit_finalize", "sparbit_strerror",
     "sparbit_tune", "sparbit_barrier_timeouts", "ALGOS",
 }
 

@@ -61,6 +61,7 @@ def _load() -> ctypes.CDLL:
     L.sparbit_allgather_algo.argtypes = [vp, vp, ci, sz, ci, vp]
     L.sparbit_allgather_mode.argtypes = [vp, vp, ci, sz, ci, ci, vp]
     L.sparbit_allgather_steps.argtypes = [vp, vp, ci, sz, ci, ci, ci, vp]
+    L.sparbit_allgatherv.argtypes = [vp, vp, ci, vp, vp, sz, ci, vp]
     L.sparbit_plan_create.argtypes = [ci, ci, ctypes.POINTER(vp)]
     L.sparbit_plan_num_steps.argtypes = [vp]
     L.sparbit_plan_step.argtypes = [vp, ci, ctypes.POINTER(_Step)]
@@ -74,7 +75,7 @@ def _load() -> ctypes.CDLL:
     L.sparbit_tune.argtypes = [ctypes.c_char_p, ctypes.c_longlong]
     L.sparbit_barrier_timeouts.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
     for name in ("sparbit_allgather", "sparbit_allgather_algo", "sparbit_allgather_mode",
-                 "sparbit_allgather_steps", "sparbit_plan_create", "sparbit_plan_num_steps",
+                 "sparbit_allgather_steps", "sparbit_allgatherv", "sparbit_plan_create", "sparbit_plan_num_steps",
                  "sparbit_plan_step", "sparbit_last_hip_error", "sparbit_tune",
                  "sparbit_barrier_timeouts"):
         getattr(L, name).restype = ci
@@ -136,6 +137,16 @@ def sparbit_allgather_steps(sendbufs, recvbufs, p: int, block_bytes: int, algo: 
     _check(lib.sparbit_allgather_steps(_ptr(sendbufs), _ptr(recvbufs), p, block_bytes, algo,
                                        first_step, last_step, _stream(stream)),
            "sparbit_allgather_steps")
+
+
+def sparbit_allgatherv(sendbufs, recvbufs, p: int, counts, displs, row_bytes: int, algo: int = SPARBIT,
+                       stream=None) -> None:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    d = np.ascontiguousarray(displs, dtype=np.uint64)
+    if c.shape != (p,) or d.shape != (p,):
+        raise ValueError("counts and displs need p entries")
+    _check(lib.sparbit_allgatherv(_ptr(sendbufs), _ptr(recvbufs), p, c.ctypes.data, d.ctypes.data, row_bytes,
+                                  algo, _stream(stream)), "sparbit_allgatherv")
 
 
 def sparbit_finalize() -> None:

@@ -2,6 +2,7 @@
 // tables, and the launches.  See include/sparbit.h for the contract.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstring>
 #include <map>
@@ -50,6 +51,15 @@ struct DevicePlan {
     DevPhase* d_phases_in_place = nullptr; // phases of an in-place call
     std::vector<uint32_t> first_copy;      // per host phase
     std::vector<DevPhase> out_of_place, in_place;
+    DevicePlan() = default;
+    DevicePlan(const DevicePlan&) = delete;
+    DevicePlan& operator=(const DevicePlan&) = delete;
+    ~DevicePlan()  // the owning device is current when plans are destroyed (finalize, or a failed build)
+    {
+        (void)hipFree(d_copies);
+        (void)hipFree(d_phases);
+        (void)hipFree(d_phases_in_place);
+    }
 };
 
 struct FlowStream {  // per-stream state of the dataflow kernel
@@ -59,9 +69,31 @@ struct FlowStream {  // per-stream state of the dataflow kernel
     uint32_t epoch = 0;  // last call number handed out (0 is never used: fresh flags are 0)
 };
 
+// Allgatherv: explicit byte-offset copy lists for one (schedule, p, counts, displs, row_bytes).
+struct VarPhase {
+    Buffer src_buf, dst_buf;
+    uint32_t first, ncopies;
+    uint64_t max_len;
+};
+
+struct VarPlan {
+    int algo = 0, p = 0;
+    size_t row_bytes = 0;
+    std::vector<size_t> counts, displs;
+    std::vector<VarPhase> out_of_place, in_place;
+    VarCopy* d_copies = nullptr;
+    uint64_t last_use = 0;
+    VarPlan() = default;
+    VarPlan(const VarPlan&) = delete;
+    VarPlan& operator=(const VarPlan&) = delete;
+    ~VarPlan() { (void)hipFree(d_copies); }
+};
+
 struct DeviceState {
     int device = -1;
     int num_cus = 0;
+    std::vector<std::unique_ptr<VarPlan>> var_plans;  // small most-recently-used cache
+    uint64_t var_clock = 0;
     std::map<hipStream_t, FlowStream> flows;
     std::map<std::pair<int, int>, std::unique_ptr<DevicePlan>> plans;  // (algo, p)
     std::map<hipStream_t, BarrierState*> barriers;
@@ -293,7 +325,8 @@ int launch_persistent_v(const PersistentArgs& a, int num_cus, uint64_t max_tiles
     long long want = g_wgs_per_cu.load();
     if (want < 1) want = 1;
     if (per_cu < 1) return SPARBIT_ERR_HIP;
-    if (want > per_cu) want = per_cu;
+    const int half = per_cu > 1 ? per_cu / 2 : 1;
+    if (want > half) want = half;  // every workgroup must be resident, and the rest of the GPU stays usable
     uint64_t grid = uint64_t(num_cus) * uint64_t(want);
     if (grid > max_tiles) grid = max_tiles ? max_tiles : 1;  // no more workgroups than the largest phase has tiles
     if (nt)
@@ -311,11 +344,145 @@ int launch_dataflow_v(const FlowArgs& a, int num_cus, hipStream_t stream)
     SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dataflow_kernel<V>, WG, 0));
     if (per_cu < 1) return SPARBIT_ERR_HIP;
     long long want = g_flow_wgs_per_cu.load();
-    if (want > per_cu) want = per_cu;  // every workgroup must be resident
+    const int half = per_cu > 1 ? per_cu / 2 : 1;
+    if (want > half) want = half;  // every workgroup must be resident, and the rest of the GPU stays usable
     uint64_t grid = uint64_t(num_cus) * uint64_t(want);
     if (grid > a.total_items) grid = a.total_items;
     hipLaunchKernelGGL((dataflow_kernel<V>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
     SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb);
+
+constexpr size_t kVarPlanCacheSize = 8;
+
+// Look up or build the copy lists of an Allgatherv geometry.  Block index b of a
+// receive-side buffer means (rank b / p, slot b % p); of the send buffer, rank b.
+int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t* counts, const size_t* displs,
+                 size_t row_bytes, VarPlan** out)
+{
+    for (auto& vp : ds->var_plans) {
+        if (vp->algo == algo && vp->p == p && vp->row_bytes == row_bytes &&
+            std::memcmp(vp->counts.data(), counts, size_t(p) * sizeof(size_t)) == 0 &&
+            std::memcmp(vp->displs.data(), displs, size_t(p) * sizeof(size_t)) == 0) {
+            vp->last_use = ++ds->var_clock;
+            *out = vp.get();
+            return SPARBIT_OK;
+        }
+    }
+    auto vp = std::make_unique<VarPlan>();
+    vp->algo = algo;
+    vp->p = p;
+    vp->row_bytes = row_bytes;
+    vp->counts.assign(counts, counts + p);
+    vp->displs.assign(displs, displs + p);
+    std::vector<VarCopy> all;
+    for (const Phase& ph : dp->host.phases) {
+        VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), 0u, 0u};
+        for (const Copy& c : ph.copies) {
+            const uint32_t slot = c.dst_block % uint32_t(p);  // the destination always names the slot
+            if (counts[slot] == 0) continue;
+            VarCopy vc;
+            vc.src_off = ph.src_buf == BUF_SEND ? displs[c.src_block]
+                                                : uint64_t(c.src_block / uint32_t(p)) * row_bytes + displs[c.src_block % uint32_t(p)];
+            vc.dst_off = uint64_t(c.dst_block / uint32_t(p)) * row_bytes + displs[slot];
+            vc.len = counts[slot];
+            vc.pad = 0;
+            all.push_back(vc);
+            if (vc.len > v.max_len) v.max_len = vc.len;
+        }
+        v.ncopies = uint32_t(all.size()) - v.first;
+        if (v.ncopies == 0) continue;
+        if (!ph.only_in_place && !ph.covered_by_fused) vp->out_of_place.push_back(v);
+        if (!ph.skip_in_place) vp->in_place.push_back(v);
+    }
+    if (!all.empty()) {
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&vp->d_copies), all.size() * sizeof(VarCopy)));
+        SB_HIP(hipMemcpy(vp->d_copies, all.data(), all.size() * sizeof(VarCopy), hipMemcpyHostToDevice));
+    }
+    if (ds->var_plans.size() >= kVarPlanCacheSize) {
+        // Evict the least recently used geometry; its table may still be read by queued launches.
+        SB_HIP(hipDeviceSynchronize());
+        size_t victim = 0;
+        for (size_t i = 1; i < ds->var_plans.size(); ++i)
+            if (ds->var_plans[i]->last_use < ds->var_plans[victim]->last_use) victim = i;
+        ds->var_plans.erase(ds->var_plans.begin() + victim);
+    }
+    vp->last_use = ++ds->var_clock;
+    *out = vp.get();
+    ds->var_plans.push_back(std::move(vp));
+    return SPARBIT_OK;
+}
+
+template <typename V>
+int launch_var(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t ncopies, uint64_t max_len,
+               hipStream_t stream)
+{
+    const uint64_t tiles = (max_len / sizeof(V) + WG - 1) / WG;
+    if (tiles == 0 || ncopies == 0) return SPARBIT_OK;
+    uint32_t lg_g = uint32_t(g_interleave_log2.load());
+    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;
+    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
+    const uint32_t gy = groups < 32768u ? groups : 32768u;
+    const uint32_t gz = (groups + gy - 1) / gy;
+    if ((tiles << lg_g) > 0x7fffffffull / WG || gz > 65535u) return SPARBIT_ERR_ARG;
+    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
+    if (g_nontemporal.load() != 0)
+        hipLaunchKernelGGL((copy_var_kernel<V, true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
+    else
+        hipLaunchKernelGGL((copy_var_kernel<V, false>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, const size_t* displs, size_t row_bytes,
+          int algo, void* stream_v)
+{
+    if (p < 1 || p > SPARBIT_MAX_P || !recvbufs || !counts || !displs) return SPARBIT_ERR_ARG;
+    if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
+    if (algo == SPARBIT_ALGO_BRUCK) return SPARBIT_ERR_UNSUPPORTED;  // its rotated buffer assumes equal blocks
+    if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING && (p & (p - 1))) return SPARBIT_ERR_UNSUPPORTED;
+    if ((unsigned __int128)row_bytes * unsigned(p) > (unsigned __int128)0x7fffffffffffffffull) return SPARBIT_ERR_ARG;
+    uintptr_t bits = uintptr_t(sendbufs) | uintptr_t(recvbufs) | uintptr_t(row_bytes);
+    std::vector<std::pair<size_t, size_t>> spans;  // (start, end) of the non-empty blocks
+    for (int k = 0; k < p; ++k) {
+        if (displs[k] > row_bytes || counts[k] > row_bytes - displs[k]) return SPARBIT_ERR_ARG;
+        if (counts[k]) {
+            bits |= uintptr_t(displs[k]) | uintptr_t(counts[k]);
+            spans.emplace_back(displs[k], displs[k] + counts[k]);
+        }
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)  // blocks of one receive buffer must not overlap
+        if (spans[i].first < spans[i - 1].second) return SPARBIT_ERR_ARG;
+    const bool any = !spans.empty();
+    const bool in_place = sendbufs == nullptr;
+    if (!in_place && ranges_overlap(sendbufs, row_bytes, recvbufs, size_t(p) * row_bytes)) return SPARBIT_ERR_ALIAS;
+    if (!any) return SPARBIT_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* ds = nullptr;
+    int rc = get_device_state(&ds);
+    if (rc != SPARBIT_OK) return rc;
+    DevicePlan* dp = nullptr;
+    if ((rc = get_plan(ds, algo, p, &dp)) != SPARBIT_OK) return rc;
+    VarPlan* vp = nullptr;
+    if ((rc = get_var_plan(ds, dp, algo, p, counts, displs, row_bytes, &vp)) != SPARBIT_OK) return rc;
+    const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs), nullptr};
+    const int width = (bits & 15) == 0 ? 16 : (bits & 3) == 0 ? 4 : 1;
+    for (const VarPhase& ph : in_place ? vp->in_place : vp->out_of_place) {
+        const uint8_t* src = base[ph.src_buf];
+        uint8_t* dst = const_cast<uint8_t*>(base[ph.dst_buf]);
+        const VarCopy* copies = vp->d_copies + ph.first;
+        switch (width) {
+        case 16: rc = launch_var<u32x4>(src, dst, copies, ph.ncopies, ph.max_len, stream); break;
+        case 4: rc = launch_var<uint32_t>(src, dst, copies, ph.ncopies, ph.max_len, stream); break;
+        default: rc = launch_var<uint8_t>(src, dst, copies, ph.ncopies, ph.max_len, stream); break;
+        }
+        if (rc != SPARBIT_OK) return rc;
+    }
     return SPARBIT_OK;
 }
 
@@ -483,6 +650,12 @@ int sparbit_allgather_mode(const void* sendbufs, void* recvbufs, int p, size_t b
     return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, mode, true, 0, 0, stream);
 }
 
+int sparbit_allgatherv(const void* sendbufs, void* recvbufs, int p, const size_t* counts, const size_t* displs,
+                       size_t row_bytes, int algo, void* stream)
+{
+    return sparbit::run_v(sendbufs, recvbufs, p, counts, displs, row_bytes, algo, stream);
+}
+
 int sparbit_allgather_steps(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, int first_step,
                             int last_step, void* stream)
 {
@@ -498,11 +671,8 @@ void sparbit_finalize(void)
     for (auto& kv : sparbit::g_devices) {
         sparbit::DeviceState* ds = kv.second.get();
         if (hipSetDevice(ds->device) != hipSuccess) continue;
-        for (auto& pk : ds->plans) {
-            (void)hipFree(pk.second->d_copies);
-            (void)hipFree(pk.second->d_phases);
-            (void)hipFree(pk.second->d_phases_in_place);
-        }
+        ds->plans.clear();  // frees the device tables while this device is current
+        ds->var_plans.clear();
         for (auto& bk : ds->barriers) (void)hipFree(bk.second);
         for (auto& fk : ds->flows) {
             (void)hipFree(fk.second.state);

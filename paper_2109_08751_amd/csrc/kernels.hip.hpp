@@ -73,6 +73,39 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
 }
 
 // ---------------------------------------------------------------------------
+// Blocks of different sizes (Allgatherv): every copy carries its own byte
+// offsets and length.  Same shape as copy_tiles_kernel -- one tile per
+// workgroup, copies dealt round-robin to consecutive workgroups -- with the
+// grid's x extent sized for the longest block of the phase; workgroups past
+// the end of a shorter block exit at once.  V is the access width that all
+// offsets, lengths and base addresses of the call allow.
+// ---------------------------------------------------------------------------
+struct VarCopy {
+    uint64_t src_off;  // bytes from the phase's source base
+    uint64_t dst_off;  // bytes from the phase's destination base
+    uint64_t len;      // bytes
+    uint64_t pad;
+};
+
+template <typename V, bool NT>
+__global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict__ src_base,
+                                                      uint8_t* __restrict__ dst_base,
+                                                      const VarCopy* __restrict__ copies, uint32_t ncopies,
+                                                      uint32_t lg_g)
+{
+    const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
+    const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
+    if (c >= ncopies) return;
+    const VarCopy cp = copies[c];
+    const uint64_t v = uint64_t(blockIdx.x >> lg_g) * WG + threadIdx.x;
+    if (v < cp.len / sizeof(V)) {
+        const V* __restrict__ s = reinterpret_cast<const V*>(src_base + cp.src_off);
+        V* __restrict__ d = reinterpret_cast<V*>(dst_base + cp.dst_off);
+        st<V, NT>(d + v, ld<V, NT>(s + v));
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Small or odd-sized blocks: the (copy, element) space is flattened and every
 // lane finds its copy by one division, so a workgroup's tile may span many
 // short blocks.  V is the access width the alignment allows.

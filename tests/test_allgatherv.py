@@ -1,0 +1,191 @@
+"""Allgatherv (blocks of different sizes; the extension named in the paper's
+conclusion): oracle pins on the CPU, host-side argument checks of the C-ABI,
+and GPU parity against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2109_08751_amd as sb
+from paper_2109_08751_amd import binding, workloads
+
+POISON = workloads.POISON
+
+
+def geometry(p, seed, align=1, max_len=40, gaps=True, shuffle=True):
+    """Random block sizes (some zero), displacements with gaps and in shuffled order."""
+    rng = np.random.default_rng(seed)
+    counts = rng.integers(0, max_len // align + 1, p) * align
+    if p > 2:
+        counts[rng.integers(0, p)] = 0
+    order = rng.permutation(p) if shuffle else np.arange(p)
+    displs = np.zeros(p, dtype=np.int64)
+    at = 0
+    for k in order:
+        at += int(rng.integers(0, 3)) * align if gaps else 0
+        displs[k] = at
+        at += int(counts[k])
+    row = at + (align * int(rng.integers(0, 3)) if gaps else 0)
+    row = max(row, align)
+    return counts.astype(np.uint64), displs.astype(np.uint64), int(row)
+
+
+def payload(row, seed):
+    return workloads.make_send_raw(1, row, seed).reshape(row)
+
+
+def definition(p, counts, displs, row, send):
+    """MPI_Allgatherv by definition: block k of the send layout lands at
+    displs[k] of every receive buffer; everything else is untouched."""
+    want = np.full((p, row), POISON, dtype=np.uint8)
+    for r in range(p):
+        for k in range(p):
+            d, c = int(displs[k]), int(counts[k])
+            want[r, d:d + c] = send[d:d + c]
+    return want
+
+
+@pytest.mark.parametrize("p", list(range(1, 34)) + [64, 96, 257])
+def test_oracle_allgatherv_equals_definition(p):
+    for algo in (oracle.SPARBIT, oracle.RING, oracle.NAIVE):
+        counts, displs, row = geometry(p, seed=p * 3 + algo)
+        send = payload(row, p)
+        recv = np.full((p, row), POISON, dtype=np.uint8)
+        oracle.allgatherv(algo, p, counts, displs, row, send, recv)
+        assert np.array_equal(recv, definition(p, counts, displs, row, send)), (algo, p)
+
+
+@pytest.mark.parametrize("p", [1, 2, 5, 6, 21, 64, 96])
+def test_oracle_allgatherv_with_equal_blocks_is_allgather(p):
+    """Same schedule, same messages: with counts = B and displs = k*B the
+    result, every step boundary and the message log equal the Allgather run."""
+    B = 6
+    counts = np.full(p, B, dtype=np.uint64)
+    displs = np.arange(p, dtype=np.uint64) * B
+    send = workloads.make_send_raw(p, B, seed=p)
+    for steps in range(-1, oracle.num_steps(oracle.SPARBIT, p) + 1):
+        a = np.full((p, p, B), POISON, dtype=np.uint8)
+        b = np.full((p, p * B), POISON, dtype=np.uint8)
+        ra = oracle.allgather(oracle.SPARBIT, p, B, send, a, steps, want_trace=True)
+        rb = oracle.allgatherv(oracle.SPARBIT, p, counts, displs, p * B, send.reshape(-1), b, steps, want_trace=True)
+        assert np.array_equal(a.reshape(p, p * B), b)
+        assert np.array_equal(ra.trace, rb.trace) and np.array_equal(ra.step_info, rb.step_info)
+
+
+@pytest.mark.parametrize("p", [2, 5, 21, 33])
+def test_oracle_allgatherv_message_log_does_not_depend_on_sizes(p):
+    counts, displs, row = geometry(p, seed=p)
+    recv = np.full((p, row), POISON, dtype=np.uint8)
+    rv = oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, payload(row, 1), recv, want_trace=True)
+    ru = oracle.allgather(oracle.SPARBIT, p, 1, np.zeros((p, 1), np.uint8), np.zeros((p, p, 1), np.uint8),
+                          want_trace=True)
+    assert np.array_equal(rv.trace, ru.trace)
+    assert (rv.sent_per_rank == p - 1).all()
+
+
+def test_oracle_allgatherv_in_place_and_rejections():
+    p = 7
+    counts, displs, row = geometry(p, seed=11)
+    send = payload(row, 2)
+    recv = np.full((p, row), POISON, dtype=np.uint8)
+    for r in range(p):
+        d, c = int(displs[r]), int(counts[r])
+        recv[r, d:d + c] = send[d:d + c]
+    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None, recv)
+    assert np.array_equal(recv, definition(p, counts, displs, row, send))
+    with pytest.raises(oracle.OracleError):  # Bruck's rotated buffer needs equal blocks
+        oracle.allgatherv(oracle.BRUCK, p, counts, displs, row, send, recv)
+    bad = counts.copy()
+    bad[0] = row + 1
+    with pytest.raises(oracle.OracleError):
+        oracle.allgatherv(oracle.SPARBIT, p, bad, displs, row, send, recv)
+
+
+def test_allgatherv_arguments_are_checked_on_the_host():
+    L = binding.lib
+    import ctypes
+    def call(p, counts, displs, row, algo=0, send=0x1000, recv=0x100000):
+        c = (ctypes.c_size_t * len(counts))(*counts)
+        d = (ctypes.c_size_t * len(displs))(*displs)
+        return L.sparbit_allgatherv(send, recv, p, c, d, row, algo, None)
+    assert call(0, [1], [0], 8) == -1
+    assert call(2, [4, 5], [0, 4], 8) == -1           # block 1 runs past the row
+    assert call(2, [4, 4], [0, 2], 8) == -1           # blocks overlap
+    assert call(3, [4, 4, 4], [0, 4, 8], 12, algo=sb.BRUCK) == -3
+    assert call(3, [4, 4, 4], [0, 4, 8], 12, algo=sb.RECURSIVE_DOUBLING) == -3
+    assert call(2, [4, 4], [0, 4], 8, send=0x100004) == -2   # send overlaps the receive buffers
+    assert call(2, [0, 0], [0, 0], 8) == 0            # nothing to move
+    assert L.sparbit_allgatherv(0x1000, 0x100000, 2, None, None, 8, 0, None) == -1
+
+
+# ------------------------------------------------------------------ GPU parity
+def gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=False, misalign=0):
+    dev = torch.device("cuda:0")
+    sraw = torch.empty(row + 64, dtype=torch.uint8, device=dev)
+    rraw = torch.full((p * row + 64,), POISON, dtype=torch.uint8, device=dev)
+    d_send = sraw[misalign:misalign + row]
+    d_recv = rraw[misalign:misalign + p * row]
+    d_send.copy_(torch.from_numpy(send))
+    if in_place:
+        v = d_recv.view(p, row)
+        for r in range(p):
+            d, c = int(displs[r]), int(counts[r])
+            v[r, d:d + c] = d_send[d:d + c]
+    sb.sparbit_allgatherv(None if in_place else d_send, d_recv, p, counts, displs, row, algo)
+    torch.cuda.synchronize()
+    assert bool((rraw[:misalign] == POISON).all()) and bool((rraw[misalign + p * row:] == POISON).all())
+    return d_recv.cpu().numpy().reshape(p, row)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_matches_oracle():
+    import torch
+    algos = {sb.SPARBIT: oracle.SPARBIT, sb.RING: oracle.RING, sb.RECURSIVE_DOUBLING: oracle.RECURSIVE_DOUBLING,
+             sb.DIRECT: oracle.NAIVE}
+    for p in list(range(1, 18)) + [21, 32, 33, 64, 96, 257]:
+        for align, max_len in ((1, 40), (4, 400), (16, 9000)):
+            counts, displs, row = geometry(p, seed=p * 10 + align, align=align, max_len=max_len)
+            send = payload(row, p)
+            for algo, oalgo in algos.items():
+                if algo == sb.RECURSIVE_DOUBLING and p & (p - 1):
+                    continue
+                if algo == sb.RING and p > 64:
+                    continue
+                print("[case] allgatherv", p, align, algo, flush=True)
+                want = np.full((p, row), POISON, dtype=np.uint8)
+                oracle.allgatherv(oalgo, p, counts, displs, row, send, want)
+                got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
+                assert np.array_equal(got, want), (p, align, algo)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_in_place_misaligned_and_cached_geometries():
+    import torch
+    for rep in range(2):  # the second pass hits the geometry cache, then evicts through it
+        for p in (5, 6, 21, 33, 64, 7, 9, 11, 13, 15):
+            counts, displs, row = geometry(p, seed=p, align=4, max_len=600)
+            send = payload(row, p + rep)
+            want = np.full((p, row), POISON, dtype=np.uint8)
+            for r in range(p):
+                d, c = int(displs[r]), int(counts[r])
+                want[r, d:d + c] = send[d:d + c]
+            oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None, want)
+            got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=True, misalign=4 * rep)
+            assert np.array_equal(got, want), (rep, p)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_large_unequal_blocks():
+    """Blocks from 0 bytes to 3 MiB in one call (several tiles, ragged tails)."""
+    import torch
+    p = 12
+    rng = np.random.default_rng(5)
+    counts = (rng.integers(0, 200000, p) * 16).astype(np.uint64)
+    counts[3] = 0
+    counts[7] = 16
+    displs = np.concatenate([[0], np.cumsum(counts[:-1] + 32)]).astype(np.uint64)
+    row = int(displs[-1] + counts[-1] + 48)
+    send = np.tile(workloads.make_send_raw(1, 65536, 9).reshape(-1), row // 65536 + 1)[:row].copy()
+    want = np.full((p, row), POISON, dtype=np.uint8)
+    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, send, want)
+    got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send)
+    assert np.array_equal(got, want)
