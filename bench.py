@@ -33,9 +33,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
 # HBM bytes per launch of the step kernel, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (one run each,
-# scaled by a plain 1 GiB copy through the same kernel); figures and commands: profiles/copy_tiles_kernel_cfg4.md.
+# scaled by a plain 1 GiB copy through the same kernel); figures and commands: profiles/copy_tiles_kernel_cfg4.md
+# and profiles/copy_tiles_kernel_cfg5.md.
 # Only meaningful for the default tuning and issue mode of that workload.
-MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16779072 + 16763447) * 1024}
+MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16769301 + 16764538) * 1024, "cfg5": (16916832 + 16890399) * 1024}
 
 
 def parse_args():
@@ -250,15 +251,17 @@ def main():
             s_ = d_send if name == w.name else make_device_send(torch, wc, dev)
             r_ = torch.full((pc, pc, Bc), workloads.POISON, dtype=torch.uint8, device=dev)
             row = {"p": pc, "block_bytes": Bc}
-            algos = [("sparbit", sb.SPARBIT), ("direct", sb.DIRECT)]
-            if name in ("cfg2", "cfg3", "cfg4", "cfg5"):
-                algos += [("bruck", sb.BRUCK)]
-                if pc & (pc - 1) == 0:
-                    algos += [("recursive_doubling", sb.RECURSIVE_DOUBLING)]
+            algos = [("sparbit", sb.SPARBIT, sb.MODE_AUTO), ("direct", sb.DIRECT, sb.MODE_AUTO)]
             if name in ("cfg1", "cfg2", "cfg3"):
-                algos += [("ring", sb.RING)]
-            for label, algo in algos:
-                fn = lambda a=algo: sb.sparbit_allgather_mode(s_, r_, pc, Bc, a, sb.MODE_AUTO, stream)
+                algos += [("sparbit_dataflow", sb.SPARBIT, sb.MODE_DATAFLOW)]
+            if name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+                algos += [("bruck", sb.BRUCK, sb.MODE_AUTO)]
+                if pc & (pc - 1) == 0:
+                    algos += [("recursive_doubling", sb.RECURSIVE_DOUBLING, sb.MODE_AUTO)]
+            if name in ("cfg1", "cfg2", "cfg3"):
+                algos += [("ring", sb.RING, sb.MODE_AUTO)]
+            for label, algo, md in algos:
+                fn = lambda a=algo, m=md: sb.sparbit_allgather_mode(s_, r_, pc, Bc, a, m, stream)
                 t = time_calls(torch, fn, stream, 5, 20)
                 row[label] = {**t, **rates(pc, Bc, t["avg_ms"])}
                 good = bool(torch.equal(r_[pc - 1], s_))
@@ -271,6 +274,23 @@ def main():
             per[name] = row
             del r_, dst, s_
             torch.cuda.empty_cache()
+        # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB)
+        import numpy as np
+        pv = 128
+        rng = np.random.default_rng(workloads.DEFAULT_SEED)
+        counts = (rng.integers(512 << 10, (1536 << 10) + 1, pv) // 4096 * 4096).astype(np.uint64)
+        displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)
+        row = int(counts.sum())
+        s_ = torch.randint(0, 256, (row,), dtype=torch.uint8, device=dev)
+        r_ = torch.full((pv, row), workloads.POISON, dtype=torch.uint8, device=dev)
+        t = time_calls(torch, lambda: sb.sparbit_allgatherv(s_, r_, pv, counts, displs, row, sb.SPARBIT, stream),
+                       stream, 3, 10)
+        per["allgatherv_p128_0.5-1.5MiB"] = {
+            "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6,
+            "hbm_GBps": 2 * pv * row / t["avg_ms"] / 1e6, "hbm_frac": 2 * pv * row / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+            "ok": bool(torch.equal(r_[pv - 1], s_))}
+        del s_, r_
+        torch.cuda.empty_cache()
         out["per_config"] = per
         assert sb.sparbit_barrier_timeouts(stream) == 0
 
