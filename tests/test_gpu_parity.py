@@ -235,3 +235,70 @@ def test_full_size_configs(torch, cfg):
     rng = np.random.default_rng(7)
     for r, k in zip(rng.integers(0, p, 24), rng.integers(0, p, 24)):
         assert np.array_equal(d_recv[r, k].cpu().numpy(), send[origin[r, k]])
+
+
+# ------------------------------------------------------------------ library life cycle
+def test_finalize_then_reuse(torch):
+    """sparbit_finalize drops every cache; the next call rebuilds them."""
+    w = workloads.WORKLOADS["cfg1"]
+    send = workloads.make_send(w)
+    want = oracle_result(sb.SPARBIT, w.p, w.block_bytes, send)
+    for _ in range(2):
+        for mode in ("per_step", "persistent", "dataflow"):
+            assert np.array_equal(gpu_result(torch, sb.SPARBIT, w.p, w.block_bytes, send, MODES[mode]), want)
+        torch.cuda.synchronize()
+        sb.sparbit_finalize()
+
+
+def test_two_host_threads(torch):
+    """Two host threads, each with its own stream and buffers, call concurrently."""
+    import threading
+    w = workloads.WORKLOADS["cfg3"]
+    send = workloads.make_send(w)
+    want = oracle_result(sb.SPARBIT, w.p, w.block_bytes, send)
+    results, errors = {}, []
+
+    def worker(i):
+        try:
+            st = torch.cuda.Stream()
+            d_send, d_recv, _ = gpu_buffers(torch, w.p, w.block_bytes, send)
+            torch.cuda.synchronize()
+            for _ in range(20):
+                sb.sparbit_allgather_mode(d_send, d_recv, w.p, w.block_bytes, sb.SPARBIT, sb.MODE_PER_STEP, st)
+            st.synchronize()
+            results[i] = d_recv.cpu().numpy().reshape(want.shape)
+        except Exception as e:  # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    for i in range(2):
+        assert np.array_equal(results[i], want)
+
+
+def test_capture_in_a_hip_graph(torch):
+    """Once the tables of (schedule, p) are cached a per-step call allocates
+    nothing and enqueues only kernels, so it can be captured; every replay must
+    reproduce the eager result, with eager work and synchronisation in between."""
+    w = workloads.WORKLOADS["cfg3"]
+    p, B = w.p, w.block_bytes
+    send = workloads.make_send(w)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_PER_STEP, st)  # builds the tables
+        st.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_PER_STEP, torch.cuda.current_stream())
+    for rep in range(3):
+        d_recv.fill_(POISON)          # eager work between replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
