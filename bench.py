@@ -221,7 +221,8 @@ def main():
     nsteps = sb.Plan(p).num_steps
     launches = 1 if (mode == sb.MODE_PERSISTENT) else nsteps  # own blocks + step 0 share the first launch
     out = {
-        "metric": "effective Allgather GB/s (p*p*block_bytes landed / time), Sparbit schedule",
+        "metric": "effective Allgather GB/s (p*p*block_bytes landed / time; % of MI355X peak HBM BW in "
+                  "roofline.frac), Sparbit schedule, per p and block size",
         "value": r["effective_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["avg_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
