@@ -302,3 +302,15 @@ def test_capture_in_a_hip_graph(torch):
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
+
+
+def test_maximum_rank_count(torch):
+    """p = SPARBIT_MAX_P (4096): 16.7 million block copies in 12 steps."""
+    p, B = 4096, 16
+    announce("p=4096")
+    send = workloads.make_send_raw(p, B, seed=8)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    assert np.array_equal(want, np.broadcast_to(send[None], (p, p, B)))
+    got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_PER_STEP)
+    assert np.array_equal(got, want)
+    sb.sparbit_finalize()  # drop the 134 MB table

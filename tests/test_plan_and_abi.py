@@ -132,3 +132,17 @@ def test_blocks_per_step_of_the_five_configs(p, want):
 
 def test_direct_plan_has_no_steps():
     assert sb.Plan(7, sb.DIRECT).num_steps == 0
+
+
+def test_plan_at_the_maximum_rank_count():
+    """p = SPARBIT_MAX_P: 12 steps, blocks per step from the comb closed form, p - 1 in total;
+    one more rank is refused."""
+    plan = sb.Plan(4096)
+    got = [plan.step(s)["nblocks"] for s in range(plan.num_steps)]
+    assert got == [2 ** s for s in range(12)] and sum(got) == 4095
+    last = plan.step(11)
+    assert last["distance"] == 1 and last["send_slot"].shape == (4096, 2048)
+    assert np.array_equal(last["send_slot"][5, :3], [5, 3, 1])
+    plan.close()
+    with pytest.raises(sb.SparbitError):
+        sb.Plan(4097)
