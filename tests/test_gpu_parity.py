@@ -236,6 +236,20 @@ def test_full_size_configs(torch, cfg):
     for r, k in zip(rng.integers(0, p, 24), rng.integers(0, p, 24)):
         assert np.array_equal(d_recv[r, k].cpu().numpy(), send[origin[r, k]])
 
+    # With enough host memory: the oracle itself at full size, every byte compared.
+    avail = 0
+    for line in open("/proc/meminfo"):
+        if line.startswith("MemAvailable:"):
+            avail = int(line.split()[1]) * 1024
+    if avail < 3 * w.recv_bytes:
+        print("[case]", cfg, "full-size oracle run skipped: host memory", avail >> 30, "GiB", flush=True)
+        return
+    announce(cfg, "oracle at full size")
+    want = np.full((p, p, B), POISON, dtype=np.uint8)
+    oracle.allgather(oracle.SPARBIT, p, B, send, want)
+    for r in range(p):
+        assert np.array_equal(d_recv[r].cpu().numpy(), want[r]), (cfg, "oracle row", r)
+
 
 # ------------------------------------------------------------------ library life cycle
 def test_finalize_then_reuse(torch):
@@ -314,3 +328,27 @@ def test_maximum_rank_count(torch):
     got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_PER_STEP)
     assert np.array_equal(got, want)
     sb.sparbit_finalize()  # drop the 134 MB table
+
+
+@pytest.mark.parametrize("extra,in_place", [(4112, False), (4112, True), (4, False)])
+def test_blocks_larger_than_4_gib(torch, extra, in_place):
+    """Offsets inside one block beyond 32 bits: p = 2 with blocks of 4 GiB + a ragged tail
+    (16-byte path, and the 4-byte flat path whose element index needs 64 bits).  The expected
+    state is the oracle's, taken from its run on rank tags."""
+    p, B = 2, (4 << 30) + extra
+    announce("huge blocks", B, in_place)
+    dev = torch.device("cuda:0")
+    origin = expected_origins(p)
+    assert (origin == np.arange(p)[None, :]).all()
+    d_send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev)
+    d_recv = torch.full((p, p, B), POISON, dtype=torch.uint8, device=dev)
+    if in_place:
+        for r in range(p):
+            d_recv[r, r] = d_send[r]
+    sb.sparbit_allgather_mode(None if in_place else d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_PER_STEP)
+    torch.cuda.synchronize()
+    for r in range(p):
+        for k in range(p):
+            assert torch.equal(d_recv[r, k], d_send[origin[r, k]]), (r, k)
+    del d_send, d_recv
+    torch.cuda.empty_cache()
