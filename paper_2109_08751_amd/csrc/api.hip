@@ -379,7 +379,10 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     vp->displs.assign(displs, displs + p);
     std::vector<VarCopy> all;
     for (const Phase& ph : dp->host.phases) {
-        VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), 0u, 0u};
+        // The copies of a phase are independent, so they may be regrouped: one launch per size class
+        // (lengths within a factor of two), so that a phase mixing tiny and huge blocks neither wastes
+        // dispatches on the tiny ones nor overflows the grid.
+        std::vector<VarCopy> bucket[65];
         for (const Copy& c : ph.copies) {
             const uint32_t slot = c.dst_block % uint32_t(p);  // the destination always names the slot
             if (counts[slot] == 0) continue;
@@ -389,13 +392,19 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
             vc.dst_off = uint64_t(c.dst_block / uint32_t(p)) * row_bytes + displs[slot];
             vc.len = counts[slot];
             vc.pad = 0;
-            all.push_back(vc);
-            if (vc.len > v.max_len) v.max_len = vc.len;
+            int cls = 0;
+            while ((uint64_t(1) << cls) < vc.len) ++cls;  // ceil(log2 len)
+            bucket[cls].push_back(vc);
         }
-        v.ncopies = uint32_t(all.size()) - v.first;
-        if (v.ncopies == 0) continue;
-        if (!ph.only_in_place && !ph.covered_by_fused) vp->out_of_place.push_back(v);
-        if (!ph.skip_in_place) vp->in_place.push_back(v);
+        for (int cls = 64; cls >= 0; --cls) {
+            if (bucket[cls].empty()) continue;
+            VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), uint32_t(bucket[cls].size()), 0u};
+            for (const VarCopy& vc : bucket[cls])
+                if (vc.len > v.max_len) v.max_len = vc.len;
+            all.insert(all.end(), bucket[cls].begin(), bucket[cls].end());
+            if (!ph.only_in_place && !ph.covered_by_fused) vp->out_of_place.push_back(v);
+            if (!ph.skip_in_place) vp->in_place.push_back(v);
+        }
     }
     if (!all.empty()) {
         SB_HIP(hipMalloc(reinterpret_cast<void**>(&vp->d_copies), all.size() * sizeof(VarCopy)));

@@ -76,9 +76,10 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
 // Blocks of different sizes (Allgatherv): every copy carries its own byte
 // offsets and length.  Same shape as copy_tiles_kernel -- one tile per
 // workgroup, copies dealt round-robin to consecutive workgroups -- with the
-// grid's x extent sized for the longest block of the phase; workgroups past
-// the end of a shorter block exit at once.  V is the access width that all
-// offsets, lengths and base addresses of the call allow.
+// grid's x extent sized for the longest block of the launch; workgroups past
+// the end of a shorter block exit at once (the host groups the copies of a
+// phase into launches of similar length, so at most half of them do).  V is
+// the access width that all offsets, lengths and base addresses allow.
 // ---------------------------------------------------------------------------
 struct VarCopy {
     uint64_t src_off;  // bytes from the phase's source base

@@ -189,3 +189,21 @@ def test_gpu_allgatherv_large_unequal_blocks():
     oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, send, want)
     got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send)
     assert np.array_equal(got, want)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_skewed_sizes():
+    """One 40 MiB block among blocks of 0 B .. 100 KiB: copies of one step go out in
+    launches per size class."""
+    import torch
+    p = 9
+    counts = np.array([16, 0, 40 << 20, 100 << 10, 48, 4096, 0, 33 << 10, 16], dtype=np.uint64)
+    displs = np.concatenate([[0], np.cumsum(counts[:-1] + 16)]).astype(np.uint64)
+    row = int(displs[-1] + counts[-1])
+    send = np.tile(workloads.make_send_raw(1, 65536, 4).reshape(-1), row // 65536 + 1)[:row].copy()
+    for algo, oalgo in ((sb.SPARBIT, oracle.SPARBIT), (sb.RING, oracle.RING), (sb.DIRECT, oracle.NAIVE)):
+        print("[case] skewed allgatherv", algo, flush=True)
+        want = np.full((p, row), POISON, dtype=np.uint8)
+        oracle.allgatherv(oalgo, p, counts, displs, row, send, want)
+        got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
+        assert np.array_equal(got, want)
