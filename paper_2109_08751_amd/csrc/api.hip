@@ -92,6 +92,7 @@ struct VarPlan {
 struct DeviceState {
     int device = -1;
     int num_cus = 0;
+    std::map<const void*, int> occupancy;              // resident workgroups per CU, per kernel
     std::vector<std::unique_ptr<VarPlan>> var_plans;  // small most-recently-used cache
     uint64_t var_clock = 0;
     std::map<hipStream_t, FlowStream> flows;
@@ -312,16 +313,31 @@ int launch_phase(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t 
     }
 }
 
+// Workgroups of `kernel` (WG lanes, no dynamic LDS) that fit on one compute unit; asked once per device.
+template <typename Kernel>
+int resident_per_cu(DeviceState* ds, Kernel kernel, int* out)
+{
+    const void* key = reinterpret_cast<const void*>(kernel);
+    auto it = ds->occupancy.find(key);
+    if (it == ds->occupancy.end()) {
+        int n = 0;
+        SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, WG, 0));
+        it = ds->occupancy.emplace(key, n).first;
+    }
+    *out = it->second;
+    return SPARBIT_OK;
+}
+
 template <typename V>
-int launch_persistent_v(const PersistentArgs& a, int num_cus, uint64_t max_tiles, hipStream_t stream)
+int launch_persistent_v(const PersistentArgs& a, DeviceState* ds, uint64_t max_tiles, hipStream_t stream)
 {
     constexpr int U = 4;
+    const int num_cus = ds->num_cus;
     const bool nt = g_nontemporal.load() != 0;
     int per_cu = 0;
-    if (nt)
-        SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_kernel<V, U, true>, WG, 0));
-    else
-        SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_kernel<V, U, false>, WG, 0));
+    int rc = nt ? resident_per_cu(ds, persistent_kernel<V, U, true>, &per_cu)
+                : resident_per_cu(ds, persistent_kernel<V, U, false>, &per_cu);
+    if (rc != SPARBIT_OK) return rc;
     long long want = g_wgs_per_cu.load();
     if (want < 1) want = 1;
     if (per_cu < 1) return SPARBIT_ERR_HIP;
@@ -338,10 +354,12 @@ int launch_persistent_v(const PersistentArgs& a, int num_cus, uint64_t max_tiles
 }
 
 template <typename V>
-int launch_dataflow_v(const FlowArgs& a, int num_cus, hipStream_t stream)
+int launch_dataflow_v(const FlowArgs& a, DeviceState* ds, hipStream_t stream)
 {
+    const int num_cus = ds->num_cus;
     int per_cu = 0;
-    SB_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, dataflow_kernel<V>, WG, 0));
+    const int rc = resident_per_cu(ds, dataflow_kernel<V>, &per_cu);
+    if (rc != SPARBIT_OK) return rc;
     if (per_cu < 1) return SPARBIT_ERR_HIP;
     long long want = g_flow_wgs_per_cu.load();
     const int half = per_cu > 1 ? per_cu / 2 : 1;
@@ -591,9 +609,9 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             a.epoch = fs->epoch;
             a.total_items = uint32_t(items);
             switch (width) {
-            case 16: return launch_dataflow_v<uint64_t>(a, ds->num_cus, stream);
-            case 4: return launch_dataflow_v<uint32_t>(a, ds->num_cus, stream);
-            default: return launch_dataflow_v<uint8_t>(a, ds->num_cus, stream);
+            case 16: return launch_dataflow_v<uint64_t>(a, ds, stream);
+            case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);
+            default: return launch_dataflow_v<uint8_t>(a, ds, stream);
             }
         }
         mode = SPARBIT_MODE_PER_STEP;  // too many items for one grid
@@ -617,9 +635,9 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             if (t > max_tiles) max_tiles = t;
         }
         switch (width) {
-        case 16: return launch_persistent_v<u32x4>(a, ds->num_cus, max_tiles, stream);
-        case 4: return launch_persistent_v<uint32_t>(a, ds->num_cus, max_tiles, stream);
-        default: return launch_persistent_v<uint8_t>(a, ds->num_cus, max_tiles, stream);
+        case 16: return launch_persistent_v<u32x4>(a, ds, max_tiles, stream);
+        case 4: return launch_persistent_v<uint32_t>(a, ds, max_tiles, stream);
+        default: return launch_persistent_v<uint8_t>(a, ds, max_tiles, stream);
         }
     }
 
