@@ -229,6 +229,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.note}; recv {w.recv_bytes / 2**30:.2f} GiB; {nsteps} steps",
                    "p": p, "block_bytes": B, "mode": args.mode},
         "min_ms": head["min_ms"], "max_ms": head["max_ms"], "wall_ms_per_step": head["wall_ms_per_call"],
+        "schedule_only_GBps": p * (p - 1) * B / head["avg_ms"] / 1e6,  # without the own-block placement
         "roofline": {"bound": "hbm", "achieved": r["hbm_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": r["hbm_frac"],
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_CALL[w.name] / launches
