@@ -298,6 +298,14 @@ def main():
 
     if not args.skip_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
+    # Context only (Sections IV and V of the paper): another machine, another metric -- not a target.
+    out["paper_context"] = {
+        "hardware": "Open MPI 4.0.3, OSU osu_allgather 5.7; Yahoo: 16 nodes of 2x Xeon L5420, GbE leaves + 10 Gb/s "
+                    "core; Cervino: 5 nodes of 2x Xeon E5-2683 v4, 40 Gb/s flat; 1 B..1 MiB blocks, up to 256 / 320 "
+                    "processes",
+        "reported": "no absolute rates; Sparbit has the best average time in 46.43 % (Yahoo) / 39.64 % (Cervino) of "
+                    "the cases under sequential mapping, improving on the second best by 34.70 / 26.16 / 84.16 % "
+                    "(mean / median / highest, Yahoo) and 30.23 / 29.00 / 77.78 % (Cervino)"}
     sb.sparbit_finalize()
     print(json.dumps(out))
 
