@@ -163,12 +163,13 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
 /*
  * Tuning knobs for experiments (process-wide; unknown keys or out-of-range
  * values return SPARBIT_ERR_ARG):
- *   "wg_threads"           lanes per workgroup of the large-block kernel: 64, 128, 256, 512, 1024
- *   "unroll"               16-byte vectors each lane of that kernel moves: 1, 2 or 4
+ *   "wg_threads"           most lanes per workgroup of the per-step kernel: 64, 128, 256, 512, 1024
+ *   "unroll"               vectors each lane of that kernel moves: 1, 2 or 4 (2 and 4 only with 256 lanes)
  *   "interleave_log2"      log2 of the block copies dealt round-robin to consecutive workgroups (3 = one per XCD)
- *   "flat_below_bytes"     blocks smaller than this use the flattened small-block kernel
- *   "persistent_max_bytes" AUTO uses the persistent kernel when p*p*block_bytes is at most this
- *   "dataflow_max_bytes"   AUTO uses the dataflow kernel when p*p*block_bytes is at most this (and above the former)
+ *   "dataflow_max_items"   AUTO uses the dataflow kernel when the call has at most this many work items
+ *                          (block copies x chunks per block)
+ *   "persistent_max_bytes" else AUTO uses the persistent kernel when p*p*block_bytes is at most this;
+ *                          otherwise one launch per step
  *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16)
  *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint

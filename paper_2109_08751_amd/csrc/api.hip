@@ -33,16 +33,15 @@ thread_local int tl_last_hip_error = 0;
 
 // ---- tuning knobs ----------------------------------------------------------
 std::atomic<long long> g_wg_threads{256};                     // lanes per workgroup of the tile kernel
-std::atomic<long long> g_unroll{1};                           // 16-byte vectors per lane of the tile kernel
+std::atomic<long long> g_unroll{1};                           // vectors per lane of the tile kernel (2 and 4 only with 256 lanes)
 std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
-std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO threshold on p*p*B
 std::atomic<long long> g_nontemporal{1};
-std::atomic<long long> g_dataflow_max_bytes{64ll << 10};      // AUTO threshold on p*p*B for the dataflow kernel
+std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO uses the persistent kernel up to this p*p*B
+std::atomic<long long> g_dataflow_max_items{256};             // AUTO uses the dataflow kernel up to this many work items
 std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
 std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
-std::atomic<long long> g_flat_below_bytes{4096};              // blocks smaller than this use the flat kernel
 
 struct DevicePlan {
     Plan host;
@@ -228,21 +227,31 @@ int access_width(const void* a, const void* b, const void* c, size_t block_bytes
     return 1;
 }
 
-template <typename V, typename Index>
-int launch_flat_t(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B,
-                  bool nt, hipStream_t stream)
+template <typename V, typename Index, int T, int U>
+int launch_tiles(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                 hipStream_t stream)
 {
-    constexpr int U = 4;
     const uint64_t vpb = B / sizeof(V);
-    const uint64_t total = vpb * ncopies;
-    const uint64_t ntiles = (total + WG * U - 1) / (WG * U);
-    if (ntiles > 0x7fffffffull) return SPARBIT_ERR_ARG;
-    if (nt)
-        hipLaunchKernelGGL((copy_flat_kernel<V, Index, U, true>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
-                           dst, copies, uint64_t(B), Index(vpb), Index(total));
+    uint64_t tiles = (vpb + T * U - 1) / (T * U);
+    uint32_t lg_g = uint32_t(g_interleave_log2.load());
+    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
+    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
+    const uint32_t gy = groups < 32768u ? groups : 32768u;
+    const uint32_t gz = (groups + gy - 1) / gy;
+    if (gz > 65535u) return SPARBIT_ERR_ARG;
+    const uint64_t max_tiles = (0x7fffffffull / T) >> lg_g;  // grid x extent stays below 2^31 lanes
+    const bool loop = tiles > max_tiles;                     // the kernel then takes several trips
+    if (loop) tiles = max_tiles;
+    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
+    if (loop)
+        hipLaunchKernelGGL((copy_tiles_kernel<V, Index, T, U, true, true>), grid, dim3(T), 0, stream, src, dst, copies,
+                           ncopies, uint64_t(B), lg_g);
+    else if (nt)
+        hipLaunchKernelGGL((copy_tiles_kernel<V, Index, T, U, true, false>), grid, dim3(T), 0, stream, src, dst,
+                           copies, ncopies, uint64_t(B), lg_g);
     else
-        hipLaunchKernelGGL((copy_flat_kernel<V, Index, U, false>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
-                           dst, copies, uint64_t(B), Index(vpb), Index(total));
+        hipLaunchKernelGGL((copy_tiles_kernel<V, Index, T, U, false, false>), grid, dim3(T), 0, stream, src, dst,
+                           copies, ncopies, uint64_t(B), lg_g);
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
@@ -251,42 +260,47 @@ template <typename V>
 int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
                 hipStream_t stream)
 {
-    const uint64_t total = (B / sizeof(V)) * uint64_t(ncopies);
-    if (total + WG * 8 <= 0xffffffffull) return launch_flat_t<V, uint32_t>(src, dst, copies, ncopies, B, nt, stream);
-    return launch_flat_t<V, uint64_t>(src, dst, copies, ncopies, B, nt, stream);
-}
-
-template <int T, int U>
-int launch_tiles_tu(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
-                    hipStream_t stream)
-{
-    const uint64_t vpb = B >> 4;
-    const uint64_t tiles = (vpb + T * U - 1) / (T * U);
-    uint32_t lg_g = uint32_t(g_interleave_log2.load());
-    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
-    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
-    const uint32_t gy = groups < 32768u ? groups : 32768u;
-    const uint32_t gz = (groups + gy - 1) / gy;
-    if ((tiles << lg_g) > 0x7fffffffull / T || gz > 65535u) return SPARBIT_ERR_ARG;
-    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
+    constexpr int U = 4;
+    const uint32_t vpb = uint32_t(B / sizeof(V));  // < 64 here
+    const uint64_t total = uint64_t(vpb) * ncopies;
+    const uint64_t ntiles = (total + WG * U - 1) / (WG * U);
+    if (total + WG * U > 0xffffffffull) return SPARBIT_ERR_ARG;  // cannot happen: ncopies < 2^25, vpb < 64
     if (nt)
-        hipLaunchKernelGGL((copy_tiles_kernel<T, U, true>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
-                           uint64_t(B), lg_g);
+        hipLaunchKernelGGL((copy_flat_kernel<V, uint32_t, U, true>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
+                           dst, copies, uint64_t(B), vpb, uint32_t(total));
     else
-        hipLaunchKernelGGL((copy_tiles_kernel<T, U, false>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
-                           uint64_t(B), lg_g);
+        hipLaunchKernelGGL((copy_flat_kernel<V, uint32_t, U, false>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
+                           dst, copies, uint64_t(B), vpb, uint32_t(total));
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
 
-template <int T>
-int launch_tiles_t(int unroll, const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B,
-                   bool nt, hipStream_t stream)
+// Picks the workgroup size (no wider than the block, no wider than the "wg_threads" knob) and the index width.
+template <typename V>
+int launch_phase_v(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                   hipStream_t stream)
 {
-    switch (unroll) {
-    case 4: return launch_tiles_tu<T, 4>(src, dst, copies, ncopies, B, nt, stream);
-    case 2: return launch_tiles_tu<T, 2>(src, dst, copies, ncopies, B, nt, stream);
-    default: return launch_tiles_tu<T, 1>(src, dst, copies, ncopies, B, nt, stream);
+    const uint64_t vpb = B / sizeof(V);
+    // Blocks shorter than one wavefront.  A tile per block leaves lanes idle and costs one workgroup per
+    // block; flattened tiles keep the lanes busy and neighbouring blocks' writes coalesced, but every lane pays
+    // a division and a table look-up.  Measured: with byte-wide accesses flattened tiles always win (p = 253,
+    // B = 1: 43 us against 147 us); with 16-byte vectors a tile per block wins until a launch holds tens of
+    // thousands of blocks (p = 125, B = 16..512: 31 us against 40 us per call; one launch of 65536 16-byte
+    // blocks: 33 us against 14.5 us).
+    if (vpb < 64 && (sizeof(V) < 16 || ncopies >= 16384u)) return launch_flat<V>(src, dst, copies, ncopies, B, nt, stream);
+    if (2 * vpb > 0xffffffffull)  // lane index plus a grid-wide stride must not wrap
+        return launch_tiles<V, uint64_t, 256, 1>(src, dst, copies, ncopies, B, nt, stream);
+    long long t = g_wg_threads.load();
+    while (t > 64 && uint64_t(t / 2) >= vpb) t /= 2;
+    const int u = int(g_unroll.load());
+    if (u == 4 && t == 256) return launch_tiles<V, uint32_t, 256, 4>(src, dst, copies, ncopies, B, nt, stream);
+    if (u == 2 && t == 256) return launch_tiles<V, uint32_t, 256, 2>(src, dst, copies, ncopies, B, nt, stream);
+    switch (t) {
+    case 64: return launch_tiles<V, uint32_t, 64, 1>(src, dst, copies, ncopies, B, nt, stream);
+    case 128: return launch_tiles<V, uint32_t, 128, 1>(src, dst, copies, ncopies, B, nt, stream);
+    case 512: return launch_tiles<V, uint32_t, 512, 1>(src, dst, copies, ncopies, B, nt, stream);
+    case 1024: return launch_tiles<V, uint32_t, 1024, 1>(src, dst, copies, ncopies, B, nt, stream);
+    default: return launch_tiles<V, uint32_t, 256, 1>(src, dst, copies, ncopies, B, nt, stream);
     }
 }
 
@@ -296,20 +310,10 @@ int launch_phase(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t 
 {
     if (ncopies == 0) return SPARBIT_OK;
     const bool nt = g_nontemporal.load() != 0;
-    if (width == 16 && B >= size_t(g_flat_below_bytes.load()) && (B >> 4) <= 0x3fffffffull) {
-        const int u = int(g_unroll.load());
-        switch (g_wg_threads.load()) {
-        case 64: return launch_tiles_t<64>(u, src, dst, copies, ncopies, B, nt, stream);
-        case 128: return launch_tiles_t<128>(u, src, dst, copies, ncopies, B, nt, stream);
-        case 512: return launch_tiles_t<512>(u, src, dst, copies, ncopies, B, nt, stream);
-        case 1024: return launch_tiles_t<1024>(u, src, dst, copies, ncopies, B, nt, stream);
-        default: return launch_tiles_t<256>(u, src, dst, copies, ncopies, B, nt, stream);
-        }
-    }
     switch (width) {
-    case 16: return launch_flat<u32x4>(src, dst, copies, ncopies, B, nt, stream);
-    case 4: return launch_flat<uint32_t>(src, dst, copies, ncopies, B, nt, stream);
-    default: return launch_flat<uint8_t>(src, dst, copies, ncopies, B, nt, stream);
+    case 16: return launch_phase_v<u32x4>(src, dst, copies, ncopies, B, nt, stream);
+    case 4: return launch_phase_v<uint32_t>(src, dst, copies, ncopies, B, nt, stream);
+    default: return launch_phase_v<uint8_t>(src, dst, copies, ncopies, B, nt, stream);
     }
 }
 
@@ -563,18 +567,21 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
                               static_cast<const uint8_t*>(work)};
     const int width = access_width(sendbufs, recvbufs, work, B);
 
+    const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
     if (mode == SPARBIT_MODE_AUTO) {
-        // Single-launch forms only where the whole job is a handful of workgroups: a grid that waits on
-        // itself while it holds most of the machine starves whatever else runs on the GPU (and is starved
-        // by it), so anything larger goes out as one launch per step, which never waits on the device.
-        if (recv_bytes <= size_t(g_dataflow_max_bytes.load()) && !in_place)
+        // The single-launch dataflow form only where the whole job is a handful of workgroups: a grid that
+        // waits on itself while it holds much of the machine starves whatever else runs on the GPU (and is
+        // starved by it).  Anything larger goes out as one launch per step, which never waits on the device.
+        const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
+        const uint64_t chunk = uint64_t(g_flow_chunk_bytes.load());
+        const uint64_t items = copies_total * ((B + chunk - 1) / chunk);
+        if (!in_place && items <= uint64_t(g_dataflow_max_items.load()))
             mode = SPARBIT_MODE_DATAFLOW;
         else if (recv_bytes <= size_t(g_persistent_max_bytes.load()))
-            mode = SPARBIT_MODE_PERSISTENT;
+            mode = SPARBIT_MODE_PERSISTENT;  // at most 16 workgroups of flattened tiles: the barrier is cheap there
         else
             mode = SPARBIT_MODE_PER_STEP;
     }
-    const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
 
     // Dataflow form: flags instead of barriers.  In-place calls have no item that
     // would publish the flags of the own slots, so they take the per-step path.
@@ -768,9 +775,9 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "persistent_max_bytes")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_persistent_max_bytes = value;
-    } else if (!std::strcmp(key, "dataflow_max_bytes")) {
+    } else if (!std::strcmp(key, "dataflow_max_items")) {
         if (value < 0) return SPARBIT_ERR_ARG;
-        g_dataflow_max_bytes = value;
+        g_dataflow_max_items = value;
     } else if (!std::strcmp(key, "flow_wgs_per_cu")) {
         if (value < 1 || value > 16) return SPARBIT_ERR_ARG;
         g_flow_wgs_per_cu = value;
@@ -785,9 +792,6 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "spin_limit_ms")) {
         if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;
         g_spin_limit_ms = value;
-    } else if (!std::strcmp(key, "flat_below_bytes")) {
-        if (value < 16) return SPARBIT_ERR_ARG;
-        g_flat_below_bytes = value;
     } else {
         return SPARBIT_ERR_ARG;
     }

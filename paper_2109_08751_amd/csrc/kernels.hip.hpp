@@ -1,7 +1,7 @@
 // gfx950 copy kernels: every phase of a schedule is a batch of independent
 // block copies  dst_base[dst_block * B ..] <- src_base[src_block * B ..].
 // Nothing here is a contraction: the kernels are plain HBM streams built from
-// 16-byte (or 4- / 1-byte) global loads and stores, several in flight per lane.
+// 16-byte (or 4- / 1-byte) global loads and stores.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -34,12 +34,14 @@ __device__ __forceinline__ void st(V* p, V v)
 }
 
 // ---------------------------------------------------------------------------
-// Large blocks (B a multiple of 16, pointers 16-aligned).  One workgroup of T
-// lanes moves one tile of T * U 16-byte vectors of one block copy and exits:
-// no loop, and the table entry, both base addresses and the bound are
-// wave-uniform (scalar registers).  On MI355X the best rate comes from the
-// smallest footprint per wave (U = 1: one load and one store per lane) with
-// the parallelism left to the dispatcher.
+// The per-step kernel.  One workgroup of T lanes moves one tile of T * U
+// vectors of one block copy and exits: no loop, and the table entry, both base
+// addresses and the bound are wave-uniform (scalar registers).  V is the
+// access width the call's alignment allows (16, 4 or 1 bytes); Index is 32-bit
+// unless a block holds 2^32 vectors or more.  On MI355X the best rate comes
+// from the smallest footprint per wave (U = 1: one load and one store per
+// lane) with the parallelism left to the dispatcher; for blocks shorter than
+// a tile the host picks a smaller T.
 //
 // XCD-aware mapping.  The dispatcher deals consecutive workgroups round-robin
 // to the 8 XCDs, each with its own L2 and its own address-translation caches.
@@ -49,7 +51,7 @@ __device__ __forceinline__ void st(V* p, V v)
 // blockIdx.x interleaves G = 2^lg_g copies: copy = group * G + (x mod G),
 // tile = x / G.  With G = 8 each XCD streams one whole block by itself.
 // ---------------------------------------------------------------------------
-template <int T, int U, bool NT>
+template <typename V, typename Index, int T, int U, bool NT, bool LOOP>
 __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict__ src_base,
                                                        uint8_t* __restrict__ dst_base,
                                                        const Copy* __restrict__ copies, uint32_t ncopies,
@@ -59,17 +61,25 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
     const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
     if (c >= ncopies) return;
     const Copy cp = copies[c];
-    const u32x4* __restrict__ s = reinterpret_cast<const u32x4*>(src_base + uint64_t(cp.src_block) * block_bytes);
-    u32x4* __restrict__ d = reinterpret_cast<u32x4*>(dst_base + uint64_t(cp.dst_block) * block_bytes);
-    const uint32_t vpb = uint32_t(block_bytes >> 4);
-    const uint32_t v = (blockIdx.x >> lg_g) * (T * U) + threadIdx.x;
-    u32x4 x[U];
+    const V* __restrict__ s = reinterpret_cast<const V*>(src_base + uint64_t(cp.src_block) * block_bytes);
+    V* __restrict__ d = reinterpret_cast<V*>(dst_base + uint64_t(cp.dst_block) * block_bytes);
+    const Index vpb = Index(block_bytes / sizeof(V));
+    const Index v0 = Index(blockIdx.x >> lg_g) * Index(T * U) + threadIdx.x;
+    auto move = [&](Index v) {
+        V x[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (v + u * T < vpb) x[u] = ld<u32x4, NT>(s + v + u * T);
+        for (int u = 0; u < U; ++u)
+            if (v + Index(u * T) < vpb) x[u] = ld<V, NT>(s + v + Index(u * T));
 #pragma unroll
-    for (int u = 0; u < U; ++u)
-        if (v + u * T < vpb) st<u32x4, NT>(d + v + u * T, x[u]);
+        for (int u = 0; u < U; ++u)
+            if (v + Index(u * T) < vpb) st<V, NT>(d + v + Index(u * T), x[u]);
+    };
+    if constexpr (LOOP) {  // blocks so long that their tiles exceed the grid's x extent: several trips
+        const Index stride = Index(gridDim.x >> lg_g) * Index(T * U);
+        for (Index v = v0; v < vpb; v += stride) move(v);
+    } else {
+        move(v0);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -107,9 +117,13 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------
-// Small or odd-sized blocks: the (copy, element) space is flattened and every
-// lane finds its copy by one division, so a workgroup's tile may span many
-// short blocks.  V is the access width the alignment allows.
+// Flattened tiles: the (copy, element) space of a phase is one index range and
+// every lane finds its copy by one division, so a tile may span many short
+// blocks.  Used by the persistent kernel's grid-stride loop and, as a kernel of
+// its own, for blocks shorter than one wavefront's worth of vectors, where a
+// tile per block would leave most lanes idle and scatter partial-line writes
+// over the XCDs.  (For longer blocks copy_tiles_kernel wins at every size: the
+// per-lane division and table look-up cost more than a few idle lanes.)
 // ---------------------------------------------------------------------------
 template <typename V, typename Index, int UNROLL, bool NT>
 __device__ __forceinline__ void copy_flat_tile(const uint8_t* __restrict__ src_base,
