@@ -126,8 +126,20 @@ def cpu_baseline(w):
         Bs >>= 1
     if Bs > B:
         dt, B = run(Bs), Bs
+    model, mem_total = "unknown", 0
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+        for line in open("/proc/meminfo"):
+            if line.startswith("MemTotal:"):
+                mem_total = int(line.split()[1]) * 1024
+    except OSError:
+        pass
     return {"value": p * p * B / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "seconds": dt,
+            "host": {"cpu_model": model, "nproc": os.cpu_count(), "mem_total_GiB": round(mem_total / 2**30, 1)},
             "sample": f"Sparbit oracle, p={p}, block {B} B (workload block {w.block_bytes} B), "
                       f"recv {p * p * B / 2**20:.0f} MiB, one pass"}
 
