@@ -24,10 +24,16 @@ __device__ __forceinline__ V ld(const V* p)
         return *p;
 }
 
+// Streaming store.  For 16-byte vectors the fastest form measured on MI355X is a write-through store at
+// system scope (sc0 sc1): a linear copy runs at 6.69 TB/s with it against 6.45 TB/s with the non-temporal
+// hint alone.  The compiler has no builtin that emits it for 16 bytes, hence the one-instruction asm; the
+// data operand comes from a tracked load, so the wait for that load is still the compiler's.
 template <typename V, bool NT>
 __device__ __forceinline__ void st(V* p, V v)
 {
-    if constexpr (NT)
+    if constexpr (NT && sizeof(V) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (NT)
         __builtin_nontemporal_store(v, p);
     else
         *p = v;
