@@ -36,7 +36,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # scaled by a plain 1 GiB copy through the same kernel); figures and commands: profiles/copy_tiles_kernel_cfg4.md
 # and profiles/copy_tiles_kernel_cfg5.md.
 # Only meaningful for the default tuning and issue mode of that workload.
-MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16769574 + 16763996) * 1024, "cfg5": (16917049 + 16889624) * 1024}
+MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16779292 + 16777216) * 1024, "cfg5": (16917006 + 16908544) * 1024}
 
 
 def parse_args():
