@@ -34,7 +34,7 @@ __device__ __forceinline__ void st(V* p, V v)
     if constexpr (NT && sizeof(V) == 16)
         asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
     else if constexpr (NT)
-        __builtin_nontemporal_store(v, p);
+        __builtin_nontemporal_store(v, p);  // narrower stores fill a line piecewise: write-through is slower there
     else
         *p = v;
 }
