@@ -401,10 +401,12 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     vp->displs.assign(displs, displs + p);
     std::vector<VarCopy> all;
     for (const Phase& ph : dp->host.phases) {
-        // The copies of a phase are independent, so they may be regrouped: one launch per size class
-        // (lengths within a factor of two), so that a phase mixing tiny and huge blocks neither wastes
-        // dispatches on the tiny ones nor overflows the grid.
-        std::vector<VarCopy> bucket[65];
+        // The copies of a phase are independent, so they may be regrouped.  Lengths within a factor of four
+        // share one launch (workgroups past the end of a shorter block exit at once); a phase with more skew
+        // goes out as one launch per size class (factor of two), so that it neither wastes dispatches on tiny
+        // blocks nor overflows the grid.
+        std::vector<VarCopy> bucket[65], in_order;
+        uint64_t longest = 0, shortest = ~uint64_t(0);
         for (const Copy& c : ph.copies) {
             const uint32_t slot = c.dst_block % uint32_t(p);  // the destination always names the slot
             if (counts[slot] == 0) continue;
@@ -417,6 +419,13 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
             int cls = 0;
             while ((uint64_t(1) << cls) < vc.len) ++cls;  // ceil(log2 len)
             bucket[cls].push_back(vc);
+            in_order.push_back(vc);
+            if (vc.len > longest) longest = vc.len;
+            if (vc.len < shortest) shortest = vc.len;
+        }
+        if (longest != 0 && longest <= 4 * shortest) {  // little skew: one launch, schedule order
+            for (int cls = 0; cls <= 64; ++cls) bucket[cls].clear();
+            bucket[64].swap(in_order);
         }
         for (int cls = 64; cls >= 0; --cls) {
             if (bucket[cls].empty()) continue;

@@ -28,10 +28,10 @@ __device__ __forceinline__ V ld(const V* p)
 // system scope (sc0 sc1): a linear copy runs at 6.69 TB/s with it against 6.45 TB/s with the non-temporal
 // hint alone.  The compiler has no builtin that emits it for 16 bytes, hence the one-instruction asm; the
 // data operand comes from a tracked load, so the wait for that load is still the compiler's.
-template <typename V, bool NT>
+template <typename V, bool NT, bool WRITE_THROUGH = true>
 __device__ __forceinline__ void st(V* p, V v)
 {
-    if constexpr (NT && sizeof(V) == 16)
+    if constexpr (NT && WRITE_THROUGH && sizeof(V) == 16)
         asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
     else if constexpr (NT)
         __builtin_nontemporal_store(v, p);  // narrower stores fill a line piecewise: write-through is slower there
@@ -118,7 +118,9 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
     if (v < cp.len / sizeof(V)) {
         const V* __restrict__ s = reinterpret_cast<const V*>(src_base + cp.src_off);
         V* __restrict__ d = reinterpret_cast<V*>(dst_base + cp.dst_off);
-        st<V, NT>(d + v, ld<V, NT>(s + v));
+        // Non-temporal store here: measured on 128 ranks x 1 MiB, this kernel runs at 6.5 TB/s with it and at
+        // 6.4 TB/s with the write-through form that serves copy_tiles_kernel better.
+        st<V, NT, false>(d + v, ld<V, NT>(s + v));
     }
 }
 
