@@ -352,3 +352,40 @@ def test_blocks_larger_than_4_gib(torch, extra, in_place):
             assert torch.equal(d_recv[r, k], d_send[origin[r, k]]), (r, k)
     del d_send, d_recv
     torch.cuda.empty_cache()
+
+
+def test_randomized_cases(torch):
+    """150 seeded random (schedule, p, block size, mode, in-place, misalignment) cases against the oracle."""
+    rng = np.random.default_rng(20210908)
+    algos = [sb.SPARBIT, sb.SPARBIT, sb.SPARBIT, sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT]
+    modes = ["per_step", "persistent", "dataflow", "auto"]
+    sizes = [1, 2, 3, 4, 7, 8, 12, 16, 20, 31, 32, 48, 64, 100, 128, 256, 500, 1024, 1040, 4096, 4100, 8192, 20000,
+             65536, 70000]
+    done = 0
+    while done < 150:
+        algo = algos[rng.integers(len(algos))]
+        p = int(rng.integers(1, 81))
+        if algo == sb.RECURSIVE_DOUBLING:
+            p = 1 << int(rng.integers(0, 7))
+        B = sizes[rng.integers(len(sizes))]
+        if p * p * B > (64 << 20):
+            continue
+        mode = modes[rng.integers(len(modes))]
+        in_place = bool(rng.integers(0, 4) == 0) and algo != sb.BRUCK
+        misalign = [0, 0, 0, 1, 4, 8, 16][rng.integers(7)]
+        announce("random", done, algo, p, B, mode, in_place, misalign)
+        send = workloads.make_send_raw(p, B, seed=done)
+        want = oracle_result(algo, p, B, send, in_place=in_place)
+        got = gpu_result(torch, algo, p, B, send, MODES[mode], in_place=in_place, misalign=misalign)
+        assert np.array_equal(got, want), (algo, p, B, mode, in_place, misalign)
+        done += 1
+
+
+def test_ring_with_256_steps(torch):
+    """Ring at p = 257: 256 dependent launches (or barrier phases) per call."""
+    p, B = 257, 64
+    send = workloads.make_send_raw(p, B, seed=6)
+    want = oracle_result(sb.RING, p, B, send)
+    for mode in ("per_step", "persistent", "dataflow"):
+        announce("ring 257", mode)
+        assert np.array_equal(gpu_result(torch, sb.RING, p, B, send, MODES[mode]), want)
