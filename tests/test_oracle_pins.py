@@ -7,7 +7,6 @@ definition (p rank-shifted binomial trees, Section III-A/B) and planted
 mistakes that the pins must catch.
 """
 import os
-import re
 import subprocess
 import sys
 
