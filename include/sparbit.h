@@ -23,6 +23,18 @@
  * never throws.  Work is enqueued on the caller's stream; the call returns
  * without synchronising (the first call for a given (schedule, p) on a device
  * builds and uploads its tables and does synchronise).
+ *
+ * Recording into a HIP graph (stream capture).  A call on a capturing stream
+ * records one kernel launch per step and nothing else; it is replayed with the
+ * pointers it was recorded with.  It cannot allocate or upload, so the same
+ * call (same schedule and p; for Allgatherv the same counts, displs and
+ * row_bytes; for Bruck a call at least as large) must have run once outside
+ * the capture -- otherwise SPARBIT_ERR_UNSUPPORTED, with nothing recorded.
+ * SPARBIT_MODE_AUTO records the per-step form; the PERSISTENT and DATAFLOW
+ * modes keep per-stream state on the device that replays would share and are
+ * refused with SPARBIT_ERR_UNSUPPORTED.  The graph refers to the library's
+ * cached tables: destroy it before sparbit_finalize, and (Allgatherv) before
+ * more than 7 other geometries have been used on the device.
  */
 #ifndef SPARBIT_H
 #define SPARBIT_H
@@ -38,7 +50,8 @@ extern "C" {
 #define SPARBIT_OK 0
 #define SPARBIT_ERR_ARG (-1)         /* p < 1, p > SPARBIT_MAX_P, NULL recvbufs, size overflow, bad step range, bad enum */
 #define SPARBIT_ERR_ALIAS (-2)       /* sendbufs range overlaps recvbufs range (MPI forbids it; use NULL for in-place) */
-#define SPARBIT_ERR_UNSUPPORTED (-3) /* Recursive Doubling with p not a power of two; Bruck in place */
+#define SPARBIT_ERR_UNSUPPORTED (-3) /* Recursive Doubling with p not a power of two; Bruck in place; a call on a
+                                        capturing stream that would have to allocate or wait on itself */
 #define SPARBIT_ERR_HIP (-4)         /* a HIP call failed; see sparbit_last_hip_error() */
 #define SPARBIT_ERR_NOMEM (-5)       /* host allocation failed */
 

@@ -31,6 +31,32 @@ thread_local int tl_last_hip_error = 0;
         }                                               \
     } while (0)
 
+// True while `stream` records into a HIP graph.  A recorded call is replayed with the arguments it had at
+// capture time and possibly next to other replays, so it may not allocate, may not build tables, and may not
+// use the kernels that wait on themselves through per-stream device state.
+bool stream_is_capturing(hipStream_t stream)
+{
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &status) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return status != hipStreamCaptureStatusNone;
+}
+
+// The C ABI never throws: host allocation failures inside the library become an error code.
+template <typename F>
+int no_throw(F&& body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return SPARBIT_ERR_NOMEM;
+    } catch (...) {
+        return SPARBIT_ERR_NOMEM;
+    }
+}
+
 // ---- tuning knobs ----------------------------------------------------------
 std::atomic<long long> g_wg_threads{256};                     // lanes per workgroup of the tile kernel
 std::atomic<long long> g_unroll{1};                           // vectors per lane of the tile kernel (2 and 4 only with 256 lanes)
@@ -42,6 +68,7 @@ std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (a
 std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
+std::atomic<long long> g_realign_min_bytes{512};              // blocks at least this long, not 16-byte aligned: realigning kernel
 
 struct DevicePlan {
     Plan host;
@@ -122,7 +149,7 @@ int get_device_state(DeviceState** out)
     return SPARBIT_OK;
 }
 
-int get_plan(DeviceState* ds, int algo, int p, DevicePlan** out)
+int get_plan(DeviceState* ds, int algo, int p, bool may_build, DevicePlan** out)
 {
     auto key = std::make_pair(algo, p);
     auto it = ds->plans.find(key);
@@ -130,6 +157,7 @@ int get_plan(DeviceState* ds, int algo, int p, DevicePlan** out)
         *out = it->second.get();
         return SPARBIT_OK;
     }
+    if (!may_build) return SPARBIT_ERR_UNSUPPORTED;  // stream capture: the tables must exist already
     auto dp = std::make_unique<DevicePlan>();
     int rc = build_plan(p, algo, dp->host);
     if (rc != SPARBIT_OK) return rc;
@@ -202,9 +230,10 @@ int get_flow(DeviceState* ds, hipStream_t stream, size_t nflags, FlowStream** ou
     return SPARBIT_OK;
 }
 
-int get_work(DeviceState* ds, size_t bytes, void** out)
+int get_work(DeviceState* ds, size_t bytes, bool may_allocate, void** out)
 {
     if (ds->work_bytes < bytes) {
+        if (!may_allocate) return SPARBIT_ERR_UNSUPPORTED;
         if (ds->work) {
             SB_HIP(hipDeviceSynchronize());
             SB_HIP(hipFree(ds->work));
@@ -275,6 +304,52 @@ int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t n
     return SPARBIT_OK;
 }
 
+// Grid of one tile of T vectors per workgroup for `ncopies` copies of at most `max_vecs` vectors each, copies dealt
+// round-robin in groups of 2^lg_g to consecutive workgroups.  Blocks with more tiles than the x extent allows get
+// the largest extent (the kernels that accept such a grid loop).  False if the copies do not fit a grid at all.
+bool tile_grid(uint64_t max_vecs, uint32_t ncopies, int T, dim3* grid, uint32_t* lg_g_out)
+{
+    uint64_t tiles = (max_vecs + uint64_t(T) - 1) / uint64_t(T);
+    if (tiles == 0) tiles = 1;
+    uint32_t lg_g = uint32_t(g_interleave_log2.load());
+    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
+    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
+    const uint32_t gy = groups < 32768u ? groups : 32768u;
+    const uint32_t gz = (groups + gy - 1) / gy;
+    if (gz > 65535u) return false;
+    const uint64_t max_tiles = (0x7fffffffull / uint64_t(T)) >> lg_g;  // grid x extent stays below 2^31 lanes
+    if (tiles > max_tiles) tiles = max_tiles;
+    *grid = dim3(uint32_t(tiles << lg_g), gy, gz);
+    *lg_g_out = lg_g;
+    return true;
+}
+
+template <int T>
+int launch_realign_t(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                     hipStream_t stream)
+{
+    dim3 grid;
+    uint32_t lg_g = 0;
+    if (!tile_grid(B >> 4, ncopies, T, &grid, &lg_g)) return SPARBIT_ERR_ARG;
+    if (nt)
+        hipLaunchKernelGGL((copy_tiles_realign_kernel<T, true>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
+                           uint64_t(B), lg_g);
+    else
+        hipLaunchKernelGGL((copy_tiles_realign_kernel<T, false>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
+                           uint64_t(B), lg_g);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
+int launch_realign(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                   hipStream_t stream)
+{
+    const uint64_t vecs = B >> 4;
+    if (vecs <= 64) return launch_realign_t<64>(src, dst, copies, ncopies, B, nt, stream);
+    if (vecs <= 128) return launch_realign_t<128>(src, dst, copies, ncopies, B, nt, stream);
+    return launch_realign_t<256>(src, dst, copies, ncopies, B, nt, stream);
+}
+
 // Picks the workgroup size (no wider than the block, no wider than the "wg_threads" knob) and the index width.
 template <typename V>
 int launch_phase_v(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
@@ -310,6 +385,8 @@ int launch_phase(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t 
 {
     if (ncopies == 0) return SPARBIT_OK;
     const bool nt = g_nontemporal.load() != 0;
+    if (width < 16 && B >= size_t(g_realign_min_bytes.load()))
+        return launch_realign(src, dst, copies, ncopies, B, nt, stream);
     switch (width) {
     case 16: return launch_phase_v<u32x4>(src, dst, copies, ncopies, B, nt, stream);
     case 4: return launch_phase_v<uint32_t>(src, dst, copies, ncopies, B, nt, stream);
@@ -382,7 +459,7 @@ constexpr size_t kVarPlanCacheSize = 8;
 // Look up or build the copy lists of an Allgatherv geometry.  Block index b of a
 // receive-side buffer means (rank b / p, slot b % p); of the send buffer, rank b.
 int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t* counts, const size_t* displs,
-                 size_t row_bytes, VarPlan** out)
+                 size_t row_bytes, bool may_build, VarPlan** out)
 {
     for (auto& vp : ds->var_plans) {
         if (vp->algo == algo && vp->p == p && vp->row_bytes == row_bytes &&
@@ -393,6 +470,7 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
             return SPARBIT_OK;
         }
     }
+    if (!may_build) return SPARBIT_ERR_UNSUPPORTED;
     auto vp = std::make_unique<VarPlan>();
     vp->algo = algo;
     vp->p = p;
@@ -455,18 +533,36 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     return SPARBIT_OK;
 }
 
+int launch_var_realign(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t ncopies, uint64_t max_len,
+                       hipStream_t stream)
+{
+    dim3 grid;
+    uint32_t lg_g = 0;
+    if (!tile_grid(max_len >> 4, ncopies, WG, &grid, &lg_g)) return SPARBIT_ERR_ARG;
+    if (g_nontemporal.load() != 0)
+        hipLaunchKernelGGL((copy_var_realign_kernel<true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
+    else
+        hipLaunchKernelGGL((copy_var_realign_kernel<false>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
 template <typename V>
 int launch_var(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t ncopies, uint64_t max_len,
                hipStream_t stream)
 {
     const uint64_t tiles = (max_len / sizeof(V) + WG - 1) / WG;
     if (tiles == 0 || ncopies == 0) return SPARBIT_OK;
+    if (sizeof(V) < 16 && max_len >= uint64_t(g_realign_min_bytes.load()))
+        return launch_var_realign(src, dst, copies, ncopies, max_len, stream);
     uint32_t lg_g = uint32_t(g_interleave_log2.load());
     while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;
     const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
     const uint32_t gy = groups < 32768u ? groups : 32768u;
     const uint32_t gz = (groups + gy - 1) / gy;
-    if ((tiles << lg_g) > 0x7fffffffull / WG || gz > 65535u) return SPARBIT_ERR_ARG;
+    if (gz > 65535u) return SPARBIT_ERR_ARG;
+    if ((tiles << lg_g) > 0x7fffffffull / WG)  // a block too long for one tile per workgroup: the looping kernel
+        return launch_var_realign(src, dst, copies, ncopies, max_len, stream);
     const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
     if (g_nontemporal.load() != 0)
         hipLaunchKernelGGL((copy_var_kernel<V, true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
@@ -501,15 +597,16 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     if (!in_place && ranges_overlap(sendbufs, row_bytes, recvbufs, size_t(p) * row_bytes)) return SPARBIT_ERR_ALIAS;
     if (!any) return SPARBIT_OK;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const bool capturing = stream_is_capturing(stream);
 
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState* ds = nullptr;
     int rc = get_device_state(&ds);
     if (rc != SPARBIT_OK) return rc;
     DevicePlan* dp = nullptr;
-    if ((rc = get_plan(ds, algo, p, &dp)) != SPARBIT_OK) return rc;
+    if ((rc = get_plan(ds, algo, p, !capturing, &dp)) != SPARBIT_OK) return rc;
     VarPlan* vp = nullptr;
-    if ((rc = get_var_plan(ds, dp, algo, p, counts, displs, row_bytes, &vp)) != SPARBIT_OK) return rc;
+    if ((rc = get_var_plan(ds, dp, algo, p, counts, displs, row_bytes, !capturing, &vp)) != SPARBIT_OK) return rc;
     const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs), nullptr};
     const int width = (bits & 15) == 0 ? 16 : (bits & 3) == 0 ? 4 : 1;
     for (const VarPhase& ph : in_place ? vp->in_place : vp->out_of_place) {
@@ -555,12 +652,18 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         return SPARBIT_OK;
     }
 
+    const bool capturing = stream_is_capturing(stream);
+    if (capturing) {
+        if (mode == SPARBIT_MODE_PERSISTENT || mode == SPARBIT_MODE_DATAFLOW) return SPARBIT_ERR_UNSUPPORTED;
+        mode = SPARBIT_MODE_PER_STEP;
+    }
+
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState* ds = nullptr;
     int rc = get_device_state(&ds);
     if (rc != SPARBIT_OK) return rc;
     DevicePlan* dp = nullptr;
-    if ((rc = get_plan(ds, algo, p, &dp)) != SPARBIT_OK) return rc;
+    if ((rc = get_plan(ds, algo, p, !capturing, &dp)) != SPARBIT_OK) return rc;
     const int nsteps = int(dp->host.steps.size());
     if (!whole) {
         if (first_step < -1 || last_step < -1 || first_step > last_step || last_step >= nsteps) return SPARBIT_ERR_ARG;
@@ -571,7 +674,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     }
 
     void* work = nullptr;
-    if (algo == SPARBIT_ALGO_BRUCK && (rc = get_work(ds, recv_bytes, &work)) != SPARBIT_OK) return rc;
+    if (algo == SPARBIT_ALGO_BRUCK && (rc = get_work(ds, recv_bytes, !capturing, &work)) != SPARBIT_OK) return rc;
     const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs),
                               static_cast<const uint8_t*>(work)};
     const int width = access_width(sendbufs, recvbufs, work, B);
@@ -678,32 +781,39 @@ extern "C" {
 
 int sparbit_allgather(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, void* stream)
 {
-    return sparbit::run(sendbufs, recvbufs, p, block_bytes, SPARBIT_ALGO_SPARBIT, SPARBIT_MODE_AUTO, true, 0, 0,
-                        stream);
+    return sparbit::no_throw([&] {
+        return sparbit::run(sendbufs, recvbufs, p, block_bytes, SPARBIT_ALGO_SPARBIT, SPARBIT_MODE_AUTO, true, 0, 0,
+                            stream);
+    });
 }
 
 int sparbit_allgather_algo(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, void* stream)
 {
-    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_AUTO, true, 0, 0, stream);
+    return sparbit::no_throw(
+        [&] { return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_AUTO, true, 0, 0, stream); });
 }
 
 int sparbit_allgather_mode(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, int mode,
                            void* stream)
 {
-    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, mode, true, 0, 0, stream);
+    return sparbit::no_throw(
+        [&] { return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, mode, true, 0, 0, stream); });
 }
 
 int sparbit_allgatherv(const void* sendbufs, void* recvbufs, int p, const size_t* counts, const size_t* displs,
                        size_t row_bytes, int algo, void* stream)
 {
-    return sparbit::run_v(sendbufs, recvbufs, p, counts, displs, row_bytes, algo, stream);
+    return sparbit::no_throw(
+        [&] { return sparbit::run_v(sendbufs, recvbufs, p, counts, displs, row_bytes, algo, stream); });
 }
 
 int sparbit_allgather_steps(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, int algo, int first_step,
                             int last_step, void* stream)
 {
-    return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_PER_STEP, false, first_step, last_step,
-                        stream);
+    return sparbit::no_throw([&] {
+        return sparbit::run(sendbufs, recvbufs, p, block_bytes, algo, SPARBIT_MODE_PER_STEP, false, first_step,
+                            last_step, stream);
+    });
 }
 
 void sparbit_finalize(void)
@@ -714,6 +824,7 @@ void sparbit_finalize(void)
     for (auto& kv : sparbit::g_devices) {
         sparbit::DeviceState* ds = kv.second.get();
         if (hipSetDevice(ds->device) != hipSuccess) continue;
+        (void)hipDeviceSynchronize();  // queued launches may still read the tables
         ds->plans.clear();  // frees the device tables while this device is current
         ds->var_plans.clear();
         for (auto& bk : ds->barriers) (void)hipFree(bk.second);
@@ -748,24 +859,26 @@ int sparbit_barrier_timeouts(void* stream_v, uint64_t* count)
     if (!count) return SPARBIT_ERR_ARG;
     *count = 0;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState* ds = nullptr;
-    int rc = get_device_state(&ds);
-    if (rc != SPARBIT_OK) return rc;
-    SB_HIP(hipStreamSynchronize(stream));
-    auto it = ds->barriers.find(stream);
-    if (it != ds->barriers.end()) {
-        BarrierState host;
-        SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
-        *count += host.errors;
-    }
-    auto jt = ds->flows.find(stream);
-    if (jt != ds->flows.end() && jt->second.state) {
-        FlowState host;
-        SB_HIP(hipMemcpy(&host, jt->second.state, sizeof host, hipMemcpyDeviceToHost));
-        *count += host.errors;
-    }
-    return SPARBIT_OK;
+    return no_throw([&]() -> int {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState* ds = nullptr;
+        int rc = get_device_state(&ds);
+        if (rc != SPARBIT_OK) return rc;
+        SB_HIP(hipStreamSynchronize(stream));
+        auto it = ds->barriers.find(stream);
+        if (it != ds->barriers.end()) {
+            BarrierState host;
+            SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
+            *count += host.errors;
+        }
+        auto jt = ds->flows.find(stream);
+        if (jt != ds->flows.end() && jt->second.state) {
+            FlowState host;
+            SB_HIP(hipMemcpy(&host, jt->second.state, sizeof host, hipMemcpyDeviceToHost));
+            *count += host.errors;
+        }
+        return SPARBIT_OK;
+    });
 }
 
 int sparbit_tune(const char* key, long long value)
@@ -798,6 +911,9 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "wgs_per_cu")) {
         if (value < 1 || value > 16) return SPARBIT_ERR_ARG;
         g_wgs_per_cu = value;
+    } else if (!std::strcmp(key, "realign_min_bytes")) {
+        if (value < 16) return SPARBIT_ERR_ARG;
+        g_realign_min_bytes = value;
     } else if (!std::strcmp(key, "spin_limit_ms")) {
         if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;
         g_spin_limit_ms = value;

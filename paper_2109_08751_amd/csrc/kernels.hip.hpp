@@ -125,6 +125,78 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
 }
 
 // ---------------------------------------------------------------------------
+// Blocks whose ends do not fall on 16-byte boundaries.  Moving them with 4- or
+// 1-byte accesses costs 2x to 6x of the 16-byte rate, so the body of such a copy
+// is moved in 16-byte vectors all the same: stores are aligned on the
+// destination (whole-line writes), loads take whatever alignment the source then
+// has -- global loads on this target accept any byte address, which is what the
+// compiler itself assumes when it is handed an under-aligned vector type -- and
+// the first workgroup of the copy also moves the up to 15 bytes before the first
+// aligned vector and the up to 15 bytes after the last, one byte per lane.
+// Same shape as the kernels above: one tile per workgroup, copies dealt
+// round-robin to consecutive workgroups; the trip loop only matters for blocks
+// longer than the grid's x extent.
+// ---------------------------------------------------------------------------
+typedef u32x4 u32x4_any_align __attribute__((aligned(1)));
+
+template <int T, bool NT>
+__device__ __forceinline__ void realign_copy(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint64_t n,
+                                             uint64_t tile, uint64_t tiles_in_grid)
+{
+    static_assert(T >= 32, "head and tail take lanes 0..15 and 16..31");
+    uint32_t head = uint32_t(0u - uint32_t(reinterpret_cast<uintptr_t>(d))) & 15u;
+    if (head > n) head = uint32_t(n);
+    const uint64_t nvec = (n - head) >> 4;
+    const uint32_t tail = uint32_t(n - head) & 15u;
+    if (tile == 0) {
+        const uint32_t l = threadIdx.x;
+        if (l < head) {
+            d[l] = s[l];
+        } else if (l >= 16u && l - 16u < tail) {
+            const uint64_t o = head + (nvec << 4) + (l - 16u);
+            d[o] = s[o];
+        }
+    }
+    const u32x4_any_align* __restrict__ sv = reinterpret_cast<const u32x4_any_align*>(s + head);
+    u32x4* __restrict__ dv = reinterpret_cast<u32x4*>(d + head);
+    for (uint64_t v = tile * T + threadIdx.x; v < nvec; v += tiles_in_grid * T) {
+        u32x4 x;
+        if constexpr (NT)
+            x = __builtin_nontemporal_load(sv + v);
+        else
+            x = sv[v];
+        st<u32x4, NT, false>(dv + v, x);
+    }
+}
+
+template <int T, bool NT>
+__global__ __launch_bounds__(T) void copy_tiles_realign_kernel(const uint8_t* __restrict__ src_base,
+                                                               uint8_t* __restrict__ dst_base,
+                                                               const Copy* __restrict__ copies, uint32_t ncopies,
+                                                               uint64_t block_bytes, uint32_t lg_g)
+{
+    const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
+    const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
+    if (c >= ncopies) return;
+    const Copy cp = copies[c];
+    realign_copy<T, NT>(src_base + uint64_t(cp.src_block) * block_bytes, dst_base + uint64_t(cp.dst_block) * block_bytes,
+                        block_bytes, blockIdx.x >> lg_g, gridDim.x >> lg_g);
+}
+
+template <bool NT>
+__global__ __launch_bounds__(WG) void copy_var_realign_kernel(const uint8_t* __restrict__ src_base,
+                                                              uint8_t* __restrict__ dst_base,
+                                                              const VarCopy* __restrict__ copies, uint32_t ncopies,
+                                                              uint32_t lg_g)
+{
+    const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
+    const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
+    if (c >= ncopies) return;
+    const VarCopy cp = copies[c];
+    realign_copy<WG, NT>(src_base + cp.src_off, dst_base + cp.dst_off, cp.len, blockIdx.x >> lg_g, gridDim.x >> lg_g);
+}
+
+// ---------------------------------------------------------------------------
 // Flattened tiles: the (copy, element) space of a phase is one index range and
 // every lane finds its copy by one division, so a tile may span many short
 // blocks.  Used by the persistent kernel's grid-stride loop and, as a kernel of

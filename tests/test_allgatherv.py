@@ -207,3 +207,30 @@ def test_gpu_allgatherv_skewed_sizes():
         oracle.allgatherv(oalgo, p, counts, displs, row, send, want)
         got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
         assert np.array_equal(got, want)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_blocks_off_the_16_byte_grid():
+    """Byte-granular counts and displacements with blocks from 0 bytes to ~300 KiB: the body of every copy moves
+    in aligned 16-byte stores, head and tail byte-wise; gaps between blocks keep their poison."""
+    import torch
+    for p, seed, mis in ((5, 1, 0), (12, 2, 3), (33, 3, 8), (64, 4, 1)):
+        rng = np.random.default_rng(seed)
+        counts = rng.integers(0, 300000 // (1 + p // 16), p).astype(np.uint64)
+        counts[rng.integers(0, p)] = 0
+        counts[rng.integers(0, p)] = 1
+        counts[rng.integers(0, p)] = 513
+        gaps = rng.integers(0, 40, p).astype(np.uint64)
+        displs = (np.concatenate([[0], np.cumsum(counts[:-1] + gaps[:-1])]) + 5).astype(np.uint64)
+        row = int(displs[-1] + counts[-1] + 9)
+        send = np.tile(workloads.make_send_raw(1, 65536, seed).reshape(-1), row // 65536 + 1)[:row].copy()
+        for in_place in (False, True):
+            print("[case] off-grid allgatherv", p, mis, in_place, flush=True)
+            want = np.full((p, row), POISON, dtype=np.uint8)
+            if in_place:
+                for r in range(p):
+                    d, c = int(displs[r]), int(counts[r])
+                    want[r, d:d + c] = send[d:d + c]
+            oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
+            got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+            assert np.array_equal(got, want), (p, in_place)

@@ -41,12 +41,14 @@ def oracle_result(algo, p, B, send, max_steps=-1, in_place=False):
     return recv
 
 
-def gpu_buffers(torch, p, B, send, in_place=False, misalign=0):
-    """Device send / poison-filled recv; `misalign` shifts both base addresses."""
+def gpu_buffers(torch, p, B, send, in_place=False, misalign=0, send_misalign=None):
+    """Device send / poison-filled recv; `misalign` shifts both base addresses (`send_misalign`: the send
+    buffer's own shift)."""
     dev = torch.device("cuda:0")
     sraw = torch.empty(p * B + 64, dtype=torch.uint8, device=dev)
     rraw = torch.full((p * p * B + 64,), POISON, dtype=torch.uint8, device=dev)
-    d_send = sraw[misalign:misalign + p * B]
+    ms = misalign if send_misalign is None else send_misalign
+    d_send = sraw[ms:ms + p * B]
     d_recv = rraw[misalign:misalign + p * p * B]
     d_send.copy_(torch.from_numpy(send.reshape(-1)))
     if in_place:
@@ -56,8 +58,8 @@ def gpu_buffers(torch, p, B, send, in_place=False, misalign=0):
     return d_send, d_recv, (sraw, rraw)
 
 
-def gpu_result(torch, algo, p, B, send, mode, in_place=False, misalign=0):
-    d_send, d_recv, keep = gpu_buffers(torch, p, B, send, in_place, misalign)
+def gpu_result(torch, algo, p, B, send, mode, in_place=False, misalign=0, send_misalign=None):
+    d_send, d_recv, keep = gpu_buffers(torch, p, B, send, in_place, misalign, send_misalign)
     sb.sparbit_allgather_mode(None if in_place else d_send.data_ptr(), d_recv.data_ptr(), p, B, algo, mode)
     torch.cuda.synchronize()
     assert sb.sparbit_barrier_timeouts() == 0
@@ -118,6 +120,40 @@ def test_misaligned_base_pointers(torch, mode, misalign):
         want = oracle_result(sb.SPARBIT, p, B, send)
         got = gpu_result(torch, sb.SPARBIT, p, B, send, MODES[mode], misalign=misalign)
         assert np.array_equal(got, want), (p, B)
+
+
+@pytest.mark.parametrize("algo", [sb.SPARBIT, sb.RING, sb.BRUCK, sb.DIRECT])
+def test_blocks_off_the_16_byte_grid(torch, algo):
+    """Blocks whose ends fall between 16-byte boundaries, source and destination shifted against each other:
+    aligned body, byte-wise head and tail.  The bytes around the receive buffer must stay untouched."""
+    cases = ((5, 513, 0, 0), (7, 1000, 3, 9), (8, 4099, 1, 0), (3, 70001, 15, 2), (12, (1 << 20) + 7, 5, 11),
+             (16, 515, 0, 4), (9, 4100, 4, 8), (2, 1 << 16, 7, 7))
+    for p, B, ms, mr in cases:
+        send = workloads.make_send_raw(p, B, seed=B)
+        for in_place in (False, True):
+            if in_place and algo == sb.BRUCK:
+                continue
+            announce("off grid", algo, p, B, ms, mr, in_place)
+            want = oracle_result(algo, p, B, send, in_place=in_place)
+            got = gpu_result(torch, algo, p, B, send, sb.MODE_PER_STEP, in_place=in_place, misalign=mr,
+                             send_misalign=ms)
+            assert np.array_equal(got, want), (p, B, ms, mr, in_place)
+
+
+def test_realigning_kernel_on_tiny_blocks(torch):
+    """The same kernel forced onto blocks of 16..600 bytes: heads that reach the end of the block, bodies of zero
+    or one vector, every relative shift of source and destination."""
+    sb.sparbit_tune("realign_min_bytes", 16)
+    try:
+        for B in (17, 18, 23, 31, 33, 47, 63, 100, 255, 257, 600):
+            for p, ms, mr in ((5, 0, 1), (6, 13, 0), (9, 2, 15)):
+                announce("tiny realign", p, B, ms, mr)
+                send = workloads.make_send_raw(p, B, seed=B + p)
+                want = oracle_result(sb.SPARBIT, p, B, send)
+                got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_PER_STEP, misalign=mr, send_misalign=ms)
+                assert np.array_equal(got, want), (p, B, ms, mr)
+    finally:
+        sb.sparbit_tune("realign_min_bytes", 512)
 
 
 @pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
@@ -316,6 +352,46 @@ def test_capture_in_a_hip_graph(torch):
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
+
+
+def test_capture_of_an_auto_call_records_the_per_step_form(torch):
+    """A small AUTO call runs the dataflow kernel when issued eagerly; that kernel's call number is a launch
+    argument, so a replay would find every ready flag already set.  On a capturing stream AUTO therefore records
+    the per-step launches, the self-waiting modes are refused, and so is a call whose tables do not exist yet;
+    the refused calls record nothing, so the graph still replays correctly."""
+    w = workloads.WORKLOADS["cfg1"]
+    p, B = w.p, w.block_bytes
+    send = workloads.make_send(w)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    st = torch.cuda.Stream()
+    refused = []
+    sb.sparbit_finalize()  # drop every cached table, so that (Ring, 7) below is certainly absent
+    with torch.cuda.stream(st):
+        sb.sparbit_allgather(d_send, d_recv, p, B, st)  # eager: builds the tables
+        st.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            cur = torch.cuda.current_stream()
+            for mode in (sb.MODE_DATAFLOW, sb.MODE_PERSISTENT):
+                try:
+                    sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, mode, cur)
+                except sb.SparbitError as e:
+                    refused.append(e.code)
+            try:
+                sb.sparbit_allgather_algo(d_send, d_recv, 7, 16, sb.RING, cur)  # (Ring, 7) was never built
+            except sb.SparbitError as e:
+                refused.append(e.code)
+            sb.sparbit_allgather(d_send, d_recv, p, B, cur)
+    assert refused == [-3, -3, -3]
+    for rep in range(3):
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
+    assert sb.sparbit_barrier_timeouts(st) == 0
 
 
 def test_maximum_rank_count(torch):
