@@ -15,9 +15,11 @@
  *             drained) slot k of every rank holds rank k's block: the
  *             MPI_Allgather post-condition of Section II of the paper.
  *   Blocks are opaque bytes; the MPI (count, datatype) pair collapses into
- *   block_bytes.  Any block_bytes is accepted; copies use 16-byte
- *   accesses when both base pointers and block_bytes are multiples of 16,
- *   4-byte accesses when they are multiples of 4, single bytes otherwise.
+ *   block_bytes.  Any block_bytes and any base alignment is accepted.  The
+ *   full rate needs base pointers and block_bytes that are multiples of 16;
+ *   otherwise blocks of 512 bytes and more still move in 16-byte vectors
+ *   (aligned stores, unaligned loads, ~80-95 % of the aligned rate) and
+ *   shorter ones with 4-byte or single-byte accesses.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
@@ -187,6 +189,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
  *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
+ *   "realign_min_bytes"    blocks at least this long that are off the 16-byte grid use the realigning kernel (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  */
 int sparbit_tune(const char *key, long long value);

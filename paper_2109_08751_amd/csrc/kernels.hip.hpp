@@ -131,8 +131,8 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
 // destination (whole-line writes), loads take whatever alignment the source then
 // has -- global loads on this target accept any byte address, which is what the
 // compiler itself assumes when it is handed an under-aligned vector type -- and
-// the first workgroup of the copy also moves the up to 15 bytes before the first
-// aligned vector and the up to 15 bytes after the last, one byte per lane.
+// the first workgroup of the copy also moves the bytes before the first aligned
+// vector and the up to 15 bytes after the last, one byte per lane.
 // Same shape as the kernels above: one tile per workgroup, copies dealt
 // round-robin to consecutive workgroups; the trip loop only matters for blocks
 // longer than the grid's x extent.
@@ -143,17 +143,17 @@ template <int T, bool NT>
 __device__ __forceinline__ void realign_copy(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint64_t n,
                                              uint64_t tile, uint64_t tiles_in_grid)
 {
-    static_assert(T >= 32, "head and tail take lanes 0..15 and 16..31");
-    uint32_t head = uint32_t(0u - uint32_t(reinterpret_cast<uintptr_t>(d))) & 15u;
+    // Long blocks start their vectors on a 128-byte line of the destination, so that every wavefront's store
+    // covers whole lines (measured: 5.5 against 5.3 TB/s on 256 KiB blocks); short ones settle for 16 bytes.
+    const uint32_t align_mask = n >= 32768u ? 127u : 15u;
+    uint32_t head = uint32_t(0u - uint32_t(reinterpret_cast<uintptr_t>(d))) & align_mask;
     if (head > n) head = uint32_t(n);
     const uint64_t nvec = (n - head) >> 4;
     const uint32_t tail = uint32_t(n - head) & 15u;
     if (tile == 0) {
-        const uint32_t l = threadIdx.x;
-        if (l < head) {
-            d[l] = s[l];
-        } else if (l >= 16u && l - 16u < tail) {
-            const uint64_t o = head + (nvec << 4) + (l - 16u);
+        for (uint32_t l = threadIdx.x; l < head; l += T) d[l] = s[l];
+        if (threadIdx.x < tail) {
+            const uint64_t o = head + (nvec << 4) + threadIdx.x;
             d[o] = s[o];
         }
     }
@@ -165,7 +165,7 @@ __device__ __forceinline__ void realign_copy(const uint8_t* __restrict__ s, uint
             x = __builtin_nontemporal_load(sv + v);
         else
             x = sv[v];
-        st<u32x4, NT, false>(dv + v, x);
+        st<u32x4, NT, false>(dv + v, x);  // write-through is slower here (4.4-5.5 against 5.3-6.4 TB/s)
     }
 }
 
