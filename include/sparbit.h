@@ -71,7 +71,7 @@ extern "C" {
 #define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
 #define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
 #define SPARBIT_MODE_DATAFLOW 3   /* one launch; no barrier: a copy starts when the chunk it forwards has landed
-                                     (ready flag per chunk of a receive slot); in-place calls use PER_STEP.
+                                     (ready flag per chunk of a receive slot).
                                      PERSISTENT and DATAFLOW grids wait on themselves and need all their
                                      workgroups resident: they take at most half of the GPU's wave slots, their
                                      waits are bounded (see sparbit_barrier_timeouts), and AUTO picks them only

@@ -687,7 +687,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
         const uint64_t chunk = uint64_t(g_flow_chunk_bytes.load());
         const uint64_t items = copies_total * ((B + chunk - 1) / chunk);
-        if (!in_place && items <= uint64_t(g_dataflow_max_items.load()))
+        if (items <= uint64_t(g_dataflow_max_items.load()))
             mode = SPARBIT_MODE_DATAFLOW;
         else if (recv_bytes <= size_t(g_persistent_max_bytes.load()))
             mode = SPARBIT_MODE_PERSISTENT;  // at most 16 workgroups of flattened tiles: the barrier is cheap there
@@ -695,9 +695,8 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             mode = SPARBIT_MODE_PER_STEP;
     }
 
-    // Dataflow form: flags instead of barriers.  In-place calls have no item that
-    // would publish the flags of the own slots, so they take the per-step path.
-    if (whole && mode == SPARBIT_MODE_DATAFLOW && !in_place && !phases.empty()) {
+    // Dataflow form: flags instead of barriers.
+    if (whole && mode == SPARBIT_MODE_DATAFLOW && !phases.empty()) {
         const size_t unit = width == 16 ? 8 : size_t(width);  // widest single-copy atomic access is 8 bytes
         size_t chunk = size_t(g_flow_chunk_bytes.load());
         chunk -= chunk % 16;
@@ -715,7 +714,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             a.base[1] = base[1];
             a.base[2] = base[2];
             a.copies = dp->d_copies;
-            a.phases = dp->d_phases;
+            a.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
             a.state = fs->state;
             a.flags = fs->flags;
             a.block_bytes = B;
@@ -727,6 +726,8 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             if (++fs->epoch == 0) fs->epoch = 1;  // wrapped: 0 stays reserved for "never filled"
             a.epoch = fs->epoch;
             a.total_items = uint32_t(items);
+            a.p = uint32_t(p);
+            a.in_place = in_place ? 1u : 0u;
             switch (width) {
             case 16: return launch_dataflow_v<uint64_t>(a, ds, stream);
             case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);

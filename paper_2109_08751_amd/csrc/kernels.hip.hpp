@@ -349,8 +349,8 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
 // Items are numbered in phase order and dealt round-robin to the workgroups of
 // a grid that the host sizes to be fully resident; a workgroup takes its items
 // in increasing order, waits for the flag of the item's source chunk (unless
-// the source is the send buffer), copies, and publishes the flag of the
-// destination chunk.  An item only waits for an
+// the source is the send buffer or, in place, a rank's own slot), copies, and
+// publishes the flag of the destination chunk.  An item only waits for an
 // item of an earlier phase, i.e. a lower number, so the lowest unfinished item
 // can always run: no deadlock while all workgroups are resident.  Waits are
 // bounded all the same.
@@ -397,6 +397,8 @@ struct FlowArgs {
     uint32_t flags_per_buf;
     uint32_t epoch;          // number of this call on its stream, never 0
     uint32_t total_items;
+    uint32_t p;
+    uint32_t in_place;       // 1: slot r of rank r was filled by the caller before the call; nobody flags it
 };
 
 template <typename V>
@@ -413,7 +415,10 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
         const uint32_t v0 = q * a.chunk_vecs;
         const uint32_t v1 = (vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
-        if (P.src_buf != BUF_SEND) {
+        // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
+        // the own slot of every rank (block index rank * p + rank of the receive buffer).
+        const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
+        if (P.src_buf != BUF_SEND && !own_slot) {
             if (threadIdx.x == 0) {
                 const uint32_t* f = a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) +
                                     cp.src_block * a.chunks_per_block + q;
