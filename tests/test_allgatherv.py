@@ -234,3 +234,35 @@ def test_gpu_allgatherv_blocks_off_the_16_byte_grid():
             oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
             got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place, misalign=mis)
             assert np.array_equal(got, want), (p, in_place)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_block_with_more_tiles_than_the_grid_holds():
+    """Eight copies of a block of 4 GiB + 48 B in one launch (DIRECT, p = 8, the other blocks tiny): the looping
+    kernel takes over.  Expected state: every receive buffer equals the send layout inside the blocks (the
+    Allgatherv definition the oracle is pinned to) and keeps its poison in the gaps; compared on the device."""
+    import torch
+    p = 8
+    counts = np.array([16, 48, (4 << 30) + 48, 0, 4096, 16, 1024, 32], dtype=np.uint64)
+    displs = np.concatenate([[0], np.cumsum(counts[:-1] + 16)]).astype(np.uint64)
+    row = int(displs[-1] + counts[-1] + 16)
+    dev = torch.device("cuda:0")
+    print("[case] allgatherv, more tiles than the grid", flush=True)
+    d_send = torch.empty(row, dtype=torch.uint8, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(5)
+    piece = torch.randint(0, 256, ((1 << 28) + 12347,), dtype=torch.uint8, device=dev, generator=g)
+    for at in range(0, row, piece.numel()):
+        n = min(piece.numel(), row - at)
+        d_send[at:at + n] = piece[:n]
+    want = torch.full((row,), POISON, dtype=torch.uint8, device=dev)
+    for k in range(p):
+        d, c = int(displs[k]), int(counts[k])
+        want[d:d + c] = d_send[d:d + c]
+    d_recv = torch.full((p * row,), POISON, dtype=torch.uint8, device=dev)
+    sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.DIRECT)
+    torch.cuda.synchronize()
+    for r in range(p):
+        assert torch.equal(d_recv[r * row:(r + 1) * row], want), r
+    del d_send, d_recv, want, piece
+    torch.cuda.empty_cache()

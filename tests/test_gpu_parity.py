@@ -409,7 +409,7 @@ def test_maximum_rank_count(torch):
 @pytest.mark.parametrize("extra,in_place", [(4112, False), (4112, True), (4, False)])
 def test_blocks_larger_than_4_gib(torch, extra, in_place):
     """Offsets inside one block beyond 32 bits: p = 2 with blocks of 4 GiB + a ragged tail
-    (16-byte path, and the 4-byte flat path whose element index needs 64 bits).  The expected
+    (16-byte path, and a size that is only a multiple of 4: the realigning kernel).  The expected
     state is the oracle's, taken from its run on rank tags."""
     p, B = 2, (4 << 30) + extra
     announce("huge blocks", B, in_place)
@@ -427,6 +427,39 @@ def test_blocks_larger_than_4_gib(torch, extra, in_place):
         for k in range(p):
             assert torch.equal(d_recv[r, k], d_send[origin[r, k]]), (r, k)
     del d_send, d_recv
+    torch.cuda.empty_cache()
+
+
+def _fill_aperiodic(torch, t, seed):
+    """Fill a flat uint8 device tensor from a random piece whose length shares no factor with any tile, grid or
+    block size, so that data copied from a wrong offset cannot look right."""
+    g = torch.Generator(device=t.device)
+    g.manual_seed(seed)
+    piece = torch.randint(0, 256, ((1 << 28) + 12347,), dtype=torch.uint8, device=t.device, generator=g)
+    for at in range(0, t.numel(), piece.numel()):
+        n = min(piece.numel(), t.numel() - at)
+        t[at:at + n] = piece[:n]
+
+
+@pytest.mark.parametrize("shift", [0, 4])
+def test_blocks_with_more_tiles_than_the_grid_holds(torch, shift):
+    """Nine copies of 4 GiB + 4112-byte blocks in one launch (DIRECT, p = 3): one tile per workgroup would need
+    more than 2^31 lanes along x, so the kernels take several trips (the aligned tile kernel, and with the base
+    addresses shifted by 4 bytes the realigning one).  Expected state: the Allgather definition (Section II),
+    which is what the oracle's DIRECT schedule is pinned to; compared on the device."""
+    p, B = 3, (4 << 30) + 4112
+    announce("more tiles than the grid", shift)
+    dev = torch.device("cuda:0")
+    sraw = torch.empty(p * B + 16, dtype=torch.uint8, device=dev)
+    rraw = torch.full((p * p * B + 16,), POISON, dtype=torch.uint8, device=dev)
+    d_send, d_recv = sraw[shift:shift + p * B], rraw[shift:shift + p * p * B]
+    _fill_aperiodic(torch, d_send, 77 + shift)
+    sb.sparbit_allgather_mode(d_send.data_ptr(), d_recv.data_ptr(), p, B, sb.DIRECT, sb.MODE_PER_STEP)
+    torch.cuda.synchronize()
+    for r in range(p):
+        assert torch.equal(d_recv[r * p * B:(r + 1) * p * B], d_send), r
+    assert bool((rraw[:shift] == POISON).all()) and bool((rraw[shift + p * p * B:] == POISON).all())
+    del d_send, d_recv, sraw, rraw
     torch.cuda.empty_cache()
 
 
