@@ -697,7 +697,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
 
     // Dataflow form: flags instead of barriers.
     if (whole && mode == SPARBIT_MODE_DATAFLOW && !phases.empty()) {
-        const size_t unit = width == 16 ? 8 : size_t(width);  // widest single-copy atomic access is 8 bytes
+        const size_t unit = size_t(width);
         size_t chunk = size_t(g_flow_chunk_bytes.load());
         chunk -= chunk % 16;
         if (chunk < 16) chunk = 16;
@@ -729,7 +729,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             a.p = uint32_t(p);
             a.in_place = in_place ? 1u : 0u;
             switch (width) {
-            case 16: return launch_dataflow_v<uint64_t>(a, ds, stream);
+            case 16: return launch_dataflow_v<u32x4>(a, ds, stream);
             case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);
             default: return launch_dataflow_v<uint8_t>(a, ds, stream);
             }

@@ -361,7 +361,7 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
 //  - an agent-scope release / acquire is a write-back / invalidate of the whole
 //    L2 of the XCD (~300 ns each, serialised per XCD), far too much per chunk.
 //    Instead every data access is itself coherent at agent scope (relaxed
-//    atomic loads and stores of 8, 4 or 1 bytes: they go past the XCD's L2 to
+//    atomic loads and stores of 4 or 1 bytes, sc1 on the 16-byte ones: past the XCD's L2 to
 //    the memory side), so no cache maintenance is needed: a wave waits for its
 //    own stores to be acknowledged (s_waitcnt vmcnt(0)), the workgroup meets at
 //    a barrier, and one lane stores the flag.
@@ -376,6 +376,38 @@ template <typename V>
 __device__ __forceinline__ void coherent_st(V* p, V v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 16-byte forms of the same coherent accesses.  The language offers no 16-byte atomic, and none is needed: the
+// flag protocol orders the data, the accesses only have to go past the XCD's L2 like the ones above, which is the
+// sc1 bit on the plain 16-byte instructions.  The compiler does not track loads issued from asm, so a group of
+// four is issued and waited for inside one statement.
+__device__ __forceinline__ void coherent_ld4(const u32x4* p0, const u32x4* p1, const u32x4* p2, const u32x4* p3,
+                                             u32x4& x0, u32x4& x1, u32x4& x2, u32x4& x3)
+{
+    asm volatile(
+        "global_load_dwordx4 %0, %4, off sc1\n\t"
+        "global_load_dwordx4 %1, %5, off sc1\n\t"
+        "global_load_dwordx4 %2, %6, off sc1\n\t"
+        "global_load_dwordx4 %3, %7, off sc1\n\t"
+        "s_waitcnt vmcnt(0)"
+        : "=&v"(x0), "=&v"(x1), "=&v"(x2), "=&v"(x3)
+        : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+        : "memory");
+}
+
+template <>
+__device__ __forceinline__ u32x4 coherent_ld<u32x4>(const u32x4* p)
+{
+    u32x4 x;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=&v"(x) : "v"(p) : "memory");
+    return x;
+}
+
+template <>
+__device__ __forceinline__ void coherent_st<u32x4>(u32x4* p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
 }
 
 struct FlowState {
@@ -442,15 +474,29 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         }
         const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
         V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
-        constexpr int U = 8;
-        for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
-            V x[U];
+        if constexpr (sizeof(V) == 16) {
+            uint32_t v = v0;
+            for (; v1 - v >= 4u * WG; v += 4u * WG) {  // whole groups: four vectors per lane in flight
+                const uint32_t l = v + threadIdx.x;
+                V x0, x1, x2, x3;
+                coherent_ld4(s + l, s + l + WG, s + l + 2 * WG, s + l + 3 * WG, x0, x1, x2, x3);
+                coherent_st<V>(d + l, x0);
+                coherent_st<V>(d + l + WG, x1);
+                coherent_st<V>(d + l + 2 * WG, x2);
+                coherent_st<V>(d + l + 3 * WG, x3);
+            }
+            for (v += threadIdx.x; v < v1; v += WG) coherent_st<V>(d + v, coherent_ld<V>(s + v));
+        } else {
+            constexpr int U = 8;
+            for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
+                V x[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (v + u * WG < v1) x[u] = coherent_ld<V>(s + v + u * WG);
+                for (int u = 0; u < U; ++u)
+                    if (v + u * WG < v1) x[u] = coherent_ld<V>(s + v + u * WG);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
+                for (int u = 0; u < U; ++u)
+                    if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
+            }
         }
         // Own stores acknowledged by the memory side, then the workgroup meets, then the flag.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
