@@ -288,21 +288,35 @@ def main():
             per[name] = row
             del r_, dst, s_
             torch.cuda.empty_cache()
-        # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB)
+        # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB), at three
+        # granularities: 4 KiB (every block on the 16-byte grid), 4 bytes and 1 byte (the realigning kernel).
         import numpy as np
         pv = 128
-        rng = np.random.default_rng(workloads.DEFAULT_SEED)
-        counts = (rng.integers(512 << 10, (1536 << 10) + 1, pv) // 4096 * 4096).astype(np.uint64)
-        displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)
-        row = int(counts.sum())
-        s_ = torch.randint(0, 256, (row,), dtype=torch.uint8, device=dev)
-        r_ = torch.full((pv, row), workloads.POISON, dtype=torch.uint8, device=dev)
-        t = time_calls(torch, lambda: sb.sparbit_allgatherv(s_, r_, pv, counts, displs, row, sb.SPARBIT, stream),
+        for label, grain in (("allgatherv_p128_0.5-1.5MiB", 4096), ("allgatherv_p128_0.5-1.5MiB_grain4B", 4),
+                             ("allgatherv_p128_0.5-1.5MiB_grain1B", 1)):
+            rng = np.random.default_rng(workloads.DEFAULT_SEED)
+            counts = (rng.integers(512 << 10, (1536 << 10) + 1, pv) // grain * grain).astype(np.uint64)
+            displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)
+            row = int(counts.sum())
+            s_ = torch.randint(0, 256, (row,), dtype=torch.uint8, device=dev)
+            r_ = torch.full((pv, row), workloads.POISON, dtype=torch.uint8, device=dev)
+            t = time_calls(torch, lambda: sb.sparbit_allgatherv(s_, r_, pv, counts, displs, row, sb.SPARBIT, stream),
+                           stream, 3, 10)
+            per[label] = {
+                "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6,
+                "hbm_GBps": 2 * pv * row / t["avg_ms"] / 1e6,
+                "hbm_frac": 2 * pv * row / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+                "ok": bool(torch.equal(r_[pv - 1], s_))}
+            del s_, r_
+            torch.cuda.empty_cache()
+        # Equal blocks off the 16-byte grid: cfg4's shape with 4 more bytes per block
+        pu, Bu = 128, (1 << 20) + 4
+        s_ = torch.randint(0, 256, (pu, Bu), dtype=torch.uint8, device=dev)
+        r_ = torch.full((pu, pu, Bu), workloads.POISON, dtype=torch.uint8, device=dev)
+        t = time_calls(torch, lambda: sb.sparbit_allgather_mode(s_, r_, pu, Bu, sb.SPARBIT, sb.MODE_AUTO, stream),
                        stream, 3, 10)
-        per["allgatherv_p128_0.5-1.5MiB"] = {
-            "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6,
-            "hbm_GBps": 2 * pv * row / t["avg_ms"] / 1e6, "hbm_frac": 2 * pv * row / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
-            "ok": bool(torch.equal(r_[pv - 1], s_))}
+        per["sparbit_p128_1MiB+4B"] = {"p": pu, "block_bytes": Bu, **t, **rates(pu, Bu, t["avg_ms"]),
+                                       "ok": bool(torch.equal(r_[pu - 1], s_))}
         del s_, r_
         torch.cuda.empty_cache()
         out["per_config"] = per
