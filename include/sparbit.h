@@ -85,7 +85,7 @@ extern "C" {
  *   sendbufs    device, p * block_bytes bytes; NULL = in place (as MPI_IN_PLACE:
  *               recvbufs slot r of rank r already holds rank r's block).
  *   recvbufs    device, p * p * block_bytes bytes.
- *   stream      a hipStream_t (NULL = the null stream).
+ *   stream      a hipStream_t of the current device (NULL = the null stream).
  * p = 1 is legal (no steps, the own block is placed).  block_bytes = 0 is legal
  * and does nothing (MPI allows a zero count).
  */

@@ -684,6 +684,8 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         // The single-launch dataflow form only where the whole job is a handful of workgroups: a grid that
         // waits on itself while it holds much of the machine starves whatever else runs on the GPU (and is
         // starved by it).  Anything larger goes out as one launch per step, which never waits on the device.
+        // (With the default limit the grid has one workgroup per item, and an item only waits for items of
+        // lower-numbered workgroups, which are dispatched first.)
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
         const uint64_t chunk = uint64_t(g_flow_chunk_bytes.load());
         const uint64_t items = copies_total * ((B + chunk - 1) / chunk);
