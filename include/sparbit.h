@@ -67,7 +67,9 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes */
+#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes: DATAFLOW for jobs of at most 256 work items,
+                                     PERSISTENT for other jobs of at most 64 KiB, else PER_STEP with the first small
+                                     steps (at most 1024 work items) merged into one DATAFLOW launch */
 #define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
 #define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
 #define SPARBIT_MODE_DATAFLOW 3   /* one launch; no barrier: a copy starts when the chunk it forwards has landed
@@ -185,6 +187,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          (block copies x chunks per block)
  *   "persistent_max_bytes" else AUTO uses the persistent kernel when p*p*block_bytes is at most this;
  *                          otherwise one launch per step
+ *   "hybrid_max_items"     ... where the leading steps that together have at most this many work items (0..1024;
+ *                          one workgroup each) share one dataflow launch; 0 = every step its own launch
  *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16)
  *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint

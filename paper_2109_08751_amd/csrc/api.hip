@@ -64,6 +64,7 @@ std::atomic<long long> g_interleave_log2{3};                  // copies interlea
 std::atomic<long long> g_nontemporal{1};
 std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO uses the persistent kernel up to this p*p*B
 std::atomic<long long> g_dataflow_max_items{256};             // AUTO uses the dataflow kernel up to this many work items
+std::atomic<long long> g_hybrid_max_items{1024};              // AUTO: leading steps with at most this many items share one dataflow launch
 std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
 std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
@@ -680,63 +681,81 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     const int width = access_width(sendbufs, recvbufs, work, B);
 
     const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
+    size_t flow_chunk = size_t(g_flow_chunk_bytes.load());
+    flow_chunk -= flow_chunk % 16;
+    if (flow_chunk < 16) flow_chunk = 16;
+    const uint64_t cpb = (B + flow_chunk - 1) / flow_chunk;  // dataflow work items (and ready flags) per block
+    size_t flow_prefix = 0;  // leading phases that go out as one dataflow launch ahead of per-step launches
     if (mode == SPARBIT_MODE_AUTO) {
         // The single-launch dataflow form only where the whole job is a handful of workgroups: a grid that
         // waits on itself while it holds much of the machine starves whatever else runs on the GPU (and is
-        // starved by it).  Anything larger goes out as one launch per step, which never waits on the device.
-        // (With the default limit the grid has one workgroup per item, and an item only waits for items of
-        // lower-numbered workgroups, which are dispatched first.)
+        // starved by it).  Anything larger goes out as one launch per step, which never waits on the device --
+        // except that the first steps of a log-step schedule are small, so as many leading phases as fit in
+        // one workgroup per item share one dataflow launch (a flag hand-over costs less than a kernel boundary).
+        // With one workgroup per item an item only waits for lower-numbered workgroups, which are dispatched
+        // first, so these grids do not depend on residency.
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
-        const uint64_t chunk = uint64_t(g_flow_chunk_bytes.load());
-        const uint64_t items = copies_total * ((B + chunk - 1) / chunk);
-        if (items <= uint64_t(g_dataflow_max_items.load()))
+        if (copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
             mode = SPARBIT_MODE_DATAFLOW;
-        else if (recv_bytes <= size_t(g_persistent_max_bytes.load()))
+        } else if (recv_bytes <= size_t(g_persistent_max_bytes.load())) {
             mode = SPARBIT_MODE_PERSISTENT;  // at most 16 workgroups of flattened tiles: the barrier is cheap there
-        else
+        } else {
             mode = SPARBIT_MODE_PER_STEP;
+            const uint64_t limit = uint64_t(g_hybrid_max_items.load());
+            while (flow_prefix < phases.size() &&
+                   (phases[flow_prefix].copies_before + phases[flow_prefix].ncopies) * cpb <= limit)
+                ++flow_prefix;
+            if (flow_prefix < 2) flow_prefix = 0;  // nothing to merge
+        }
     }
 
-    // Dataflow form: flags instead of barriers.
-    if (whole && mode == SPARBIT_MODE_DATAFLOW && !phases.empty()) {
+    // Dataflow form (flags instead of barriers) for the first `nph` phases of the call.
+    auto launch_flow = [&](size_t nph, bool* launched) -> int {
+        *launched = false;
         const size_t unit = size_t(width);
-        size_t chunk = size_t(g_flow_chunk_bytes.load());
-        chunk -= chunk % 16;
-        if (chunk < 16) chunk = 16;
-        const uint64_t cpb = (B + chunk - 1) / chunk;
-        const uint64_t ncopies_total = phases.back().copies_before + phases.back().ncopies;
-        const uint64_t items = ncopies_total * cpb;
+        const uint64_t items = (phases[nph - 1].copies_before + phases[nph - 1].ncopies) * cpb;
         const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
-        if (items <= 0x7fffffffull && flags_per_buf <= 0x3fffffffull && chunk / unit <= 0xffffffffull) {
-            FlowStream* fs = nullptr;
-            if ((rc = get_flow(ds, stream, size_t(2 * flags_per_buf), &fs)) != SPARBIT_OK) return rc;
-            FlowArgs a;
-            std::memset(&a, 0, sizeof a);
-            a.base[0] = base[0];
-            a.base[1] = base[1];
-            a.base[2] = base[2];
-            a.copies = dp->d_copies;
-            a.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
-            a.state = fs->state;
-            a.flags = fs->flags;
-            a.block_bytes = B;
-            a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
-            a.nphases = uint32_t(phases.size());
-            a.chunks_per_block = uint32_t(cpb);
-            a.chunk_vecs = uint32_t(chunk / unit);
-            a.flags_per_buf = uint32_t(flags_per_buf);
-            if (++fs->epoch == 0) fs->epoch = 1;  // wrapped: 0 stays reserved for "never filled"
-            a.epoch = fs->epoch;
-            a.total_items = uint32_t(items);
-            a.p = uint32_t(p);
-            a.in_place = in_place ? 1u : 0u;
-            switch (width) {
-            case 16: return launch_dataflow_v<u32x4>(a, ds, stream);
-            case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);
-            default: return launch_dataflow_v<uint8_t>(a, ds, stream);
-            }
+        if (items > 0x7fffffffull || flags_per_buf > 0x3fffffffull || flow_chunk / unit > 0xffffffffull)
+            return SPARBIT_OK;  // too many items for one grid
+        FlowStream* fs = nullptr;
+        int frc = get_flow(ds, stream, size_t(2 * flags_per_buf), &fs);
+        if (frc != SPARBIT_OK) return frc;
+        FlowArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.base[0] = base[0];
+        a.base[1] = base[1];
+        a.base[2] = base[2];
+        a.copies = dp->d_copies;
+        a.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
+        a.state = fs->state;
+        a.flags = fs->flags;
+        a.block_bytes = B;
+        a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
+        a.nphases = uint32_t(nph);
+        a.chunks_per_block = uint32_t(cpb);
+        a.chunk_vecs = uint32_t(flow_chunk / unit);
+        a.flags_per_buf = uint32_t(flags_per_buf);
+        if (++fs->epoch == 0) fs->epoch = 1;  // wrapped: 0 stays reserved for "never filled"
+        a.epoch = fs->epoch;
+        a.total_items = uint32_t(items);
+        a.p = uint32_t(p);
+        a.in_place = in_place ? 1u : 0u;
+        *launched = true;
+        switch (width) {
+        case 16: return launch_dataflow_v<u32x4>(a, ds, stream);
+        case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);
+        default: return launch_dataflow_v<uint8_t>(a, ds, stream);
         }
-        mode = SPARBIT_MODE_PER_STEP;  // too many items for one grid
+    };
+    if (whole && mode == SPARBIT_MODE_DATAFLOW && !phases.empty()) {
+        bool launched = false;
+        if ((rc = launch_flow(phases.size(), &launched)) != SPARBIT_OK || launched) return rc;
+        mode = SPARBIT_MODE_PER_STEP;
+    }
+    if (flow_prefix) {
+        bool launched = false;
+        if ((rc = launch_flow(flow_prefix, &launched)) != SPARBIT_OK) return rc;
+        if (!launched) flow_prefix = 0;
     }
 
     if (whole && mode == SPARBIT_MODE_PERSISTENT && !phases.empty()) {
@@ -764,12 +783,15 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     }
 
     // One launch per phase; stream order is the Waitall.
+    size_t active = 0;  // index of the phase in `phases` (the list the single-launch kernels walk)
     for (size_t i = 0; i < dp->host.phases.size(); ++i) {
         const Phase& ph = dp->host.phases[i];
         if (in_place ? ph.skip_in_place : ph.only_in_place) continue;
         if (whole && !in_place ? ph.covered_by_fused : ph.fused_first) continue;
         const int step = (ph.step >= nsteps) ? nsteps - 1 : ph.step;  // Bruck's rotation rides with the last step
         if (step < first_step || step > last_step) continue;
+        if (ph.copies.empty()) continue;
+        if (active++ < flow_prefix) continue;  // already done by the dataflow launch above
         rc = launch_phase(base[ph.src_buf], const_cast<uint8_t*>(base[ph.dst_buf]), dp->d_copies + dp->first_copy[i],
                           uint32_t(ph.copies.size()), B, width, stream);
         if (rc != SPARBIT_OK) return rc;
@@ -900,6 +922,9 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "persistent_max_bytes")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_persistent_max_bytes = value;
+    } else if (!std::strcmp(key, "hybrid_max_items")) {
+        if (value < 0 || value > 1024) return SPARBIT_ERR_ARG;
+        g_hybrid_max_items = value;
     } else if (!std::strcmp(key, "dataflow_max_items")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_dataflow_max_items = value;

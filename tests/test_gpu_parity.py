@@ -394,6 +394,26 @@ def test_capture_of_an_auto_call_records_the_per_step_form(torch):
     assert sb.sparbit_barrier_timeouts(st) == 0
 
 
+def test_auto_merges_leading_steps_into_one_dataflow_launch(torch):
+    """AUTO sends the first small steps of a larger call through one dataflow launch and the rest as one launch
+    per step; the split point moves with the item limit (0 = never merge)."""
+    cases = ((sb.SPARBIT, 125, 512, False), (sb.SPARBIT, 64, 16384, False), (sb.SPARBIT, 33, 40000, True),
+             (sb.RING, 40, 4096, False), (sb.RING, 17, 70000, True), (sb.BRUCK, 96, 4096, False),
+             (sb.RECURSIVE_DOUBLING, 32, 65536, False), (sb.SPARBIT, 257, 1040, False), (sb.SPARBIT, 21, 4100, False))
+    try:
+        for limit in (0, 64, 300, 1024):
+            sb.sparbit_tune("hybrid_max_items", limit)
+            for algo, p, B, in_place in cases:
+                announce("hybrid", limit, algo, p, B, in_place)
+                send = workloads.make_send_raw(p, B, seed=limit + p)
+                want = oracle_result(algo, p, B, send, in_place=in_place)
+                got = gpu_result(torch, algo, p, B, send, sb.MODE_AUTO, in_place=in_place,
+                                 misalign=4 if B == 4100 else 0)
+                assert np.array_equal(got, want), (limit, algo, p, B, in_place)
+    finally:
+        sb.sparbit_tune("hybrid_max_items", 1024)
+
+
 def test_maximum_rank_count(torch):
     """p = SPARBIT_MAX_P (4096): 16.7 million block copies in 12 steps."""
     p, B = 4096, 16
