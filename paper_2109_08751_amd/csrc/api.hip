@@ -62,7 +62,7 @@ std::atomic<long long> g_wg_threads{256};                     // lanes per workg
 std::atomic<long long> g_unroll{1};                           // vectors per lane of the tile kernel (2 and 4 only with 256 lanes)
 std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
 std::atomic<long long> g_nontemporal{1};
-std::atomic<long long> g_persistent_max_bytes{64ll << 10};    // AUTO uses the persistent kernel up to this p*p*B
+std::atomic<long long> g_persistent_max_bytes{4ll << 10};     // AUTO uses the persistent kernel up to this p*p*B
 std::atomic<long long> g_dataflow_max_items{256};             // AUTO uses the dataflow kernel up to this many work items
 std::atomic<long long> g_hybrid_max_items{1024};              // AUTO: leading steps with at most this many items share one dataflow launch
 std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
@@ -698,7 +698,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         if (copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
             mode = SPARBIT_MODE_DATAFLOW;
         } else if (recv_bytes <= size_t(g_persistent_max_bytes.load())) {
-            mode = SPARBIT_MODE_PERSISTENT;  // at most 16 workgroups of flattened tiles: the barrier is cheap there
+            mode = SPARBIT_MODE_PERSISTENT;  // a single workgroup of flattened tiles: the barrier costs next to nothing
         } else {
             mode = SPARBIT_MODE_PER_STEP;
             const uint64_t limit = uint64_t(g_hybrid_max_items.load());
