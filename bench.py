@@ -44,7 +44,8 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--workload", default="cfg4",
+                    help="cfg1 .. cfg5, or pP_bB for P ranks with blocks of B bytes (uint8 payload), e.g. p128_b1048580")
     ap.add_argument("--mode", default="auto", choices=["auto", "per_step", "persistent"])
     ap.add_argument("--skip-context", action="store_true", help="only the headline workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -216,7 +217,16 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_each_way": nbytes, "launches": args.warmup + args.steps,
                           "ok": bool(torch.equal(src, dst)), **t, **rates(1, nbytes, t["avg_ms"])}))
         return
-    w = workloads.WORKLOADS[args.workload]
+    if args.workload in workloads.WORKLOADS:
+        w = workloads.WORKLOADS[args.workload]
+    else:
+        import re
+        m = re.fullmatch(r"p(\d+)_b(\d+)", args.workload)
+        if not m:
+            print(f"bench.py: unknown workload {args.workload!r}", file=sys.stderr)
+            sys.exit(2)
+        w = workloads.Workload(args.workload, int(m.group(1)), int(m.group(2)), "u8",
+                               f"p={m.group(1)}, {m.group(2)}-byte uint8 blocks")
     p, B = w.p, w.block_bytes
 
     # ---- headline: timed region of exactly --steps calls
@@ -247,7 +257,9 @@ def main():
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_CALL[w.name] / launches
                                  if w.name in MEASURED_TRAFFIC_BYTES_PER_CALL and not args.tune and args.mode == "auto"
                                  else None),
-                     "kernel": "sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 256, 1, true, false>", "launches_per_call": launches,
+                     "kernel": ("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 256, 1, true, false>"
+                                if B % 16 == 0 else "sparbit::copy_tiles_realign_kernel<256, true>"),
+                     "launches_per_call": launches,
                      "algorithmic_bytes_per_launch": 2 * p * p * B / launches,
                      "avg_launch_ms": head["avg_ms"] / launches,
                      "note": "achieved = algorithmic bytes per launch (2*p*p*B / launches) / average launch "
