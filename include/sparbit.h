@@ -16,10 +16,11 @@
  *             MPI_Allgather post-condition of Section II of the paper.
  *   Blocks are opaque bytes; the MPI (count, datatype) pair collapses into
  *   block_bytes.  Any block_bytes and any base alignment is accepted.  The
- *   full rate needs base pointers and block_bytes that are multiples of 16;
- *   otherwise blocks of 512 bytes and more still move in 16-byte vectors
- *   (aligned stores, unaligned loads, ~80-95 % of the aligned rate) and
- *   shorter ones with 4-byte or single-byte accesses.
+ *   full rate needs a receive base pointer and a block_bytes that are
+ *   multiples of 128 (whole cache lines per store); otherwise blocks of 512
+ *   bytes and more still move in 16-byte vectors (stores aligned to lines,
+ *   loads at the source's alignment, ~80-97 % of the full rate) and shorter
+ *   ones with 16-, 4- or single-byte accesses as their alignment allows.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
@@ -194,6 +195,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
  *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
  *   "realign_min_bytes"    blocks at least this long that are off the 16-byte grid use the realigning kernel (>= 16)
+ *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  */
 int sparbit_tune(const char *key, long long value);

@@ -127,7 +127,9 @@ def test_blocks_off_the_16_byte_grid(torch, algo):
     """Blocks whose ends fall between 16-byte boundaries, source and destination shifted against each other:
     aligned body, byte-wise head and tail.  The bytes around the receive buffer must stay untouched."""
     cases = ((5, 513, 0, 0), (7, 1000, 3, 9), (8, 4099, 1, 0), (3, 70001, 15, 2), (12, (1 << 20) + 7, 5, 11),
-             (16, 515, 0, 4), (9, 4100, 4, 8), (2, 1 << 16, 7, 7))
+             (16, 515, 0, 4), (9, 4100, 4, 8), (2, 1 << 16, 7, 7),
+             # on the 16-byte grid but off the 128-byte one: long blocks take the same kernel
+             (6, (1 << 16) + 16, 0, 0), (4, (1 << 18) + 64, 16, 32), (5, 1 << 17, 0, 48))
     for p, B, ms, mr in cases:
         send = workloads.make_send_raw(p, B, seed=B)
         for in_place in (False, True):
