@@ -701,13 +701,16 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         // With one workgroup per item an item only waits for lower-numbered workgroups, which are dispatched
         // first, so these grids do not depend on residency.
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
-        if (copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
+        // The dataflow kernel moves byte-aligned blocks byte by byte; beyond a couple of KiB per block the
+        // per-step realigning kernel is well ahead of that (p = 12, B = 64 KiB + 1: 15 us against 74 us).
+        const bool flow_ok = width >= 4 || B <= 2048;
+        if (flow_ok && copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
             mode = SPARBIT_MODE_DATAFLOW;
         } else if (recv_bytes <= size_t(g_persistent_max_bytes.load())) {
             mode = SPARBIT_MODE_PERSISTENT;  // a single workgroup of flattened tiles: the barrier costs next to nothing
         } else {
             mode = SPARBIT_MODE_PER_STEP;
-            const uint64_t limit = uint64_t(g_hybrid_max_items.load());
+            const uint64_t limit = flow_ok ? uint64_t(g_hybrid_max_items.load()) : 0;
             while (flow_prefix < phases.size() &&
                    (phases[flow_prefix].copies_before + phases[flow_prefix].ncopies) * cpb <= limit)
                 ++flow_prefix;
