@@ -24,9 +24,10 @@ __device__ __forceinline__ V ld(const V* p)
         return *p;
 }
 
-// Streaming store.  For 16-byte vectors the fastest form measured on MI355X is a write-through store at
-// system scope (sc0 sc1): a linear copy runs at 6.69 TB/s with it against 6.45 TB/s with the non-temporal
-// hint alone.  The compiler has no builtin that emits it for 16 bytes, hence the one-instruction asm; the
+// Streaming store.  For 16-byte vectors that cover whole 128-byte lines the fastest form measured on MI355X is a
+// write-through store at system scope (sc0 sc1): a linear copy runs at 6.69 TB/s with it against 6.45 TB/s with
+// the non-temporal hint alone, block copies of 4 KiB .. 16 MiB gain 2 .. 20 %; on lines covered piecewise it
+// loses to the hint, so the host picks.  The compiler has no builtin that emits it for 16 bytes, hence the one-instruction asm; the
 // data operand comes from a tracked load, so the wait for that load is still the compiler's.
 template <typename V, bool NT, bool WRITE_THROUGH = true>
 __device__ __forceinline__ void st(V* p, V v)
@@ -57,7 +58,7 @@ __device__ __forceinline__ void st(V* p, V v)
 // blockIdx.x interleaves G = 2^lg_g copies: copy = group * G + (x mod G),
 // tile = x / G.  With G = 8 each XCD streams one whole block by itself.
 // ---------------------------------------------------------------------------
-template <typename V, typename Index, int T, int U, bool NT, bool LOOP>
+template <typename V, typename Index, int T, int U, bool NT, bool LOOP, bool WT = true>
 __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict__ src_base,
                                                        uint8_t* __restrict__ dst_base,
                                                        const Copy* __restrict__ copies, uint32_t ncopies,
@@ -78,7 +79,7 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
             if (v + Index(u * T) < vpb) x[u] = ld<V, NT>(s + v + Index(u * T));
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (v + Index(u * T) < vpb) st<V, NT>(d + v + Index(u * T), x[u]);
+            if (v + Index(u * T) < vpb) st<V, NT, WT>(d + v + Index(u * T), x[u]);
     };
     if constexpr (LOOP) {  // blocks so long that their tiles exceed the grid's x extent: several trips
         const Index stride = Index(gridDim.x >> lg_g) * Index(T * U);
@@ -104,7 +105,7 @@ struct VarCopy {
     uint64_t pad;
 };
 
-template <typename V, bool NT>
+template <typename V, bool NT, bool WT = false>
 __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict__ src_base,
                                                       uint8_t* __restrict__ dst_base,
                                                       const VarCopy* __restrict__ copies, uint32_t ncopies,
@@ -113,14 +114,19 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
     if (c >= ncopies) return;
-    const VarCopy cp = copies[c];
+    // The whole 32-byte entry in one scalar load: fetched field by field, the length and the offsets would be two
+    // dependent round trips before the first vector load can go out.
+    typedef uint64_t u64x4 __attribute__((ext_vector_type(4)));
+    const u64x4 e = *reinterpret_cast<const u64x4*>(copies + c);
+    const uint64_t src_off = e.x, dst_off = e.y, len = e.z;
     const uint64_t v = uint64_t(blockIdx.x >> lg_g) * WG + threadIdx.x;
-    if (v < cp.len / sizeof(V)) {
-        const V* __restrict__ s = reinterpret_cast<const V*>(src_base + cp.src_off);
-        V* __restrict__ d = reinterpret_cast<V*>(dst_base + cp.dst_off);
-        // Non-temporal store here: measured on 128 ranks x 1 MiB, this kernel runs at 6.5 TB/s with it and at
-        // 6.4 TB/s with the write-through form that serves copy_tiles_kernel better.
-        st<V, NT, false>(d + v, ld<V, NT>(s + v));
+    if (v < len / sizeof(V)) {
+        const V* __restrict__ s = reinterpret_cast<const V*>(src_base + src_off);
+        V* __restrict__ d = reinterpret_cast<V*>(dst_base + dst_off);
+        // The host picks the store form: the non-temporal hint for long blocks (128 ranks x 1 MiB: 6.5 TB/s against
+        // 6.4 TB/s with the write-through form that serves copy_tiles_kernel better), write-through for whole-line
+        // blocks below 128 KiB.
+        st<V, NT, WT>(d + v, ld<V, NT>(s + v));
     }
 }
 
