@@ -258,22 +258,37 @@ int access_width(const void* a, const void* b, const void* c, size_t block_bytes
     return 1;
 }
 
-template <typename V, typename Index, int T, int U>
-int launch_tiles(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
-                 hipStream_t stream)
+// Grid of one tile of T vectors per workgroup for `ncopies` copies of at most `max_vecs` vectors each, copies dealt
+// round-robin in groups of 2^lg_g to consecutive workgroups.  Blocks with more tiles than the x extent allows get
+// the largest extent and *capped = true (the kernels that accept such a grid loop).  False if the copies do not
+// fit a grid at all.
+bool tile_grid(uint64_t max_vecs, uint32_t ncopies, int T, dim3* grid, uint32_t* lg_g_out, bool* capped)
 {
-    const uint64_t vpb = B / sizeof(V);
-    uint64_t tiles = (vpb + T * U - 1) / (T * U);
+    uint64_t tiles = (max_vecs + uint64_t(T) - 1) / uint64_t(T);
+    if (tiles == 0) tiles = 1;
     uint32_t lg_g = uint32_t(g_interleave_log2.load());
     while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
     const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
     const uint32_t gy = groups < 32768u ? groups : 32768u;
     const uint32_t gz = (groups + gy - 1) / gy;
-    if (gz > 65535u) return SPARBIT_ERR_ARG;
-    const uint64_t max_tiles = (0x7fffffffull / T) >> lg_g;  // grid x extent stays below 2^31 lanes
-    const bool loop = tiles > max_tiles;                     // the kernel then takes several trips
-    if (loop) tiles = max_tiles;
-    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
+    if (gz > 65535u) return false;
+    const uint64_t max_tiles = (0x7fffffffull / uint64_t(T)) >> lg_g;  // grid x extent stays below 2^31 lanes
+    *capped = tiles > max_tiles;
+    if (*capped) tiles = max_tiles;
+    *grid = dim3(uint32_t(tiles << lg_g), gy, gz);
+    *lg_g_out = lg_g;
+    return true;
+}
+
+template <typename V, typename Index, int T, int U>
+int launch_tiles(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
+                 hipStream_t stream)
+{
+    const uint64_t vpb = B / sizeof(V);
+    dim3 grid;
+    uint32_t lg_g = 0;
+    bool loop = false;  // blocks with more tiles than the grid holds: the kernel takes several trips
+    if (!tile_grid((vpb + U - 1) / U, ncopies, T, &grid, &lg_g, &loop)) return SPARBIT_ERR_ARG;
     if (loop)
         hipLaunchKernelGGL((copy_tiles_kernel<V, Index, T, U, true, true>), grid, dim3(T), 0, stream, src, dst, copies,
                            ncopies, uint64_t(B), lg_g);
@@ -311,33 +326,14 @@ int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t n
     return SPARBIT_OK;
 }
 
-// Grid of one tile of T vectors per workgroup for `ncopies` copies of at most `max_vecs` vectors each, copies dealt
-// round-robin in groups of 2^lg_g to consecutive workgroups.  Blocks with more tiles than the x extent allows get
-// the largest extent (the kernels that accept such a grid loop).  False if the copies do not fit a grid at all.
-bool tile_grid(uint64_t max_vecs, uint32_t ncopies, int T, dim3* grid, uint32_t* lg_g_out)
-{
-    uint64_t tiles = (max_vecs + uint64_t(T) - 1) / uint64_t(T);
-    if (tiles == 0) tiles = 1;
-    uint32_t lg_g = uint32_t(g_interleave_log2.load());
-    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;  // a short phase has fewer copies than XCDs
-    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
-    const uint32_t gy = groups < 32768u ? groups : 32768u;
-    const uint32_t gz = (groups + gy - 1) / gy;
-    if (gz > 65535u) return false;
-    const uint64_t max_tiles = (0x7fffffffull / uint64_t(T)) >> lg_g;  // grid x extent stays below 2^31 lanes
-    if (tiles > max_tiles) tiles = max_tiles;
-    *grid = dim3(uint32_t(tiles << lg_g), gy, gz);
-    *lg_g_out = lg_g;
-    return true;
-}
-
 template <int T>
 int launch_realign_t(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t ncopies, size_t B, bool nt,
                      hipStream_t stream)
 {
     dim3 grid;
     uint32_t lg_g = 0;
-    if (!tile_grid(B >> 4, ncopies, T, &grid, &lg_g)) return SPARBIT_ERR_ARG;
+    bool capped = false;  // the kernel loops, so a capped grid is fine
+    if (!tile_grid(B >> 4, ncopies, T, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
     if (nt)
         hipLaunchKernelGGL((copy_tiles_realign_kernel<T, true>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
                            uint64_t(B), lg_g);
@@ -550,7 +546,8 @@ int launch_var_realign(const uint8_t* src, uint8_t* dst, const VarCopy* copies, 
 {
     dim3 grid;
     uint32_t lg_g = 0;
-    if (!tile_grid(max_len >> 4, ncopies, WG, &grid, &lg_g)) return SPARBIT_ERR_ARG;
+    bool capped = false;  // the kernel loops, so a capped grid is fine
+    if (!tile_grid(max_len >> 4, ncopies, WG, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
     if (g_nontemporal.load() != 0)
         hipLaunchKernelGGL((copy_var_realign_kernel<true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
     else
@@ -567,15 +564,12 @@ int launch_var(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t
     if (tiles == 0 || ncopies == 0) return SPARBIT_OK;
     if (sizeof(V) < 16 && max_len >= uint64_t(g_realign_min_bytes.load()))
         return launch_var_realign(src, dst, copies, ncopies, max_len, stream);
-    uint32_t lg_g = uint32_t(g_interleave_log2.load());
-    while (lg_g > 0 && (1u << lg_g) > ncopies) --lg_g;
-    const uint32_t groups = (ncopies + (1u << lg_g) - 1) >> lg_g;
-    const uint32_t gy = groups < 32768u ? groups : 32768u;
-    const uint32_t gz = (groups + gy - 1) / gy;
-    if (gz > 65535u) return SPARBIT_ERR_ARG;
-    if ((tiles << lg_g) > 0x7fffffffull / WG)  // a block too long for one tile per workgroup: the looping kernel
+    dim3 grid;
+    uint32_t lg_g = 0;
+    bool capped = false;
+    if (!tile_grid(max_len / sizeof(V), ncopies, WG, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
+    if (capped)  // a block too long for one tile per workgroup: the looping kernel
         return launch_var_realign(src, dst, copies, ncopies, max_len, stream);
-    const dim3 grid(uint32_t(tiles << lg_g), gy, gz);
     if (g_nontemporal.load() != 0 && write_through)
         hipLaunchKernelGGL((copy_var_kernel<V, true, true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
     else if (g_nontemporal.load() != 0)
