@@ -461,6 +461,8 @@ int launch_dataflow_v(const FlowArgs& a, DeviceState* ds, hipStream_t stream)
 }
 
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb);
+int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mode, bool whole, int first_step,
+        int last_step, void* stream_v);
 
 constexpr size_t kVarPlanCacheSize = 8;
 
@@ -604,6 +606,11 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     const bool in_place = sendbufs == nullptr;
     if (!in_place && ranges_overlap(sendbufs, row_bytes, recvbufs, size_t(p) * row_bytes)) return SPARBIT_ERR_ALIAS;
     if (!any) return SPARBIT_OK;
+    // Equal blocks packed back to back are a plain Allgather: same layout, and the equal-block path has the
+    // faster kernels and the single-launch forms for small jobs.
+    bool packed = counts[0] != 0 && row_bytes == size_t(p) * counts[0];
+    for (int k = 0; k < p && packed; ++k) packed = counts[k] == counts[0] && displs[k] == size_t(k) * counts[0];
+    if (packed) return run(sendbufs, recvbufs, p, counts[0], algo, SPARBIT_MODE_AUTO, true, 0, 0, stream_v);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const bool capturing = stream_is_capturing(stream);
 

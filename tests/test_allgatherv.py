@@ -266,3 +266,24 @@ def test_gpu_allgatherv_block_with_more_tiles_than_the_grid_holds():
         assert torch.equal(d_recv[r * row:(r + 1) * row], want), r
     del d_send, d_recv, want, piece
     torch.cuda.empty_cache()
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_with_packed_equal_blocks_is_the_allgather():
+    """Equal counts packed back to back are handed to the equal-block path; same result as the oracle's Allgatherv."""
+    import torch
+    for p, B, algo, oalgo in ((6, 1024, sb.SPARBIT, oracle.SPARBIT), (33, 4100, sb.SPARBIT, oracle.SPARBIT),
+                              (16, 70000, sb.RING, oracle.RING), (8, 48, sb.RECURSIVE_DOUBLING, oracle.RECURSIVE_DOUBLING)):
+        counts = np.full(p, B, dtype=np.uint64)
+        displs = (np.arange(p) * B).astype(np.uint64)
+        row = p * B
+        send = payload(row, p)
+        for in_place in (False, True):
+            print("[case] packed allgatherv", p, B, algo, in_place, flush=True)
+            want = np.full((p, row), POISON, dtype=np.uint8)
+            if in_place:
+                for r in range(p):
+                    want[r, r * B:(r + 1) * B] = send[r * B:(r + 1) * B]
+            oracle.allgatherv(oalgo, p, counts, displs, row, None if in_place else send, want)
+            got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place)
+            assert np.array_equal(got, want), (p, B, algo, in_place)
