@@ -131,8 +131,10 @@ int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t 
  *   algo        SPARBIT, RING, RECURSIVE_DOUBLING (p a power of two) or DIRECT;
  *               BRUCK returns SPARBIT_ERR_UNSUPPORTED (its rotated working
  *               buffer is defined for equal blocks).
- * One launch per step and size class (block lengths within a factor of two
- * share a launch).  The copy lists of the last few (algo, p, counts, displs,
+ * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
+ * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
+ * Otherwise one launch per step and size class (block lengths within a factor
+ * of two share a launch).  The copy lists of the last few (algo, p, counts, displs,
  * row_bytes) geometries are cached per device; a new geometry costs O(p^2) host
  * work and one upload.
  */
