@@ -287,3 +287,51 @@ def test_gpu_allgatherv_with_packed_equal_blocks_is_the_allgather():
             oracle.allgatherv(oalgo, p, counts, displs, row, None if in_place else send, want)
             got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place)
             assert np.array_equal(got, want), (p, B, algo, in_place)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_randomized_geometries():
+    """300 seeded random geometries: schedule, p, size scale (40 B .. 2.4 MB), granularity (1, 4, 16, 128 bytes),
+    empty blocks, one outsized block, shuffled displacements with gaps, in place, shifted base addresses."""
+    import torch
+    rng = np.random.default_rng(20210908)
+    algos = [(sb.SPARBIT, oracle.SPARBIT), (sb.SPARBIT, oracle.SPARBIT), (sb.RING, oracle.RING),
+             (sb.RECURSIVE_DOUBLING, oracle.RECURSIVE_DOUBLING), (sb.DIRECT, oracle.NAIVE)]
+    done = 0
+    while done < 300:
+        algo, oalgo = algos[rng.integers(len(algos))]
+        p = int(rng.integers(1, 70))
+        if algo == sb.RECURSIVE_DOUBLING:
+            p = 1 << int(rng.integers(0, 7))
+        grain = int(rng.choice([1, 4, 16, 128]))
+        scale = int(rng.choice([40, 600, 5000, 70000, 300000]))
+        counts = (rng.integers(0, scale // grain + 1, p) * grain).astype(np.uint64)
+        if rng.integers(3) == 0:
+            counts[rng.integers(0, p)] = 0
+        if rng.integers(4) == 0:
+            counts[rng.integers(0, p)] = np.uint64(scale * 8 // grain * grain)
+        gaps = (rng.integers(0, 5, p) * grain).astype(np.uint64)
+        displs = np.zeros(p, dtype=np.uint64)
+        at = int(rng.integers(0, 3)) * grain
+        for k in rng.permutation(p):
+            displs[k] = at
+            at += int(counts[k]) + int(gaps[k])
+        row = max(at + int(rng.integers(0, 3)) * grain, grain)
+        if p * row > (48 << 20):
+            continue
+        in_place = bool(rng.integers(0, 4) == 0)
+        mis = int(rng.choice([0, 0, 1, 4, 16, 64]))
+        if grain >= 16 and mis % 16:
+            mis = 0
+        print("[case] random allgatherv", done, algo, p, grain, scale, row, in_place, mis, flush=True)
+        send = payload(row, done)
+        want = np.full((p, row), POISON, dtype=np.uint8)
+        if in_place:
+            for r in range(p):
+                d, c = int(displs[r]), int(counts[r])
+                want[r, d:d + c] = send[d:d + c]
+        # the plain all-to-all definition needs the send buffer; in place it yields the same state
+        oracle.allgatherv(oalgo, p, counts, displs, row, None if (in_place and algo != sb.DIRECT) else send, want)
+        got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+        assert np.array_equal(got, want), (done, algo, p, grain, scale, in_place, mis)
+        done += 1

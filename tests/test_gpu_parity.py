@@ -486,14 +486,15 @@ def test_blocks_with_more_tiles_than_the_grid_holds(torch, shift):
 
 
 def test_randomized_cases(torch):
-    """150 seeded random (schedule, p, block size, mode, in-place, misalignment) cases against the oracle."""
+    """400 seeded random (schedule, p, block size, mode, in-place, misalignment, AUTO limits) cases against the
+    oracle."""
     rng = np.random.default_rng(20210908)
     algos = [sb.SPARBIT, sb.SPARBIT, sb.SPARBIT, sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT]
     modes = ["per_step", "persistent", "dataflow", "auto"]
     sizes = [1, 2, 3, 4, 7, 8, 12, 16, 20, 31, 32, 48, 64, 100, 128, 256, 500, 1024, 1040, 4096, 4100, 8192, 20000,
-             65536, 70000]
+             65536, 70000, 513, 2049, 16400, 65552, 65600, 131072 + 64, 262144 + 16, 100003]
     done = 0
-    while done < 150:
+    while done < 400:
         algo = algos[rng.integers(len(algos))]
         p = int(rng.integers(1, 81))
         if algo == sb.RECURSIVE_DOUBLING:
@@ -504,10 +505,16 @@ def test_randomized_cases(torch):
         mode = modes[rng.integers(len(modes))]
         in_place = bool(rng.integers(0, 4) == 0) and algo != sb.BRUCK
         misalign = [0, 0, 0, 1, 4, 8, 16][rng.integers(7)]
+        sb.sparbit_tune("hybrid_max_items", [0, 64, 1024, 1024][rng.integers(4)])
+        sb.sparbit_tune("dataflow_max_items", [0, 256, 256, 2000][rng.integers(4)])
         announce("random", done, algo, p, B, mode, in_place, misalign)
         send = workloads.make_send_raw(p, B, seed=done)
         want = oracle_result(algo, p, B, send, in_place=in_place)
-        got = gpu_result(torch, algo, p, B, send, MODES[mode], in_place=in_place, misalign=misalign)
+        try:
+            got = gpu_result(torch, algo, p, B, send, MODES[mode], in_place=in_place, misalign=misalign)
+        finally:
+            sb.sparbit_tune("hybrid_max_items", 1024)
+            sb.sparbit_tune("dataflow_max_items", 256)
         assert np.array_equal(got, want), (algo, p, B, mode, in_place, misalign)
         done += 1
 
