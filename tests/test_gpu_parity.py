@@ -332,6 +332,40 @@ def test_two_host_threads(torch):
         assert np.array_equal(results[i], want)
 
 
+def test_auto_calls_on_eight_streams_beside_a_heavy_kernel(torch):
+    """AUTO sends small jobs and the leading steps of larger ones through grids that wait on ready flags.  Eight
+    streams issue such calls at once while another stream keeps the whole GPU busy with writes: every result must
+    match the oracle and no bounded wait may expire."""
+    dev = torch.device("cuda:0")
+    cases = [(96, 4096), (64, 16384), (125, 512), (32, 65536), (12, 1024), (6, 1024), (256, 64), (16, 262144)]
+    streams = [torch.cuda.Stream() for _ in cases]
+    background = torch.cuda.Stream()
+    big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    jobs = []
+    for i, (p, B) in enumerate(cases):
+        send = workloads.make_send_raw(p, B, seed=40 + i)
+        want = torch.from_numpy(oracle_result(sb.SPARBIT, p, B, send)).to(dev)
+        d_send, d_recv, keep = gpu_buffers(torch, p, B, send)
+        jobs.append((p, B, d_send, d_recv, want, keep))
+    for rnd in range(6):
+        announce("eight streams, round", rnd)
+        for job in jobs:
+            job[3].fill_(POISON)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(background):
+            for _ in range(4):
+                big.fill_(rnd)
+        for rep in range(10):
+            for st, (p, B, d_send, d_recv, _, _) in zip(streams, jobs):
+                sb.sparbit_allgather(d_send, d_recv, p, B, st)
+        torch.cuda.synchronize()
+        for p, B, _, d_recv, want, _ in jobs:
+            assert torch.equal(d_recv.view(p, p, B), want), (rnd, p, B)
+    assert sum(sb.sparbit_barrier_timeouts(st) for st in streams) == 0
+    del big
+    torch.cuda.empty_cache()
+
+
 def test_capture_in_a_hip_graph(torch):
     """Once the tables of (schedule, p) are cached a per-step call allocates
     nothing and enqueues only kernels, so it can be captured; every replay must
