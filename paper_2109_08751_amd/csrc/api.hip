@@ -64,7 +64,7 @@ std::atomic<long long> g_interleave_log2{3};                  // copies interlea
 std::atomic<long long> g_nontemporal{1};
 std::atomic<long long> g_persistent_max_bytes{4ll << 10};     // AUTO uses the persistent kernel up to this p*p*B
 std::atomic<long long> g_dataflow_max_items{256};             // AUTO uses the dataflow kernel up to this many work items
-std::atomic<long long> g_hybrid_max_items{1024};              // AUTO: leading steps with at most this many items share one dataflow launch
+std::atomic<long long> g_hybrid_max_items{512};               // AUTO: leading steps with at most this many items share one dataflow launch
 std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
 std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
@@ -712,7 +712,9 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         // except that the first steps of a log-step schedule are small, so as many leading phases as fit in
         // one workgroup per item share one dataflow launch (a flag hand-over costs less than a kernel boundary).
         // With one workgroup per item an item only waits for lower-numbered workgroups, which are dispatched
-        // first, so these grids do not depend on residency.
+        // first, so such a grid does not depend on its own residency; and at 512 workgroups, a quarter of the
+        // GPU's workgroup slots, the grids of four calls running at once (HIP's default number of hardware
+        // queues per process) are all resident together, so they cannot hold one another's slots either.
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
         // The dataflow kernel moves byte-aligned blocks byte by byte; beyond a couple of KiB per block the
         // per-step realigning kernel is well ahead of that (p = 12, B = 64 KiB + 1: 15 us against 74 us).

@@ -447,7 +447,7 @@ def test_auto_merges_leading_steps_into_one_dataflow_launch(torch):
                                  misalign=4 if B == 4100 else 0)
                 assert np.array_equal(got, want), (limit, algo, p, B, in_place)
     finally:
-        sb.sparbit_tune("hybrid_max_items", 1024)
+        sb.sparbit_tune("hybrid_max_items", 512)
 
 
 def test_maximum_rank_count(torch):
@@ -547,7 +547,7 @@ def test_randomized_cases(torch):
         try:
             got = gpu_result(torch, algo, p, B, send, MODES[mode], in_place=in_place, misalign=misalign)
         finally:
-            sb.sparbit_tune("hybrid_max_items", 1024)
+            sb.sparbit_tune("hybrid_max_items", 512)
             sb.sparbit_tune("dataflow_max_items", 256)
         assert np.array_equal(got, want), (algo, p, B, mode, in_place, misalign)
         done += 1
