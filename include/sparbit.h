@@ -123,7 +123,8 @@ int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t 
  *   counts, displs  HOST arrays of p entries, read during the call and not kept:
  *               rank k contributes counts[k] bytes (0 allowed), which land at
  *               byte displs[k] of every rank's receive buffer.  Blocks must lie
- *               inside row_bytes and must not overlap each other.
+ *               inside row_bytes and must not overlap each other;
+ *               p * row_bytes must stay below 2^40.
  *   recvbufs    device; rank r's receive buffer starts at byte r * row_bytes.
  *               Bytes that belong to no block are left untouched.
  *   sendbufs    device, laid out like ONE receive buffer (rank r's block at

@@ -498,18 +498,18 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
         for (const Copy& c : ph.copies) {
             const uint32_t slot = c.dst_block % uint32_t(p);  // the destination always names the slot
             if (counts[slot] == 0) continue;
-            VarCopy vc;
-            vc.src_off = ph.src_buf == BUF_SEND ? displs[c.src_block]
-                                                : uint64_t(c.src_block / uint32_t(p)) * row_bytes + displs[c.src_block % uint32_t(p)];
-            vc.dst_off = uint64_t(c.dst_block / uint32_t(p)) * row_bytes + displs[slot];
-            vc.len = counts[slot];
-            vc.pad = 0;
+            const uint64_t src_off = ph.src_buf == BUF_SEND
+                                         ? displs[c.src_block]
+                                         : uint64_t(c.src_block / uint32_t(p)) * row_bytes + displs[c.src_block % uint32_t(p)];
+            const uint64_t dst_off = uint64_t(c.dst_block / uint32_t(p)) * row_bytes + displs[slot];
+            const uint64_t len = counts[slot];
+            const VarCopy vc = pack_var_copy(src_off, dst_off, len);  // all three below 2^40: checked by the caller
             int cls = 0;
-            while ((uint64_t(1) << cls) < vc.len) ++cls;  // ceil(log2 len)
+            while ((uint64_t(1) << cls) < len) ++cls;  // ceil(log2 len)
             bucket[cls].push_back(vc);
             in_order.push_back(vc);
-            if (vc.len > longest) longest = vc.len;
-            if (vc.len < shortest) shortest = vc.len;
+            if (len > longest) longest = len;
+            if (len < shortest) shortest = len;
         }
         if (longest != 0 && longest <= 4 * shortest) {  // little skew: one launch, schedule order
             for (int cls = 0; cls <= 64; ++cls) bucket[cls].clear();
@@ -519,7 +519,7 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
             if (bucket[cls].empty()) continue;
             VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), uint32_t(bucket[cls].size()), 0u};
             for (const VarCopy& vc : bucket[cls])
-                if (vc.len > v.max_len) v.max_len = vc.len;
+                if (var_len(vc) > v.max_len) v.max_len = var_len(vc);
             all.insert(all.end(), bucket[cls].begin(), bucket[cls].end());
             if (!ph.only_in_place && !ph.covered_by_fused) vp->out_of_place.push_back(v);
             if (!ph.skip_in_place) vp->in_place.push_back(v);
@@ -589,7 +589,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
     if (algo == SPARBIT_ALGO_BRUCK) return SPARBIT_ERR_UNSUPPORTED;  // its rotated buffer assumes equal blocks
     if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING && (p & (p - 1))) return SPARBIT_ERR_UNSUPPORTED;
-    if ((unsigned __int128)row_bytes * unsigned(p) > (unsigned __int128)0x7fffffffffffffffull) return SPARBIT_ERR_ARG;
+    // the copy lists hold byte offsets into the p receive buffers in 40 bits (1 TiB; the GPU has 288 GB)
+    if ((unsigned __int128)row_bytes * unsigned(p) > (unsigned __int128)kVarFieldMask) return SPARBIT_ERR_ARG;
     uintptr_t bits = uintptr_t(sendbufs) | uintptr_t(recvbufs) | uintptr_t(row_bytes);
     std::vector<std::pair<size_t, size_t>> spans;  // (start, end) of the non-empty blocks
     for (int k = 0; k < p; ++k) {

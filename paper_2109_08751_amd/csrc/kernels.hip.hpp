@@ -98,12 +98,21 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
 // phase into launches of similar length, so at most half of them do).  V is
 // the access width that all offsets, lengths and base addresses allow.
 // ---------------------------------------------------------------------------
+// Offsets and the length are below 2^40 (the host checks), so an entry packs into 16 bytes: one scalar load per
+// workgroup, and half the table memory of three 64-bit fields (p = 4096: 16.7 million entries).
 struct VarCopy {
-    uint64_t src_off;  // bytes from the phase's source base
-    uint64_t dst_off;  // bytes from the phase's destination base
-    uint64_t len;      // bytes
-    uint64_t pad;
+    uint64_t a;  // bits 0..39: byte offset from the phase's source base; bits 40..63: length bits 0..23
+    uint64_t b;  // bits 0..39: byte offset from the phase's destination base; bits 40..55: length bits 24..39
 };
+constexpr uint64_t kVarFieldMask = (uint64_t(1) << 40) - 1;
+
+__host__ __device__ inline VarCopy pack_var_copy(uint64_t src_off, uint64_t dst_off, uint64_t len)
+{
+    return VarCopy{src_off | ((len & 0xffffffull) << 40), dst_off | ((len >> 24) << 40)};
+}
+__host__ __device__ inline uint64_t var_src_off(const VarCopy& c) { return c.a & kVarFieldMask; }
+__host__ __device__ inline uint64_t var_dst_off(const VarCopy& c) { return c.b & kVarFieldMask; }
+__host__ __device__ inline uint64_t var_len(const VarCopy& c) { return (c.a >> 40) | ((c.b >> 40) << 24); }
 
 template <typename V, bool NT, bool WT = false>
 __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict__ src_base,
@@ -114,11 +123,8 @@ __global__ __launch_bounds__(WG) void copy_var_kernel(const uint8_t* __restrict_
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
     if (c >= ncopies) return;
-    // The whole 32-byte entry in one scalar load: fetched field by field, the length and the offsets would be two
-    // dependent round trips before the first vector load can go out.
-    typedef uint64_t u64x4 __attribute__((ext_vector_type(4)));
-    const u64x4 e = *reinterpret_cast<const u64x4*>(copies + c);
-    const uint64_t src_off = e.x, dst_off = e.y, len = e.z;
+    const VarCopy cp = copies[c];
+    const uint64_t src_off = var_src_off(cp), dst_off = var_dst_off(cp), len = var_len(cp);
     const uint64_t v = uint64_t(blockIdx.x >> lg_g) * WG + threadIdx.x;
     if (v < len / sizeof(V)) {
         const V* __restrict__ s = reinterpret_cast<const V*>(src_base + src_off);
@@ -199,7 +205,8 @@ __global__ __launch_bounds__(WG) void copy_var_realign_kernel(const uint8_t* __r
     const uint32_t c = (group << lg_g) + (blockIdx.x & ((1u << lg_g) - 1u));
     if (c >= ncopies) return;
     const VarCopy cp = copies[c];
-    realign_copy<WG, NT>(src_base + cp.src_off, dst_base + cp.dst_off, cp.len, blockIdx.x >> lg_g, gridDim.x >> lg_g);
+    realign_copy<WG, NT>(src_base + var_src_off(cp), dst_base + var_dst_off(cp), var_len(cp), blockIdx.x >> lg_g,
+                         gridDim.x >> lg_g);
 }
 
 // ---------------------------------------------------------------------------
