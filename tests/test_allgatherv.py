@@ -114,6 +114,7 @@ def test_allgatherv_arguments_are_checked_on_the_host():
     assert call(3, [4, 4, 4], [0, 4, 8], 12, algo=sb.RECURSIVE_DOUBLING) == -3
     assert call(2, [4, 4], [0, 4], 8, send=0x100004) == -2   # send overlaps the receive buffers
     assert call(2, [0, 0], [0, 0], 8) == 0            # nothing to move
+    assert call(2, [4, 4], [0, 4], 1 << 39, send=1 << 44, recv=1 << 45) == -1   # p * row_bytes reaches 2^40
     assert L.sparbit_allgatherv(0x1000, 0x100000, 2, None, None, 8, 0, None) == -1
 
 
