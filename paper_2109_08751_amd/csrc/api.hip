@@ -442,12 +442,12 @@ int launch_persistent_v(const PersistentArgs& a, DeviceState* ds, uint64_t max_t
     return SPARBIT_OK;
 }
 
-template <typename V>
+template <typename V, bool REALIGN = false>
 int launch_dataflow_v(const FlowArgs& a, DeviceState* ds, hipStream_t stream)
 {
     const int num_cus = ds->num_cus;
     int per_cu = 0;
-    const int rc = resident_per_cu(ds, dataflow_kernel<V>, &per_cu);
+    const int rc = resident_per_cu(ds, dataflow_kernel<V, REALIGN>, &per_cu);
     if (rc != SPARBIT_OK) return rc;
     if (per_cu < 1) return SPARBIT_ERR_HIP;
     long long want = g_flow_wgs_per_cu.load();
@@ -455,7 +455,7 @@ int launch_dataflow_v(const FlowArgs& a, DeviceState* ds, hipStream_t stream)
     if (want > half) want = half;  // every workgroup must be resident, and the rest of the GPU stays usable
     uint64_t grid = uint64_t(num_cus) * uint64_t(want);
     if (grid > a.total_items) grid = a.total_items;
-    hipLaunchKernelGGL((dataflow_kernel<V>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    hipLaunchKernelGGL((dataflow_kernel<V, REALIGN>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
@@ -704,7 +704,8 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     size_t flow_chunk = size_t(g_flow_chunk_bytes.load());
     flow_chunk -= flow_chunk % 16;
     if (flow_chunk < 16) flow_chunk = 16;
-    const uint64_t cpb = (B + flow_chunk - 1) / flow_chunk;  // dataflow work items (and ready flags) per block
+    // Dataflow work items (and ready flags) per block: whole chunks, the last one taking the remainder as well.
+    const uint64_t cpb = B / flow_chunk ? B / flow_chunk : 1;
     size_t flow_prefix = 0;  // leading phases that go out as one dataflow launch ahead of per-step launches
     if (mode == SPARBIT_MODE_AUTO) {
         // The single-launch dataflow form only where the whole job is a handful of workgroups: a grid that
@@ -717,16 +718,13 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         // GPU's workgroup slots, the grids of four calls running at once (HIP's default number of hardware
         // queues per process) are all resident together, so they cannot hold one another's slots either.
         const uint64_t copies_total = phases.empty() ? 0 : phases.back().copies_before + phases.back().ncopies;
-        // The dataflow kernel moves byte-aligned blocks byte by byte; beyond a couple of KiB per block the
-        // per-step realigning kernel is well ahead of that (p = 12, B = 64 KiB + 1: 15 us against 74 us).
-        const bool flow_ok = width >= 4 || B <= 2048;
-        if (flow_ok && copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
+        if (copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
             mode = SPARBIT_MODE_DATAFLOW;
         } else if (recv_bytes <= size_t(g_persistent_max_bytes.load())) {
             mode = SPARBIT_MODE_PERSISTENT;  // a single workgroup of flattened tiles: the barrier costs next to nothing
         } else {
             mode = SPARBIT_MODE_PER_STEP;
-            const uint64_t limit = flow_ok ? uint64_t(g_hybrid_max_items.load()) : 0;
+            const uint64_t limit = uint64_t(g_hybrid_max_items.load());
             while (flow_prefix < phases.size() &&
                    (phases[flow_prefix].copies_before + phases[flow_prefix].ncopies) * cpb <= limit)
                 ++flow_prefix;
@@ -737,11 +735,13 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     // Dataflow form (flags instead of barriers) for the first `nph` phases of the call.
     auto launch_flow = [&](size_t nph, bool* launched) -> int {
         *launched = false;
-        const size_t unit = size_t(width);
+        // Blocks off the 16-byte grid that are long enough to have a body: byte units, realigned 16-byte accesses.
+        const bool realign = width < 16 && B >= size_t(g_realign_min_bytes.load());
+        const size_t unit = realign ? 1 : size_t(width);
         const uint64_t items = (phases[nph - 1].copies_before + phases[nph - 1].ncopies) * cpb;
         const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
-        if (items > 0x7fffffffull || flags_per_buf > 0x3fffffffull || flow_chunk / unit > 0xffffffffull)
-            return SPARBIT_OK;  // too many items for one grid
+        if (items > 0x7fffffffull || flags_per_buf > 0x3fffffffull || B / unit > 0xffffffffull)
+            return SPARBIT_OK;  // too many items for one grid, or offsets inside a block beyond the kernel's 32 bits
         FlowStream* fs = nullptr;
         int frc = get_flow(ds, stream, size_t(2 * flags_per_buf), &fs);
         if (frc != SPARBIT_OK) return frc;
@@ -766,6 +766,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         a.p = uint32_t(p);
         a.in_place = in_place ? 1u : 0u;
         *launched = true;
+        if (realign) return launch_dataflow_v<uint8_t, true>(a, ds, stream);
         switch (width) {
         case 16: return launch_dataflow_v<u32x4>(a, ds, stream);
         case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);

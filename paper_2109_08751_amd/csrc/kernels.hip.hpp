@@ -357,7 +357,7 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
 // ---------------------------------------------------------------------------
 // Dataflow form (the non-blocking variant the paper names as future work in
 // its conclusion): one launch, no device-wide barrier.  The unit of work is
-// one chunk (<= chunk_bytes) of one block copy; every chunk of a receive slot
+// one chunk (chunk_bytes, the last chunk of a block up to twice that) of one block copy; every chunk of a receive slot
 // has a ready flag that holds the number of the call that last filled it.
 // Items are numbered in phase order and dealt round-robin to the workgroups of
 // a grid that the host sizes to be fully resident; a workgroup takes its items
@@ -446,7 +446,41 @@ struct FlowArgs {
     uint32_t in_place;       // 1: slot r of rank r was filled by the caller before the call; nobody flags it
 };
 
-template <typename V>
+// One chunk whose ends are not on 16-byte boundaries, with the same coherent accesses: bytes up to the first
+// 16-byte boundary of the destination and after the last one singly, the body in 16-byte vectors (aligned stores,
+// loads at the source's alignment).
+__device__ __forceinline__ void coherent_realign_chunk(const uint8_t* __restrict__ s, uint8_t* __restrict__ d, uint32_t n)
+{
+    uint32_t head = (0u - uint32_t(reinterpret_cast<uintptr_t>(d))) & 15u;
+    if (head > n) head = n;
+    const uint32_t nvec = (n - head) >> 4;
+    const uint32_t tail = (n - head) & 15u;
+    // The single bytes are loaded first and stored last, so that their round trips overlap the body's.
+    const bool has_head = threadIdx.x < head;
+    const bool has_tail = threadIdx.x >= 32u && threadIdx.x - 32u < tail;
+    const uint32_t tail_at = head + (nvec << 4) + (threadIdx.x - 32u);
+    uint8_t head_byte = 0, tail_byte = 0;
+    if (has_head) head_byte = coherent_ld<uint8_t>(s + threadIdx.x);
+    if (has_tail) tail_byte = coherent_ld<uint8_t>(s + tail_at);
+    const u32x4* sv = reinterpret_cast<const u32x4*>(s + head);  // any alignment: only handed to the asm loads
+    u32x4* dv = reinterpret_cast<u32x4*>(d + head);
+    uint32_t v = 0;
+    for (; nvec - v >= 4u * WG; v += 4u * WG) {
+        const uint32_t l = v + threadIdx.x;
+        u32x4 x0, x1, x2, x3;
+        coherent_ld4(sv + l, sv + l + WG, sv + l + 2 * WG, sv + l + 3 * WG, x0, x1, x2, x3);
+        coherent_st<u32x4>(dv + l, x0);
+        coherent_st<u32x4>(dv + l + WG, x1);
+        coherent_st<u32x4>(dv + l + 2 * WG, x2);
+        coherent_st<u32x4>(dv + l + 3 * WG, x3);
+    }
+    for (v += threadIdx.x; v < nvec; v += WG) coherent_st<u32x4>(dv + v, coherent_ld<u32x4>(sv + v));
+    if (has_head) coherent_st<uint8_t>(d + threadIdx.x, head_byte);
+    if (has_tail) coherent_st<uint8_t>(d + tail_at, tail_byte);
+}
+
+// REALIGN (with V = uint8_t): chunks of blocks that are off the 16-byte grid move through coherent_realign_chunk.
+template <typename V, bool REALIGN = false>
 __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
 {
     __shared__ uint32_t s_ok;
@@ -459,7 +493,7 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         const DevPhase P = a.phases[ph];
         const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
         const uint32_t v0 = q * a.chunk_vecs;
-        const uint32_t v1 = (vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
+        const uint32_t v1 = (q + 1 == a.chunks_per_block) ? vpb : v0 + a.chunk_vecs;  // the last chunk takes the rest
         // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
         // the own slot of every rank (block index rank * p + rank of the receive buffer).
         const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
@@ -487,7 +521,10 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         }
         const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
         V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
-        if constexpr (sizeof(V) == 16) {
+        if constexpr (REALIGN) {
+            static_assert(sizeof(V) == 1, "chunk bounds are byte offsets");
+            coherent_realign_chunk(reinterpret_cast<const uint8_t*>(s) + v0, reinterpret_cast<uint8_t*>(d) + v0, v1 - v0);
+        } else if constexpr (sizeof(V) == 16) {
             uint32_t v = v0;
             for (; v1 - v >= 4u * WG; v += 4u * WG) {  // whole groups: four vectors per lane in flight
                 const uint32_t l = v + threadIdx.x;
