@@ -134,8 +134,10 @@ int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t 
  *               buffer is defined for equal blocks).
  * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
- * Otherwise one launch per step and size class (block lengths within a factor
- * of two share a launch).  The copy lists of the last few (algo, p, counts, displs,
+ * Otherwise, as for equal blocks, a call of at most 256 work items is one
+ * dataflow launch and the leading small steps of a larger one share one; the
+ * rest goes out as one launch per step and size class (block lengths within a
+ * factor of two share a launch).  The copy lists of the last few (algo, p, counts, displs,
  * row_bytes) geometries are cached per device; a new geometry costs O(p^2) host
  * work and one upload.
  */

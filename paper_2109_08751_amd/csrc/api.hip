@@ -102,6 +102,7 @@ struct VarPhase {
     Buffer src_buf, dst_buf;
     uint32_t first, ncopies;
     uint64_t max_len;
+    uint32_t host_phase;  // index of the schedule phase these copies belong to
 };
 
 struct VarPlan {
@@ -110,11 +111,17 @@ struct VarPlan {
     std::vector<size_t> counts, displs;
     std::vector<VarPhase> out_of_place, in_place;
     VarCopy* d_copies = nullptr;
+    uint64_t* d_geometry = nullptr;  // counts[p], then displs[p]: what the dataflow form reads
+    uint64_t max_count = 0;
     uint64_t last_use = 0;
     VarPlan() = default;
     VarPlan(const VarPlan&) = delete;
     VarPlan& operator=(const VarPlan&) = delete;
-    ~VarPlan() { (void)hipFree(d_copies); }
+    ~VarPlan()
+    {
+        (void)hipFree(d_copies);
+        (void)hipFree(d_geometry);
+    }
 };
 
 struct DeviceState {
@@ -488,7 +495,8 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     vp->counts.assign(counts, counts + p);
     vp->displs.assign(displs, displs + p);
     std::vector<VarCopy> all;
-    for (const Phase& ph : dp->host.phases) {
+    for (size_t host_phase = 0; host_phase < dp->host.phases.size(); ++host_phase) {
+        const Phase& ph = dp->host.phases[host_phase];
         // The copies of a phase are independent, so they may be regrouped.  Lengths within a factor of four
         // share one launch (workgroups past the end of a shorter block exit at once); a phase with more skew
         // goes out as one launch per size class (factor of two), so that it neither wastes dispatches on tiny
@@ -517,7 +525,7 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
         }
         for (int cls = 64; cls >= 0; --cls) {
             if (bucket[cls].empty()) continue;
-            VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), uint32_t(bucket[cls].size()), 0u};
+            VarPhase v{ph.src_buf, ph.dst_buf, uint32_t(all.size()), uint32_t(bucket[cls].size()), 0u, uint32_t(host_phase)};
             for (const VarCopy& vc : bucket[cls])
                 if (var_len(vc) > v.max_len) v.max_len = var_len(vc);
             all.insert(all.end(), bucket[cls].begin(), bucket[cls].end());
@@ -528,6 +536,16 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     if (!all.empty()) {
         SB_HIP(hipMalloc(reinterpret_cast<void**>(&vp->d_copies), all.size() * sizeof(VarCopy)));
         SB_HIP(hipMemcpy(vp->d_copies, all.data(), all.size() * sizeof(VarCopy), hipMemcpyHostToDevice));
+    }
+    {
+        std::vector<uint64_t> geometry(size_t(2) * size_t(p));
+        for (int k = 0; k < p; ++k) {
+            geometry[size_t(k)] = counts[k];
+            geometry[size_t(p) + size_t(k)] = displs[k];
+            if (counts[k] > vp->max_count) vp->max_count = counts[k];
+        }
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&vp->d_geometry), geometry.size() * sizeof(uint64_t)));
+        SB_HIP(hipMemcpy(vp->d_geometry, geometry.data(), geometry.size() * sizeof(uint64_t), hipMemcpyHostToDevice));
     }
     if (ds->var_plans.size() >= kVarPlanCacheSize) {
         // Evict the least recently used geometry; its table may still be read by queued launches.
@@ -582,6 +600,23 @@ int launch_var(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t
     return SPARBIT_OK;
 }
 
+template <bool ON_GRID>
+int launch_dataflow_var(const FlowVarArgs& a, DeviceState* ds, hipStream_t stream)
+{
+    int per_cu = 0;
+    const int rc = resident_per_cu(ds, dataflow_var_kernel<ON_GRID>, &per_cu);
+    if (rc != SPARBIT_OK) return rc;
+    if (per_cu < 1) return SPARBIT_ERR_HIP;
+    long long want = g_flow_wgs_per_cu.load();
+    const int half = per_cu > 1 ? per_cu / 2 : 1;
+    if (want > half) want = half;
+    uint64_t grid = uint64_t(ds->num_cus) * uint64_t(want);
+    if (grid > a.f.total_items) grid = a.f.total_items;
+    hipLaunchKernelGGL((dataflow_var_kernel<ON_GRID>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
+
 int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, const size_t* displs, size_t row_bytes,
           int algo, void* stream_v)
 {
@@ -626,7 +661,69 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs), nullptr};
     const int width = (bits & 15) == 0 ? 16 : (bits & 3) == 0 ? 4 : 1;
     const bool on_lines = (bits & 127) == 0;  // every block starts and ends on a 128-byte line
+
+    // As for equal blocks: a call of a few work items goes out as one dataflow launch, and in a larger one the
+    // leading small steps share one.  A copy of an empty block still counts as an item (it exits at once).
+    const std::vector<DevPhase>& phases = in_place ? dp->in_place : dp->out_of_place;
+    size_t flow_phases = 0;  // leading phases done by the dataflow launch
+    if (!capturing && !phases.empty()) {
+        size_t chunk = size_t(g_flow_chunk_bytes.load());
+        chunk -= chunk % 16;
+        if (chunk < 16) chunk = 16;
+        const uint64_t cpb = vp->max_count / chunk ? vp->max_count / chunk : 1;
+        const uint64_t copies_total = phases.back().copies_before + phases.back().ncopies;
+        if (copies_total * cpb <= uint64_t(g_dataflow_max_items.load())) {
+            flow_phases = phases.size();
+        } else {
+            const uint64_t limit = uint64_t(g_hybrid_max_items.load());
+            while (flow_phases < phases.size() &&
+                   (phases[flow_phases].copies_before + phases[flow_phases].ncopies) * cpb <= limit)
+                ++flow_phases;
+            if (flow_phases < 2) flow_phases = 0;
+        }
+        const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
+        if (flow_phases && flags_per_buf <= 0x3fffffffull) {
+            FlowStream* fs = nullptr;
+            if ((rc = get_flow(ds, stream, size_t(flags_per_buf), &fs)) != SPARBIT_OK) return rc;
+            FlowVarArgs a;
+            std::memset(&a, 0, sizeof a);
+            a.f.base[0] = base[0];
+            a.f.base[1] = base[1];
+            a.f.copies = dp->d_copies;
+            a.f.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
+            a.f.state = fs->state;
+            a.f.flags = fs->flags;
+            a.f.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
+            a.f.nphases = uint32_t(flow_phases);
+            a.f.chunks_per_block = uint32_t(cpb);
+            a.f.chunk_vecs = uint32_t(chunk);
+            a.f.flags_per_buf = uint32_t(flags_per_buf);
+            if (++fs->epoch == 0) fs->epoch = 1;
+            a.f.epoch = fs->epoch;
+            a.f.total_items = uint32_t((phases[flow_phases - 1].copies_before + phases[flow_phases - 1].ncopies) * cpb);
+            a.f.p = uint32_t(p);
+            a.f.in_place = in_place ? 1u : 0u;
+            a.counts = vp->d_geometry;
+            a.displs = vp->d_geometry + p;
+            a.row_bytes = row_bytes;
+            rc = width == 16 ? launch_dataflow_var<true>(a, ds, stream) : launch_dataflow_var<false>(a, ds, stream);
+            if (rc != SPARBIT_OK) return rc;
+        } else {
+            flow_phases = 0;
+        }
+    }
+    // Which schedule phases the dataflow launch covered: the first `flow_phases` of those that this call runs.
+    std::vector<char> covered(dp->host.phases.size(), 0);
+    for (size_t i = 0, active = 0; i < dp->host.phases.size() && active < flow_phases; ++i) {
+        const Phase& ph = dp->host.phases[i];
+        if (in_place ? ph.skip_in_place : ph.only_in_place) continue;
+        if (!in_place ? ph.covered_by_fused : ph.fused_first) continue;
+        if (ph.copies.empty()) continue;
+        covered[i] = 1;
+        ++active;
+    }
     for (const VarPhase& ph : in_place ? vp->in_place : vp->out_of_place) {
+        if (covered[ph.host_phase]) continue;
         const uint8_t* src = base[ph.src_buf];
         uint8_t* dst = const_cast<uint8_t*>(base[ph.dst_buf]);
         const VarCopy* copies = vp->d_copies + ph.first;

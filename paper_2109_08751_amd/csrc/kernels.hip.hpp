@@ -479,11 +479,59 @@ __device__ __forceinline__ void coherent_realign_chunk(const uint8_t* __restrict
     if (has_tail) coherent_st<uint8_t>(d + tail_at, tail_byte);
 }
 
+// Thread 0 polls `flag` until it holds this call's number; the whole workgroup learns the outcome.  False: a
+// bounded wait expired here or elsewhere in the launch, and the workgroup must leave.
+__device__ __forceinline__ bool flow_wait(const FlowArgs& a, const uint32_t* flag)
+{
+    __shared__ uint32_t s_ok;
+    if (threadIdx.x == 0) {
+        uint32_t good = 1;
+        const uint64_t t0 = wall_clock64();
+        while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
+            __builtin_amdgcn_s_sleep(1);
+            const bool expired = uint64_t(wall_clock64()) - t0 > a.spin_limit_ticks;
+            if (expired || __hip_atomic_load(&a.state->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch) {
+                if (expired && __hip_atomic_exchange(&a.state->abort, a.epoch, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
+                    __hip_atomic_fetch_add(&a.state->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                good = 0;
+                break;
+            }
+        }
+        s_ok = good;
+    }
+    __syncthreads();
+    return s_ok != 0;  // the next write of s_ok comes after the barrier in flow_publish
+}
+
+// Own stores acknowledged by the memory side, then the workgroup meets, then the flag.
+__device__ __forceinline__ void flow_publish(const FlowArgs& a, uint32_t* flag)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) coherent_st<uint32_t>(flag, a.epoch);
+}
+
+// One chunk of n 16-byte vectors, both ends on the 16-byte grid.
+__device__ __forceinline__ void coherent_copy_vectors(const u32x4* __restrict__ s, u32x4* __restrict__ d, uint32_t n)
+{
+    uint32_t v = 0;
+    for (; n - v >= 4u * WG; v += 4u * WG) {  // whole groups: four vectors per lane in flight
+        const uint32_t l = v + threadIdx.x;
+        u32x4 x0, x1, x2, x3;
+        coherent_ld4(s + l, s + l + WG, s + l + 2 * WG, s + l + 3 * WG, x0, x1, x2, x3);
+        coherent_st<u32x4>(d + l, x0);
+        coherent_st<u32x4>(d + l + WG, x1);
+        coherent_st<u32x4>(d + l + 2 * WG, x2);
+        coherent_st<u32x4>(d + l + 3 * WG, x3);
+    }
+    for (v += threadIdx.x; v < n; v += WG) coherent_st<u32x4>(d + v, coherent_ld<u32x4>(s + v));
+}
+
 // REALIGN (with V = uint8_t): chunks of blocks that are off the 16-byte grid move through coherent_realign_chunk.
 template <typename V, bool REALIGN = false>
 __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
 {
-    __shared__ uint32_t s_ok;
     const uint32_t vpb = uint32_t(a.block_bytes / sizeof(V));
     uint32_t ph = 0;  // items come in phase order, so the phase index only moves forward
     for (uint32_t item = blockIdx.x; item < a.total_items; item += gridDim.x) {
@@ -497,45 +545,16 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
         // the own slot of every rank (block index rank * p + rank of the receive buffer).
         const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
-        if (P.src_buf != BUF_SEND && !own_slot) {
-            if (threadIdx.x == 0) {
-                const uint32_t* f = a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) +
-                                    cp.src_block * a.chunks_per_block + q;
-                uint32_t good = 1;
-                const uint64_t t0 = wall_clock64();
-                while (__hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
-                    __builtin_amdgcn_s_sleep(1);
-                    const bool expired = uint64_t(wall_clock64()) - t0 > a.spin_limit_ticks;
-                    if (expired || __hip_atomic_load(&a.state->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch) {
-                        if (expired && __hip_atomic_exchange(&a.state->abort, a.epoch, __ATOMIC_RELAXED,
-                                                             __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
-                            __hip_atomic_fetch_add(&a.state->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        good = 0;
-                        break;
-                    }
-                }
-                s_ok = good;
-            }
-            __syncthreads();
-            if (s_ok == 0) break;  // uniform: the whole workgroup leaves
-        }
+        if (P.src_buf != BUF_SEND && !own_slot &&
+            !flow_wait(a, a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.src_block * a.chunks_per_block + q))
+            break;  // uniform: the whole workgroup leaves
         const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
         V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
         if constexpr (REALIGN) {
             static_assert(sizeof(V) == 1, "chunk bounds are byte offsets");
             coherent_realign_chunk(reinterpret_cast<const uint8_t*>(s) + v0, reinterpret_cast<uint8_t*>(d) + v0, v1 - v0);
         } else if constexpr (sizeof(V) == 16) {
-            uint32_t v = v0;
-            for (; v1 - v >= 4u * WG; v += 4u * WG) {  // whole groups: four vectors per lane in flight
-                const uint32_t l = v + threadIdx.x;
-                V x0, x1, x2, x3;
-                coherent_ld4(s + l, s + l + WG, s + l + 2 * WG, s + l + 3 * WG, x0, x1, x2, x3);
-                coherent_st<V>(d + l, x0);
-                coherent_st<V>(d + l + WG, x1);
-                coherent_st<V>(d + l + 2 * WG, x2);
-                coherent_st<V>(d + l + 3 * WG, x3);
-            }
-            for (v += threadIdx.x; v < v1; v += WG) coherent_st<V>(d + v, coherent_ld<V>(s + v));
+            coherent_copy_vectors(s + v0, d + v0, v1 - v0);
         } else {
             constexpr int U = 8;
             for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
@@ -548,13 +567,55 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
                     if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
             }
         }
-        // Own stores acknowledged by the memory side, then the workgroup meets, then the flag.
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (threadIdx.x == 0)
-            coherent_st<uint32_t>(a.flags + (P.dst_buf == BUF_WORK ? a.flags_per_buf : 0u) +
-                                      cp.dst_block * a.chunks_per_block + q,
-                                  a.epoch);
+        flow_publish(a, a.flags + (P.dst_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.dst_block * a.chunks_per_block + q);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The dataflow form for blocks of different sizes (Allgatherv): same items,
+// flags and waits; a copy's offsets and length come from its slot's entry in
+// the call's count and displacement arrays.  Every copy is given the chunk
+// count of the longest block; the items past the end of a shorter block have
+// nothing to move and nobody waits for them.  ON_GRID: every offset and length
+// is a multiple of 16.
+// ---------------------------------------------------------------------------
+struct FlowVarArgs {
+    FlowArgs f;              // block_bytes unused; chunk_vecs = chunk size in bytes
+    const uint64_t* counts;  // [p] bytes per slot
+    const uint64_t* displs;  // [p] byte offset of a slot in a receive buffer (and of a rank's block in the send buffer)
+    uint64_t row_bytes;
+};
+
+template <bool ON_GRID>
+__global__ __launch_bounds__(WG) void dataflow_var_kernel(const FlowVarArgs va)
+{
+    const FlowArgs& a = va.f;
+    uint32_t ph = 0;
+    for (uint32_t item = blockIdx.x; item < a.total_items; item += gridDim.x) {
+        const uint32_t k = item / a.chunks_per_block;
+        const uint32_t q = item - k * a.chunks_per_block;
+        while (ph + 1 < a.nphases && a.phases[ph + 1].copies_before <= k) ++ph;
+        const DevPhase P = a.phases[ph];
+        const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
+        const uint32_t dst_rank = cp.dst_block / a.p, slot = cp.dst_block - dst_rank * a.p;
+        const uint64_t len = va.counts[slot];
+        const uint64_t whole = len / a.chunk_vecs;
+        const uint64_t nchunks = whole ? whole : (len ? 1u : 0u);
+        if (q >= nchunks) continue;  // uniform: nothing of this block falls into chunk q
+        const uint64_t at = uint64_t(q) * a.chunk_vecs;
+        const uint32_t n = uint32_t((q + 1 == nchunks ? len : at + a.chunk_vecs) - at);  // below two chunks
+        const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
+        if (P.src_buf != BUF_SEND && !own_slot && !flow_wait(a, a.flags + cp.src_block * a.chunks_per_block + q)) break;
+        const uint64_t src_off = P.src_buf == BUF_SEND
+                                     ? va.displs[cp.src_block]
+                                     : uint64_t(cp.src_block / a.p) * va.row_bytes + va.displs[cp.src_block % a.p];
+        const uint8_t* __restrict__ s = a.base[P.src_buf] + src_off + at;
+        uint8_t* __restrict__ d = const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(dst_rank) * va.row_bytes + va.displs[slot] + at;
+        if constexpr (ON_GRID)
+            coherent_copy_vectors(reinterpret_cast<const u32x4*>(s), reinterpret_cast<u32x4*>(d), n >> 4);
+        else
+            coherent_realign_chunk(s, d, n);
+        flow_publish(a, a.flags + cp.dst_block * a.chunks_per_block + q);
     }
 }
 
