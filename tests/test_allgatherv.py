@@ -119,6 +119,21 @@ def test_allgatherv_arguments_are_checked_on_the_host():
 
 
 # ------------------------------------------------------------------ GPU parity
+import contextlib
+
+
+@contextlib.contextmanager
+def launch_per_step_only():
+    """AUTO without the dataflow launches (small calls and leading steps): one launch per step and size class."""
+    sb.sparbit_tune("hybrid_max_items", 0)
+    sb.sparbit_tune("dataflow_max_items", 0)
+    try:
+        yield
+    finally:
+        sb.sparbit_tune("hybrid_max_items", 512)
+        sb.sparbit_tune("dataflow_max_items", 256)
+
+
 def gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=False, misalign=0):
     dev = torch.device("cuda:0")
     sraw = torch.empty(row + 64, dtype=torch.uint8, device=dev)
@@ -156,6 +171,9 @@ def test_gpu_allgatherv_matches_oracle():
                 oracle.allgatherv(oalgo, p, counts, displs, row, send, want)
                 got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
                 assert np.array_equal(got, want), (p, align, algo)
+                with launch_per_step_only():  # the same call without the dataflow launch
+                    got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
+                assert np.array_equal(got, want), (p, align, algo, "per step")
 
 
 @pytest.mark.gpu
@@ -333,6 +351,10 @@ def test_gpu_allgatherv_randomized_geometries():
                 want[r, d:d + c] = send[d:d + c]
         # the plain all-to-all definition needs the send buffer; in place it yields the same state
         oracle.allgatherv(oalgo, p, counts, displs, row, None if (in_place and algo != sb.DIRECT) else send, want)
-        got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+        if rng.integers(3) == 0:
+            with launch_per_step_only():
+                got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+        else:
+            got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
         assert np.array_equal(got, want), (done, algo, p, grain, scale, in_place, mis)
         done += 1
