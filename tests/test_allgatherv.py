@@ -358,3 +358,39 @@ def test_gpu_allgatherv_randomized_geometries():
             got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
         assert np.array_equal(got, want), (done, algo, p, grain, scale, in_place, mis)
         done += 1
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_capture_in_a_hip_graph():
+    """A geometry that was used once outside a capture can be recorded (per-step launches only, although the same
+    call issued eagerly takes the dataflow launch) and replayed; a new geometry is refused with nothing recorded."""
+    import torch
+    p = 6
+    counts, displs, row = geometry(p, seed=77, align=16, max_len=2000)
+    send = payload(row, 3)
+    want = np.full((p, row), POISON, dtype=np.uint8)
+    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, send, want)
+    dev = torch.device("cuda:0")
+    d_send = torch.from_numpy(send).to(dev)
+    d_recv = torch.full((p * row,), POISON, dtype=torch.uint8, device=dev)
+    st = torch.cuda.Stream()
+    refused = []
+    with torch.cuda.stream(st):
+        sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+        st.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            cur = torch.cuda.current_stream()
+            try:
+                sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row + 16, sb.SPARBIT, cur)  # never seen
+            except sb.SparbitError as e:
+                refused.append(e.code)
+            sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, cur)
+    assert refused == [-3]
+    for rep in range(3):
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want), rep
