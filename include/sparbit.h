@@ -136,8 +136,8 @@ int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t 
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
  * Otherwise, as for equal blocks, a call of at most 256 work items is one
  * dataflow launch and the leading small steps of a larger one share one; the
- * rest goes out as one launch per step and size class (block lengths within a
- * factor of two share a launch).  The copy lists of the last few (algo, p, counts, displs,
+ * rest goes out as one launch per step, or, where the block lengths of a step
+ * are very uneven, one per size class (lengths within a factor of two).  The copy lists of the last few (algo, p, counts, displs,
  * row_bytes) geometries are cached per device; a new geometry costs O(p^2) host
  * work and one upload.
  */
@@ -199,6 +199,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
  *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
+ *   "var_idle_max"         Allgatherv: a step whose block lengths differ by more than a factor of four still goes out
+ *                          as one launch if that starts at most this many workgroups past the end of shorter blocks
  *   "realign_min_bytes"    blocks at least this long that are off the 16-byte grid use the realigning kernel (>= 16)
  *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels

@@ -70,6 +70,7 @@ std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per 
 std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
 std::atomic<long long> g_line_align_min_bytes{64ll << 10};    // 16-byte-aligned blocks at least this long, off the 128-byte grid: same
+std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idle workgroups one launch per step may cost before size classes pay
 std::atomic<long long> g_realign_min_bytes{512};              // blocks at least this long, not 16-byte aligned: realigning kernel
 
 struct DevicePlan {
@@ -498,9 +499,9 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
     for (size_t host_phase = 0; host_phase < dp->host.phases.size(); ++host_phase) {
         const Phase& ph = dp->host.phases[host_phase];
         // The copies of a phase are independent, so they may be regrouped.  Lengths within a factor of four
-        // share one launch (workgroups past the end of a shorter block exit at once); a phase with more skew
-        // goes out as one launch per size class (factor of two), so that it neither wastes dispatches on tiny
-        // blocks nor overflows the grid.
+        // share one launch (workgroups past the end of a shorter block exit at once), and so do phases whose
+        // skew costs few idle workgroups; any other phase goes out as one launch per size class (factor of
+        // two), so that it neither wastes dispatches on tiny blocks nor overflows the grid.
         std::vector<VarCopy> bucket[65], in_order;
         uint64_t longest = 0, shortest = ~uint64_t(0);
         for (const Copy& c : ph.copies) {
@@ -519,7 +520,13 @@ int get_var_plan(DeviceState* ds, DevicePlan* dp, int algo, int p, const size_t*
             if (len > longest) longest = len;
             if (len < shortest) shortest = len;
         }
-        if (longest != 0 && longest <= 4 * shortest) {  // little skew: one launch, schedule order
+        // Workgroups that a single launch, sized for the longest block, would start past the end of shorter blocks
+        // (4 KiB tiles).  They exit at once, so up to ~10^5 of them are cheaper than the extra launches (measured:
+        // p = 64, blocks of 1-64 KiB: 107 us with size classes, 41 us without; beyond ~10^6 idle workgroups the
+        // single launch loses).
+        uint64_t idle = 0;
+        for (const VarCopy& vc : in_order) idle += (longest + 4095) / 4096 - (var_len(vc) + 4095) / 4096;
+        if (longest != 0 && (longest <= 4 * shortest || idle <= uint64_t(g_var_idle_max.load()))) {  // one launch, schedule order
             for (int cls = 0; cls <= 64; ++cls) bucket[cls].clear();
             bucket[64].swap(in_order);
         }
@@ -1065,6 +1072,9 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "line_align_min_bytes")) {
         if (value < 16) return SPARBIT_ERR_ARG;
         g_line_align_min_bytes = value;
+    } else if (!std::strcmp(key, "var_idle_max")) {
+        if (value < 0) return SPARBIT_ERR_ARG;
+        g_var_idle_max = value;
     } else if (!std::strcmp(key, "realign_min_bytes")) {
         if (value < 16) return SPARBIT_ERR_ARG;
         g_realign_min_bytes = value;
