@@ -46,7 +46,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4",
                     help="cfg1 .. cfg5, or pP_bB for P ranks with blocks of B bytes (uint8 payload), e.g. p128_b1048580")
-    ap.add_argument("--mode", default="auto", choices=["auto", "per_step", "persistent"])
+    ap.add_argument("--mode", default="auto", choices=["auto", "per_step", "persistent", "dataflow"])
     ap.add_argument("--skip-context", action="store_true", help="only the headline workload")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE")
@@ -199,7 +199,8 @@ def main():
     for kv in args.tune:
         k, v = kv.split("=")
         sb.sparbit_tune(k, int(v))
-    mode = {"auto": sb.MODE_AUTO, "per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT}[args.mode]
+    mode = {"auto": sb.MODE_AUTO, "per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT,
+            "dataflow": sb.MODE_DATAFLOW}[args.mode]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.Stream()
@@ -241,7 +242,7 @@ def main():
         sys.exit(1)
     r = rates(p, B, head["avg_ms"])
     nsteps = sb.Plan(p).num_steps
-    launches = 1 if (mode == sb.MODE_PERSISTENT) else nsteps  # own blocks + step 0 share the first launch
+    launches = 1 if mode in (sb.MODE_PERSISTENT, sb.MODE_DATAFLOW) else nsteps  # own blocks + step 0 share the first launch
     out = {
         "metric": "effective Allgather GB/s (p*p*block_bytes landed / time; % of MI355X peak HBM BW in "
                   "roofline.frac), Sparbit schedule, per p and block size",
