@@ -36,7 +36,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # scaled by a plain 1 GiB copy through the same kernel); figures and commands: profiles/copy_tiles_kernel_cfg4.md
 # and profiles/copy_tiles_kernel_cfg5.md.
 # Only meaningful for the default tuning and issue mode of that workload.
-MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16779059 + 16777216) * 1024, "cfg5": (16916777 + 16908544) * 1024}
+MEASURED_TRAFFIC_BYTES_PER_CALL = {"cfg4": (16779229 + 16777216) * 1024, "cfg5": (16916835 + 16908544) * 1024}
 
 
 def parse_args():
@@ -258,7 +258,8 @@ def main():
                      "traffic": (MEASURED_TRAFFIC_BYTES_PER_CALL[w.name] / launches
                                  if w.name in MEASURED_TRAFFIC_BYTES_PER_CALL and not args.tune and args.mode == "auto"
                                  else None),
-                     "kernel": ("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 256, 1, true, false, true>"
+                     "kernel": ("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, %d, 1, true, false, true>"
+                                % (64 if 8192 <= B <= (4 << 20) else 256)
                                 if B % 16 == 0 else "sparbit::copy_tiles_realign_kernel<256, true>"),
                      "launches_per_call": launches,
                      "algorithmic_bytes_per_launch": 2 * p * p * B / launches,

@@ -186,7 +186,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
 /*
  * Tuning knobs for experiments (process-wide; unknown keys or out-of-range
  * values return SPARBIT_ERR_ARG):
- *   "wg_threads"           most lanes per workgroup of the per-step kernel: 64, 128, 256, 512, 1024
+ *   "wg_threads"           most lanes per workgroup of the per-step kernel: 64, 128, 256, 512, 1024, or 0 (default):
+ *                          64 for 16-byte-aligned blocks of 8 KiB .. 4 MiB, else 256
  *   "unroll"               vectors each lane of that kernel moves: 1, 2 or 4 (2 and 4 only with 256 lanes)
  *   "interleave_log2"      log2 of the block copies dealt round-robin to consecutive workgroups (3 = one per XCD)
  *   "dataflow_max_items"   AUTO uses the dataflow kernel when the call has at most this many work items

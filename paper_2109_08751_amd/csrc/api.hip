@@ -58,7 +58,7 @@ int no_throw(F&& body)
 }
 
 // ---- tuning knobs ----------------------------------------------------------
-std::atomic<long long> g_wg_threads{256};                     // lanes per workgroup of the tile kernel
+std::atomic<long long> g_wg_threads{0};                       // lanes per workgroup of the tile kernel; 0 = by block size
 std::atomic<long long> g_unroll{1};                           // vectors per lane of the tile kernel (2 and 4 only with 256 lanes)
 std::atomic<long long> g_interleave_log2{3};                  // copies interleaved over consecutive workgroups: 2^3 = one per XCD
 std::atomic<long long> g_nontemporal{1};
@@ -377,6 +377,10 @@ int launch_phase_v(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_
     if (2 * vpb > 0xffffffffull)  // lane index plus a grid-wide stride must not wrap
         return launch_tiles<V, uint64_t, 256, 1>(src, dst, copies, ncopies, B, nt, stream);
     long long t = g_wg_threads.load();
+    // One wavefront per workgroup (1 KiB tiles) is 0.5-2.5 % ahead of four for 16-byte vectors and blocks of
+    // 8 KiB .. 4 MiB (p = 128, B = 1 MiB: 5.128 against 5.160 ms per call); shorter blocks (more workgroups than
+    // the launch can hide) and 16 MiB blocks are 1-2 % better off with 256 lanes.
+    if (t == 0) t = (sizeof(V) == 16 && B >= 8192 && B <= (size_t(4) << 20)) ? 64 : 256;
     while (t > 64 && uint64_t(t / 2) >= vpb) t /= 2;
     const int u = int(g_unroll.load());
     if (u == 4 && t == 256) return launch_tiles<V, uint32_t, 256, 4>(src, dst, copies, ncopies, B, nt, stream);
@@ -1041,7 +1045,7 @@ int sparbit_tune(const char* key, long long value)
     using namespace sparbit;
     if (!key) return SPARBIT_ERR_ARG;
     if (!std::strcmp(key, "wg_threads")) {
-        if (value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return SPARBIT_ERR_ARG;
+        if (value != 0 && value != 64 && value != 128 && value != 256 && value != 512 && value != 1024) return SPARBIT_ERR_ARG;
         g_wg_threads = value;
     } else if (!std::strcmp(key, "interleave_log2")) {
         if (value < 0 || value > 8) return SPARBIT_ERR_ARG;
