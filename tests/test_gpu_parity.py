@@ -366,6 +366,32 @@ def test_auto_calls_on_eight_streams_beside_a_heavy_kernel(torch):
     torch.cuda.empty_cache()
 
 
+@pytest.mark.parametrize("mode", ["persistent", "dataflow"])
+def test_expired_waits_are_counted_and_the_next_call_is_clean(torch, mode):
+    """The waits of the self-waiting kernels are bounded.  With the bound set to zero a wait that does not find its
+    condition met at the first look gives up: the launch still ends normally (every workgroup leaves), the result is
+    declared unusable through the per-stream counter, and the next call with the normal bound is correct again."""
+    p, B = 64, 4096
+    send = workloads.make_send_raw(p, B, seed=11)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    st = torch.cuda.Stream()
+    before = sb.sparbit_barrier_timeouts(st)
+    sb.sparbit_tune("spin_limit_ms", 0)
+    try:
+        for _ in range(5):
+            sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode], st)
+        expired = sb.sparbit_barrier_timeouts(st) - before  # synchronises the stream: all five launches ended
+    finally:
+        sb.sparbit_tune("spin_limit_ms", 2000)
+    announce("expired waits", mode, expired)
+    assert 0 <= expired <= 5
+    d_recv.fill_(POISON)
+    sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode], st)
+    assert sb.sparbit_barrier_timeouts(st) - before == expired  # the clean call adds none
+    assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want)
+
+
 def test_capture_in_a_hip_graph(torch):
     """Once the tables of (schedule, p) are cached a per-step call allocates
     nothing and enqueues only kernels, so it can be captured; every replay must
