@@ -394,3 +394,33 @@ def test_gpu_allgatherv_capture_in_a_hip_graph():
         g.replay()
         torch.cuda.synchronize()
         assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want), rep
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_expired_waits_are_counted_and_the_next_call_is_clean():
+    """Same bounded waits in the Allgatherv dataflow launch: a zero bound makes them give up, the launches end and
+    are counted, and the next call with the normal bound is correct."""
+    import torch
+    p = 12
+    counts, displs, row = geometry(p, seed=5, align=16, max_len=3000)
+    send = payload(row, 8)
+    want = np.full((p, row), POISON, dtype=np.uint8)
+    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, send, want)
+    dev = torch.device("cuda:0")
+    d_send = torch.from_numpy(send).to(dev)
+    d_recv = torch.full((p * row,), POISON, dtype=torch.uint8, device=dev)
+    st = torch.cuda.Stream()
+    before = sb.sparbit_barrier_timeouts(st)
+    sb.sparbit_tune("spin_limit_ms", 0)
+    try:
+        for _ in range(5):
+            sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+        expired = sb.sparbit_barrier_timeouts(st) - before
+    finally:
+        sb.sparbit_tune("spin_limit_ms", 2000)
+    print("[case] allgatherv expired waits", expired, flush=True)
+    assert 0 <= expired <= 5
+    d_recv.fill_(POISON)
+    sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+    assert sb.sparbit_barrier_timeouts(st) - before == expired
+    assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want)
