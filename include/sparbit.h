@@ -196,7 +196,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          otherwise one launch per step
  *   "hybrid_max_items"     ... where the leading steps that together have at most this many work items (0..1024;
  *                          one workgroup each) share one dataflow launch; 0 = every step its own launch
- *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16)
+ *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16): a block is cut into
+ *                          round(block_bytes / this) equal pieces; AUTO may use 2x or 4x this to fit more steps
  *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
  *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)

@@ -357,7 +357,7 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
 // ---------------------------------------------------------------------------
 // Dataflow form (the non-blocking variant the paper names as future work in
 // its conclusion): one launch, no device-wide barrier.  The unit of work is
-// one chunk (chunk_bytes, the last chunk of a block up to twice that) of one block copy; every chunk of a receive slot
+// one piece of one block copy (a block is cut into round(block_bytes / chunk_bytes) equal pieces); every chunk of a receive slot
 // has a ready flag that holds the number of the call that last filled it.
 // Items are numbered in phase order and dealt round-robin to the workgroups of
 // a grid that the host sizes to be fully resident; a workgroup takes its items
@@ -541,7 +541,8 @@ __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
         const DevPhase P = a.phases[ph];
         const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
         const uint32_t v0 = q * a.chunk_vecs;
-        const uint32_t v1 = (q + 1 == a.chunks_per_block) ? vpb : v0 + a.chunk_vecs;  // the last chunk takes the rest
+        if (v0 >= vpb) continue;  // uniform; only with pieces of a few vectors, where rounding them up can use the block up early
+        const uint32_t v1 = (q + 1 == a.chunks_per_block || vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
         // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
         // the own slot of every rank (block index rank * p + rank of the receive buffer).
         const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
@@ -599,11 +600,14 @@ __global__ __launch_bounds__(WG) void dataflow_var_kernel(const FlowVarArgs va)
         const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
         const uint32_t dst_rank = cp.dst_block / a.p, slot = cp.dst_block - dst_rank * a.p;
         const uint64_t len = va.counts[slot];
-        const uint64_t whole = len / a.chunk_vecs;
-        const uint64_t nchunks = whole ? whole : (len ? 1u : 0u);
-        if (q >= nchunks) continue;  // uniform: nothing of this block falls into chunk q
-        const uint64_t at = uint64_t(q) * a.chunk_vecs;
-        const uint32_t n = uint32_t((q + 1 == nchunks ? len : at + a.chunk_vecs) - at);  // below two chunks
+        // The block's own number of pieces: round(len / chunk), at least one, at most what the longest block has.
+        uint64_t npieces = (len + a.chunk_vecs / 2) / a.chunk_vecs;
+        npieces = npieces > a.chunks_per_block ? a.chunks_per_block : (npieces ? npieces : (len ? 1u : 0u));
+        if (q >= npieces) continue;  // uniform: this block has no piece q
+        const uint64_t piece = ((len + npieces - 1) / npieces + 15) / 16 * 16;  // equal pieces, whole 16-byte vectors
+        const uint64_t at = uint64_t(q) * piece;
+        if (at >= len) continue;
+        const uint32_t n = uint32_t((q + 1 == npieces || len - at < piece ? len : at + piece) - at);  // below 1.5 chunks
         const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
         if (P.src_buf != BUF_SEND && !own_slot && !flow_wait(a, a.flags + cp.src_block * a.chunks_per_block + q)) break;
         const uint64_t src_off = P.src_buf == BUF_SEND
