@@ -380,7 +380,10 @@ int launch_phase_v(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_
     // One wavefront per workgroup (1 KiB tiles) is 0.5-2.5 % ahead of four for 16-byte vectors and blocks of
     // 8 KiB .. 4 MiB (p = 128, B = 1 MiB: 5.128 against 5.160 ms per call); shorter blocks (more workgroups than
     // the launch can hide) and 16 MiB blocks are 1-2 % better off with 256 lanes.
-    if (t == 0) t = (sizeof(V) == 16 && B >= 8192 && B <= (size_t(4) << 20)) ? 64 : 256;
+    // Phases that read the send buffer (own-block placement, DIRECT) re-read a small, cache-resident source and
+    // are bound by their stores; there four times as many workgroups only cost dispatch time (DIRECT, p = 32,
+    // B = 512 KiB: 116 us with 64 lanes, 77 us with 256), so the rule is for forwarding steps only.
+    if (t == 0) t = (sizeof(V) == 16 && B >= 8192 && B <= (size_t(4) << 20) && src == dst) ? 64 : 256;
     while (t > 64 && uint64_t(t / 2) >= vpb) t /= 2;
     const int u = int(g_unroll.load());
     if (u == 4 && t == 256) return launch_tiles<V, uint32_t, 256, 4>(src, dst, copies, ncopies, B, nt, stream);
