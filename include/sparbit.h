@@ -206,6 +206,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "realign_min_bytes"    blocks at least this long that are off the 16-byte grid use the realigning kernel (>= 16)
  *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
+ *   "flow_call_number"     test hook: the 32-bit call counter of the dataflow launches on every stream seen so far
  */
 int sparbit_tune(const char *key, long long value);
 

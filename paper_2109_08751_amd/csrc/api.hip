@@ -240,6 +240,20 @@ int get_flow(DeviceState* ds, hipStream_t stream, size_t nflags, FlowStream** ou
     return SPARBIT_OK;
 }
 
+// The number of the next call on this stream; flags hold the number of the call that last set them, 0 = never.
+// After 2^32 calls the numbers start over, so the flags are cleared first (in stream order, ahead of the launch
+// that uses the new number; a dataflow launch is never recorded into a graph, so the memset is not either).
+int next_epoch(FlowStream* fs, hipStream_t stream, uint32_t* epoch)
+{
+    if (++fs->epoch == 0) {
+        SB_HIP(hipMemsetAsync(fs->flags, 0, fs->flag_capacity * sizeof(uint32_t), stream));
+        SB_HIP(hipMemsetAsync(&fs->state->abort, 0, sizeof(uint32_t), stream));
+        fs->epoch = 1;
+    }
+    *epoch = fs->epoch;
+    return SPARBIT_OK;
+}
+
 int get_work(DeviceState* ds, size_t bytes, bool may_allocate, void** out)
 {
     if (ds->work_bytes < bytes) {
@@ -757,8 +771,7 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
             a.f.chunks_per_block = uint32_t(cpb);
             a.f.chunk_vecs = uint32_t(chunk);
             a.f.flags_per_buf = uint32_t(flags_per_buf);
-            if (++fs->epoch == 0) fs->epoch = 1;
-            a.f.epoch = fs->epoch;
+            if ((rc = next_epoch(fs, stream, &a.f.epoch)) != SPARBIT_OK) return rc;
             a.f.total_items = uint32_t((phases[flow_phases - 1].copies_before + phases[flow_phases - 1].ncopies) * cpb);
             a.f.p = uint32_t(p);
             a.f.in_place = in_place ? 1u : 0u;
@@ -915,8 +928,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         a.chunks_per_block = uint32_t(cpb);
         a.chunk_vecs = uint32_t((((B + cpb - 1) / cpb + 15) / 16 * 16) / unit);  // equal pieces, whole 16-byte vectors
         a.flags_per_buf = uint32_t(flags_per_buf);
-        if (++fs->epoch == 0) fs->epoch = 1;  // wrapped: 0 stays reserved for "never filled"
-        a.epoch = fs->epoch;
+        if ((frc = next_epoch(fs, stream, &a.epoch)) != SPARBIT_OK) return frc;
         a.total_items = uint32_t(items);
         a.p = uint32_t(p);
         a.in_place = in_place ? 1u : 0u;
@@ -1129,6 +1141,12 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "realign_min_bytes")) {
         if (value < 16) return SPARBIT_ERR_ARG;
         g_realign_min_bytes = value;
+    } else if (!std::strcmp(key, "flow_call_number")) {
+        // Test hook: the number the dataflow launches of every known stream count on from (they wrap at 2^32).
+        if (value < 0 || value > 0xffffffffll) return SPARBIT_ERR_ARG;
+        std::lock_guard<std::mutex> lock(g_mutex);
+        for (auto& dev : g_devices)
+            for (auto& fk : dev.second->flows) fk.second.epoch = uint32_t(value);
     } else if (!std::strcmp(key, "spin_limit_ms")) {
         if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;
         g_spin_limit_ms = value;

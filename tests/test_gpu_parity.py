@@ -392,6 +392,28 @@ def test_expired_waits_are_counted_and_the_next_call_is_clean(torch, mode):
     assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want)
 
 
+def test_dataflow_call_counter_wraps(torch):
+    """Ready flags hold the 32-bit number of the call that set them.  When the counter wraps, the flags are cleared
+    before the numbers start over, so stale flags of 2^32 calls ago cannot pass for fresh ones."""
+    p, B = 12, 4096
+    send = workloads.make_send_raw(p, B, seed=21)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    st = torch.cuda.Stream()
+    for _ in range(3):  # calls 1..3 on this stream: flags now hold 1, 2 or 3
+        sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_DATAFLOW, st)
+    st.synchronize()
+    sb.sparbit_tune("flow_call_number", 0xfffffffe)
+    for k in range(5):  # numbers 0xffffffff, then 1 (after the clearing), 2, 3, 4
+        announce("call counter wrap", k)
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_DATAFLOW, st)
+        st.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), k
+    assert sb.sparbit_barrier_timeouts(st) == 0
+
+
 def test_capture_in_a_hip_graph(torch):
     """Once the tables of (schedule, p) are cached a per-step call allocates
     nothing and enqueues only kernels, so it can be captured; every replay must
