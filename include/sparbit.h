@@ -68,9 +68,10 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes: DATAFLOW for jobs of at most 256 work items,
-                                     PERSISTENT for other jobs of at most 4 KiB, else PER_STEP with the first small
-                                     steps (at most 512 work items) merged into one DATAFLOW launch */
+#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes: DATAFLOW for calls of at most 256 work items
+                                     (block copies x 16 KiB pieces) or at most 512 with pieces of up to 64 KiB,
+                                     PERSISTENT for other calls of at most 4 KiB, else PER_STEP with the leading
+                                     small steps (at most 512 work items) merged into one DATAFLOW launch */
 #define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
 #define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
 #define SPARBIT_MODE_DATAFLOW 3   /* one launch; no barrier: a copy starts when the chunk it forwards has landed
