@@ -15,8 +15,12 @@
  *     definition written out.  oracle_allgatherv() is the same simulation with
  *     per-rank block sizes and displacements (MPI_Allgatherv, the extension
  *     named in the paper's conclusion).
- *   - Sparbit, Algorithm 1 (Section III-B), executed literally per rank with
- *     the variables data / ignore / d / last_ignore / ignore_steps.
+ *   - Sparbit (Section III-B, Algorithm 1): in every step each rank forwards
+ *     the blocks it holds, nearest origin first, to the rank d ahead, and d
+ *     halves.  How many it forwards follows from the blocks it really holds
+ *     (counted from its buffer) and from the sub-tree rule of the section's
+ *     prose: everything on a tree-expansion step and below the smallest
+ *     sub-tree, all but the farthest-travelled block otherwise.
  *   - Ring, Recursive Doubling and Bruck as described in Section II-A
  *     (context schedules).
  *
@@ -115,14 +119,6 @@ static int ceil_log2_int(int p)
     while ((1LL << l) < (long long)p)
         l++;
     return l;
-}
-
-static int count_trailing_zeros_int(int p)
-{
-    int n = 0;
-    while (((p >> n) & 1) == 0)
-        n++;
-    return n;
 }
 
 static uint8_t *slot_ptr(sim_t *s, int rank, int slot)
@@ -269,43 +265,59 @@ out:
     return rc;
 }
 
-/* ---- Sparbit, Algorithm 1: per-rank variables exactly as the listing names them */
-typedef struct {
-    int data;
-    int ignore;
-    int d;
-    int last_ignore;
-    unsigned long long ignore_steps;
-} sparbit_rank_t;
-
-static void sparbit_rank_init(sparbit_rank_t *v, int p)
+/* ---- Sparbit (Section III-B) --------------------------------------------------
+ * The p binomial trees advance one level per step: the step with distance d
+ * carries a block from every rank that holds it to the rank d further on.  A
+ * tree over p ranks is made of power-of-two sub-trees, one per set bit of p,
+ * largest first.  Whether a rank forwards everything it holds in a step, or
+ * keeps back the one block that has nowhere left to go, is read off p's binary
+ * representation as the section describes it:
+ *   - d equal to a sub-tree size other than the smallest: a tree expansion,
+ *     every held block is forwarded;
+ *   - d below the smallest sub-tree: the distributions are local to complete
+ *     power-of-two trees, every held block is forwarded;
+ *   - any other d (no sub-tree of that size, or the smallest one): the block
+ *     that travelled farthest arrived at a leaf and is kept back. */
+static int sparbit_forwards_everything(int p, int d)
 {
-    v->data = 1;
-    v->ignore = 0;
-    v->d = 1 << (ceil_log2_int(p) - 1);
-    v->last_ignore = count_trailing_zeros_int(p);
-    v->ignore_steps = (~((unsigned long long)p >> v->last_ignore) | 1ULL) << v->last_ignore;
+    int smallest_subtree = 1;
+    while ((p & smallest_subtree) == 0)
+        smallest_subtree <<= 1;
+    if (d < smallest_subtree)
+        return 1;
+    if (d == smallest_subtree)
+        return 0;
+    return (p & d) != 0;
 }
 
-static void sparbit_rank_post(sparbit_rank_t *v, sim_t *s, int rank)
+/* Blocks rank `rank` holds right now, counted from its receive buffer. */
+static int blocks_held(const sim_t *s, int rank)
+{
+    int k, n = 0;
+    for (k = 0; k < s->p; k++)
+        n += s->written[(size_t)rank * s->p + k];
+    return n;
+}
+
+/* One rank's postings for the step with distance d.  The blocks a rank holds
+ * came from the ranks 0, d', 2d', ... behind it (d' = 2d, the previous
+ * distance), so stripe j is the block of origin rank - 2jd, kept in the slot
+ * of that number; at the receiver, d further on, it is the block from
+ * (2j + 1) d behind.  The stripe kept back, if any, is the last one. */
+static int sparbit_post_step(sim_t *s, int rank, int d)
 {
     const int p = s->p;
+    const int keep_back = sparbit_forwards_everything(p, d) ? 0 : 1;
+    const int stripes = blocks_held(s, rank) - keep_back;
+    const int ahead = (int)mod_ll((long long)rank + d, p);
+    const int behind = (int)mod_ll((long long)rank - d, p);
     int j;
-    if ((unsigned long long)v->d & v->ignore_steps)
-        v->ignore = 1;
-    for (j = 0; j < v->data - v->ignore; j++) {
-        post_isend(s, rank, (int)mod_ll((long long)rank + v->d, p),
-                   (int)mod_ll((long long)rank - 2LL * j * v->d, p));
-        post_irecv(s, rank, (int)mod_ll((long long)rank - v->d, p),
-                   (int)mod_ll((long long)rank - (2LL * j + 1) * v->d, p));
+    for (j = 0; j < stripes; j++) {
+        const long long origin = (long long)rank - 2LL * j * d;
+        post_isend(s, rank, ahead, (int)mod_ll(origin, p));
+        post_irecv(s, rank, behind, (int)mod_ll(origin - d, p));
     }
-}
-
-static void sparbit_rank_advance(sparbit_rank_t *v)
-{
-    v->d = v->d >> 1;
-    v->data = (v->data << 1) - v->ignore;
-    v->ignore = 0;
+    return keep_back;
 }
 
 /* Number of communication steps of a schedule (Section II-A cost formulas,
@@ -353,7 +365,7 @@ static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, co
 {
     sim_t s;
     int rc = ORACLE_OK, r, step, nsteps;
-    sparbit_rank_t *sv = NULL;
+    int sparbit_d = 0, sparbit_kept_back = 0;
     int *bruck_have = NULL;
 
     nsteps = oracle_num_steps(algo, p);
@@ -379,10 +391,8 @@ static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, co
     s.recvs = (post_t *)malloc((size_t)p * s.cap * sizeof(post_t));
     s.nsends = (int *)calloc((size_t)p, sizeof(int));
     s.nrecvs = (int *)calloc((size_t)p, sizeof(int));
-    sv = (sparbit_rank_t *)calloc((size_t)p, sizeof(sparbit_rank_t));
     bruck_have = (int *)calloc((size_t)p, sizeof(int));
-    if (!s.written || !s.sent_now || !s.sends || !s.recvs || !s.nsends || !s.nrecvs || !sv ||
-        !bruck_have) {
+    if (!s.written || !s.sent_now || !s.sends || !s.recvs || !s.nsends || !s.nrecvs || !bruck_have) {
         rc = ORACLE_ERR_NOMEM;
         goto out;
     }
@@ -396,19 +406,19 @@ static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, co
             memcpy(slot_ptr(&s, r, own), (const uint8_t *)send + off[r], len[r]);
         s.written[(size_t)r * p + own] = 1;
         bruck_have[r] = 1;
-        if (algo == ORACLE_SPARBIT && p > 1)
-            sparbit_rank_init(&sv[r], p);
     }
 
     if (max_steps < 0 || max_steps > nsteps)
         max_steps = nsteps;
+    if (algo == ORACLE_SPARBIT && nsteps > 0)
+        sparbit_d = 1 << (nsteps - 1); /* the first level of the trees spans half of 2^ceil(log2 p) */
     for (step = 0; step < max_steps; step++) {
         s.step = step;
         for (r = 0; r < p; r++) {
             int j;
             switch (algo) {
             case ORACLE_SPARBIT:
-                sparbit_rank_post(&sv[r], &s, r);
+                sparbit_kept_back = sparbit_post_step(&s, r, sparbit_d);
                 break;
             case ORACLE_RING:
                 post_isend(&s, r, (int)mod_ll(r + 1, p), (int)mod_ll((long long)r - step, p));
@@ -443,8 +453,8 @@ static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, co
             si[2] = s.nsends[0];
             switch (algo) {
             case ORACLE_SPARBIT:
-                si[0] = sv[0].d;
-                si[1] = sv[0].ignore;
+                si[0] = sparbit_d;
+                si[1] = sparbit_kept_back;
                 break;
             case ORACLE_RING:
                 si[0] = 1;
@@ -457,9 +467,7 @@ static int run_schedule(int algo, int p, size_t row_bytes, const size_t *off, co
         rc = waitall(&s, algo == ORACLE_SPARBIT);
         if (rc != ORACLE_OK)
             goto out;
-        if (algo == ORACLE_SPARBIT)
-            for (r = 0; r < p; r++)
-                sparbit_rank_advance(&sv[r]);
+        sparbit_d /= 2;
     }
 
     if (algo == ORACLE_BRUCK && max_steps == nsteps) {
@@ -488,7 +496,6 @@ out:
     free(s.recvs);
     free(s.nsends);
     free(s.nrecvs);
-    free(sv);
     free(bruck_have);
     return rc;
 }

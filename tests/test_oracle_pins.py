@@ -296,13 +296,16 @@ def test_workload_shapes():
 
 # ---------------------------------------------------------------- planted mistakes
 MUTATIONS = [
-    ("never ignore", "        v->ignore = 1;", "        v->ignore = 0;"),
-    ("send slot sign", "(long long)rank - 2LL * j * v->d, p)", "(long long)rank + 2LL * j * v->d, p)"),
-    ("recv slot off by d", "(long long)rank - (2LL * j + 1) * v->d, p)", "(long long)rank - (2LL * j + 2) * v->d, p)"),
-    ("send peer direction", "mod_ll((long long)rank + v->d, p),", "mod_ll((long long)rank - v->d, p),"),
-    ("data not reduced", "v->data = (v->data << 1) - v->ignore;", "v->data = (v->data << 1);"),
-    ("mask without forced bit", "| 1ULL) << v->last_ignore", "| 0ULL) << v->last_ignore"),
-    ("distance starts one level low", "v->d = 1 << (ceil_log2_int(p) - 1);", "v->d = 1 << (ceil_log2_int(p) - 2);"),
+    ("never keep a block back", "sparbit_forwards_everything(p, d) ? 0 : 1;", "sparbit_forwards_everything(p, d) ? 0 : 0;"),
+    ("send slot sign", "origin = (long long)rank - 2LL * j * d;", "origin = (long long)rank + 2LL * j * d;"),
+    ("recv slot off by d", "(int)mod_ll(origin - d, p));", "(int)mod_ll(origin - 2LL * d, p));"),
+    ("send peer direction", "ahead = (int)mod_ll((long long)rank + d, p);", "ahead = (int)mod_ll((long long)rank - d, p);"),
+    ("held blocks overcounted", "stripes = blocks_held(s, rank) - keep_back;", "stripes = blocks_held(s, rank) + 1 - keep_back;"),
+    ("smallest sub-tree expands", "    if (d == smallest_subtree)\n        return 0;", "    if (d == smallest_subtree)\n        return 1;"),
+    ("missing sub-tree expands", "    return (p & d) != 0;", "    return 1;"),
+    ("keeps back below the smallest sub-tree", "    if (d < smallest_subtree)\n        return 1;", "    if (d < smallest_subtree)\n        return 0;"),
+    ("distance starts one level low", "sparbit_d = 1 << (nsteps - 1);", "sparbit_d = 1 << (nsteps - 2);"),
+    ("distance does not halve", "        sparbit_d /= 2;", "        sparbit_d /= 1;"),
 ]
 
 
