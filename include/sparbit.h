@@ -24,8 +24,19 @@
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
- * without synchronising (the first call for a given (schedule, p) on a device
- * builds and uploads its tables and does synchronise).
+ * without synchronising, with these exceptions, all of them first uses:
+ *   - the first call for a (schedule, p) on a device builds and uploads its
+ *     tables with blocking copies (the TREE form has no tables);
+ *   - the first PERSISTENT or DATAFLOW launch on a stream (AUTO may choose them
+ *     for schedules other than Sparbit) allocates that stream's barrier / flag
+ *     state and synchronises the device once; a later call that needs more ready
+ *     flags than any before it on that stream synchronises the stream, frees the
+ *     flag array and allocates a larger one (device synchronisation again);
+ *   - Bruck's working buffer grows the same way (device synchronisation), is
+ *     one per device and is shared by all streams: Bruck calls on different
+ *     streams must not overlap;
+ *   - Allgatherv: a geometry not among the last 8 used on the device is built
+ *     and uploaded, and evicting the oldest one synchronises the device.
  *
  * Recording into a HIP graph (stream capture).  A call on a capturing stream
  * records one kernel launch per step and nothing else; it is replayed with the
@@ -57,6 +68,10 @@ extern "C" {
                                         capturing stream that would have to allocate or wait on itself */
 #define SPARBIT_ERR_HIP (-4)         /* a HIP call failed; see sparbit_last_hip_error() */
 #define SPARBIT_ERR_NOMEM (-5)       /* host allocation failed */
+#define SPARBIT_ERR_TIMEOUT (-6)     /* an earlier PERSISTENT or DATAFLOW launch on this stream gave up a bounded wait: what
+                                        it wrote is incomplete.  Reported once, by the next call on that stream, which
+                                        enqueues nothing */
+
 
 #define SPARBIT_MAX_P 4096 /* the tables hold p * (p - 1) entries of 8 bytes */
 
@@ -68,18 +83,30 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks from p and block_bytes: DATAFLOW for calls of at most 256 work items
-                                     (block copies x 16 KiB pieces) or at most 512 with pieces of up to 64 KiB,
-                                     PERSISTENT for other calls of at most 4 KiB, else PER_STEP with the leading
-                                     small steps (at most 512 work items) merged into one DATAFLOW launch */
+#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit, blocks on the 16-byte grid (and, from 64 KiB on, on the
+                                     128-byte grid) or shorter than 512 bytes: TREE.  Everything else: DATAFLOW for
+                                     calls of at most 256 work items (block copies x 16 KiB pieces) or at most 512
+                                     with pieces of up to 64 KiB, PERSISTENT (one workgroup) for other calls of at most
+                                     4 KiB, else PER_STEP with the leading small steps (at most 512 work items)
+                                     merged into one DATAFLOW launch */
 #define SPARBIT_MODE_PER_STEP 1   /* one kernel launch per step (Waitall = kernel boundary) */
 #define SPARBIT_MODE_PERSISTENT 2 /* one launch; device-wide barrier between steps */
 #define SPARBIT_MODE_DATAFLOW 3   /* one launch; no barrier: a copy starts when the chunk it forwards has landed
                                      (ready flag per chunk of a receive slot).
-                                     PERSISTENT and DATAFLOW grids wait on themselves and need all their
-                                     workgroups resident: they take at most half of the GPU's wave slots, their
-                                     waits are bounded (see sparbit_barrier_timeouts), and AUTO picks them only
-                                     for jobs of a few workgroups.  PER_STEP never waits on the device. */
+                                     PERSISTENT and DATAFLOW grids wait on themselves.  A persistent grid of more
+                                     than one workgroup is a cooperative launch: the runtime makes the whole grid
+                                     resident or the call fails with SPARBIT_ERR_UNSUPPORTED.  A dataflow grid has
+                                     one workgroup per work item (block copy x piece) and needs no residency: an
+                                     item only waits for items of lower-numbered workgroups, which the GPU starts
+                                     first; a call with more than 2^24 - 1 items is refused (SPARBIT_ERR_UNSUPPORTED).
+                                     Their waits are bounded all the same (see sparbit_barrier_timeouts).
+                                     PER_STEP and TREE never wait on the device. */
+#define SPARBIT_MODE_TREE 4       /* Sparbit only, whole calls only: one launch in which every wavefront carries one
+                                     piece of one block through that block's binomial tree (Section III-B: the p
+                                     trees are independent).  Same messages as Algorithm 1, each read from the
+                                     forwarder's receive buffer; a forwarder's reads of one slot for different steps
+                                     are merged, and the order is any order in which a rank forwards after it
+                                     received.  No table, flag, barrier or device state: nothing waits. */
 
 /*
  * MPI_Allgather over p virtual ranks with the Sparbit schedule (Algorithm 1 of
@@ -162,8 +189,10 @@ typedef struct {
  * sparbit_plan_destroy.  For Bruck the slots are those of the rotated working
  * buffer (working slot i of rank r holds block (r + i) mod p). */
 int sparbit_plan_create(int p, int algo, sparbit_plan_t **out);
-/* ceil(log2 p) for Sparbit and Bruck, p - 1 for Ring, log2 p for Recursive
- * Doubling, 0 for DIRECT; negative error code for a NULL plan. */
+/* ceil(log2 p) for Sparbit (the loop bound of Algorithm 1 and the latency term
+ * of its cost formula, Section III-B) and Bruck, p - 1 for Ring, log2 p for
+ * Recursive Doubling (Section II-A), 0 for DIRECT; negative error code for a
+ * NULL plan. */
 int sparbit_plan_num_steps(const sparbit_plan_t *plan);
 /* Fill *out with pointers into the plan (valid until the plan is destroyed). */
 int sparbit_plan_step(const sparbit_plan_t *plan, int step, sparbit_step_t *out);
@@ -177,11 +206,27 @@ const char *sparbit_strerror(int code);
 /* hipError_t value of the last failed HIP call on this thread (0 if none). */
 int sparbit_last_hip_error(void);
 /*
+ * What the last successful call of this thread enqueued: the number of kernel
+ * launches in *launches and the name of the kernel that moved the most bytes,
+ * spelled as a profiler prints it (template arguments included), in
+ * kernel[0 .. cap) (NUL-terminated, truncated if cap is too small).  Either
+ * pointer may be NULL.  For reports and benchmarks: the library, not its
+ * caller, knows which variant its selection rules picked.
+ */
+int sparbit_last_launch_info(char *kernel, size_t cap, int *launches);
+/*
  * The waits of the persistent kernel (barrier) and of the dataflow kernel (ready
  * flags) are bounded, so that a launch that cannot make progress ends instead
- * of hanging; a launch whose wait expired leaves wrong results and bumps a
- * per-stream counter.  This call synchronises
- * `stream` and stores that counter in *count (0 = every launch completed).
+ * of hanging.  Neither can happen in normal operation: a persistent grid of
+ * more than one workgroup is launched cooperatively (the runtime co-schedules
+ * the whole grid or the call returns SPARBIT_ERR_UNSUPPORTED), and a dataflow
+ * grid has one workgroup per work item, each of which only waits for items of
+ * lower-numbered workgroups, which the GPU starts first.  Should a wait expire
+ * all the same (or be made to, with the "spin_limit_ms" knob), the launch
+ * leaves incomplete results, the next call on that stream returns
+ * SPARBIT_ERR_TIMEOUT without enqueuing anything, and a per-stream counter is
+ * bumped.  This call synchronises `stream` and stores that counter in *count
+ * (0 = every launch completed).
  */
 int sparbit_barrier_timeouts(void *stream, uint64_t *count);
 /*
@@ -199,15 +244,19 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          one workgroup each) share one dataflow launch; 0 = every step its own launch
  *   "flow_chunk_bytes"     unit of work and of readiness of the dataflow kernel (multiple of 16): a block is cut into
  *                          round(block_bytes / this) equal pieces; AUTO may use 2x or 4x this to fit more steps
- *   "flow_wgs_per_cu"      workgroups per compute unit of the dataflow kernel (1..16, capped by occupancy)
  *   "nontemporal"          0/1: loads and stores carry the non-temporal hint
- *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16)
+ *   "wgs_per_cu"           workgroups per compute unit of the persistent kernel (1..16, capped by occupancy)
  *   "var_idle_max"         Allgatherv: a step whose block lengths differ by more than a factor of four still goes out
  *                          as one launch if that starts at most this many workgroups past the end of shorter blocks
  *   "realign_min_bytes"    blocks at least this long that are off the 16-byte grid use the realigning kernel (>= 16)
  *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
- *   "flow_call_number"     test hook: the 32-bit call counter of the dataflow launches on every stream seen so far
+ *   "tree_auto"            0/1: AUTO runs whole Sparbit calls as the tree kernel (default 1)
+ *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12)
+ *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead
+ *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1, 2 or 4
+ *   "tree_store"           its stores: 0 plain, 1 with the non-temporal hint, 2 write-through
+ *   "tree_load_nt"         0/1: its loads carry the non-temporal hint
  */
 int sparbit_tune(const char *key, long long value);
 

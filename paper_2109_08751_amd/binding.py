@@ -19,7 +19,7 @@ import numpy as np
 from . import build as _build
 
 SPARBIT, RING, RECURSIVE_DOUBLING, BRUCK, DIRECT = 0, 1, 2, 3, 4
-MODE_AUTO, MODE_PER_STEP, MODE_PERSISTENT, MODE_DATAFLOW = 0, 1, 2, 3
+MODE_AUTO, MODE_PER_STEP, MODE_PERSISTENT, MODE_DATAFLOW, MODE_TREE = 0, 1, 2, 3, 4
 ALGOS = {"sparbit": SPARBIT, "ring": RING, "recursive_doubling": RECURSIVE_DOUBLING,
          "bruck": BRUCK, "direct": DIRECT}
 
@@ -53,11 +53,18 @@ def _load() -> ctypes.CDLL:
         import torch  # noqa: F401
     except ImportError:
         pass
-    if not os.path.exists(_build.LIB_PATH):
-        _build.build_library()  # raises if hipcc is missing: no silent fallback
+    if _build.is_stale():  # absent, or older than a source: never run a binary that is behind the sources
+        try:
+            _build.build_library()
+        except RuntimeError:
+            if not os.path.exists(_build.LIB_PATH):
+                raise  # no library and no way to build one: no silent fallback
+            import warnings
+            warnings.warn("libsparbit.so is older than its sources and could not be rebuilt")
     L = ctypes.CDLL(_build.LIB_PATH)
     vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     L.sparbit_allgather.argtypes = [vp, vp, ci, sz, vp]
+    L.sparbit_last_launch_info.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ci)]
     L.sparbit_allgather_algo.argtypes = [vp, vp, ci, sz, ci, vp]
     L.sparbit_allgather_mode.argtypes = [vp, vp, ci, sz, ci, ci, vp]
     L.sparbit_allgather_steps.argtypes = [vp, vp, ci, sz, ci, ci, ci, vp]
@@ -74,7 +81,7 @@ def _load() -> ctypes.CDLL:
     L.sparbit_last_hip_error.argtypes = []
     L.sparbit_tune.argtypes = [ctypes.c_char_p, ctypes.c_longlong]
     L.sparbit_barrier_timeouts.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
-    for name in ("sparbit_allgather", "sparbit_allgather_algo", "sparbit_allgather_mode",
+    for name in ("sparbit_allgather", "sparbit_last_launch_info", "sparbit_allgather_algo", "sparbit_allgather_mode",
                  "sparbit_allgather_steps", "sparbit_allgatherv", "sparbit_plan_create", "sparbit_plan_num_steps",
                  "sparbit_plan_step", "sparbit_last_hip_error", "sparbit_tune",
                  "sparbit_barrier_timeouts"):
@@ -119,6 +126,18 @@ def _check(rc: int, where: str) -> None:
 def sparbit_allgather(sendbufs, recvbufs, p: int, block_bytes: int, stream=None) -> None:
     _check(lib.sparbit_allgather(_ptr(sendbufs), _ptr(recvbufs), p, block_bytes, _stream(stream)),
            "sparbit_allgather")
+
+
+def sparbit_last_launch_info() -> tuple:
+    """(kernel name, launches) of this thread's last call."""
+    name = ctypes.create_string_buffer(256)
+    n = ci_zero()
+    _check(lib.sparbit_last_launch_info(name, 256, ctypes.byref(n)), "sparbit_last_launch_info")
+    return name.value.decode(), n.value
+
+
+def ci_zero():
+    return ctypes.c_int(0)
 
 
 def sparbit_allgather_algo(sendbufs, recvbufs, p: int, block_bytes: int, algo: int, stream=None) -> None:

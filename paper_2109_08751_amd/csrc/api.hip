@@ -4,6 +4,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdarg>
+#include <cstdio>
 #include <cstring>
 #include <map>
 #include <memory>
@@ -20,6 +22,38 @@ namespace sparbit {
 namespace {
 
 thread_local int tl_last_hip_error = 0;
+
+// What the current call of this thread has enqueued so far (sparbit_last_launch_info).
+struct LaunchInfo {
+    int launches = 0;
+    uint64_t most_bytes = 0;
+    char kernel[256] = "";
+};
+thread_local LaunchInfo tl_launch_info;
+
+template <typename V>
+constexpr const char* type_label()
+{
+    if constexpr (sizeof(V) == 16) return "unsigned int __vector(4)";
+    else if constexpr (sizeof(V) == 8) return "unsigned long";
+    else if constexpr (sizeof(V) == 4) return "unsigned int";
+    else return "unsigned char";
+}
+
+constexpr const char* bool_label(bool b) { return b ? "true" : "false"; }
+
+// Records one launch that moves `bytes`; the name is kept if no earlier launch of the call moved more.
+__attribute__((format(printf, 2, 3))) void note_launch(uint64_t bytes, const char* fmt, ...)
+{
+    LaunchInfo& li = tl_launch_info;
+    ++li.launches;
+    if (bytes < li.most_bytes || (li.launches > 1 && bytes == li.most_bytes)) return;
+    li.most_bytes = bytes;
+    va_list ap;
+    va_start(ap, fmt);
+    std::vsnprintf(li.kernel, sizeof li.kernel, fmt, ap);
+    va_end(ap);
+}
 
 #define SB_HIP(expr)                                    \
     do {                                                \
@@ -66,12 +100,18 @@ std::atomic<long long> g_persistent_max_bytes{4ll << 10};     // AUTO uses the p
 std::atomic<long long> g_dataflow_max_items{256};             // AUTO uses the dataflow kernel up to this many work items
 std::atomic<long long> g_hybrid_max_items{512};               // AUTO: leading steps with at most this many items share one dataflow launch
 std::atomic<long long> g_flow_chunk_bytes{16384};             // unit of work (and of readiness) of the dataflow kernel
-std::atomic<long long> g_flow_wgs_per_cu{4};                  // workgroups per compute unit of the dataflow kernel (half the wave slots)
 std::atomic<long long> g_wgs_per_cu{1};
 std::atomic<long long> g_spin_limit_ms{2000};
 std::atomic<long long> g_line_align_min_bytes{64ll << 10};    // 16-byte-aligned blocks at least this long, off the 128-byte grid: same
 std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idle workgroups one launch per step may cost before size classes pay
-std::atomic<long long> g_realign_min_bytes{512};              // blocks at least this long, not 16-byte aligned: realigning kernel
+std::atomic<long long> g_realign_min_bytes{512};
+std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
+std::atomic<long long> g_tree_run_log2{5};                    // tree kernel: relative ranks are walked in runs of 2^this
+std::atomic<long long> g_tree_small_bytes{64ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
+std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
+std::atomic<long long> g_tree_store{0};                       // its stores: 0 plain, 1 non-temporal hint, 2 write-through
+std::atomic<long long> g_tree_load_nt{0};                     // its loads carry the non-temporal hint
+std::atomic<long long> g_tree_lds_bytes{0};                   // LDS each of its wavefronts reserves (unused: caps the wavefronts per CU)              // blocks at least this long, not 16-byte aligned: realigning kernel
 
 struct DevicePlan {
     Plan host;
@@ -91,11 +131,18 @@ struct DevicePlan {
     }
 };
 
-struct FlowStream {  // per-stream state of the dataflow kernel
-    FlowState* state = nullptr;
+// Per-stream state of the two kernels that wait on themselves (dataflow: ready flags; persistent: barrier).
+struct StreamState {
+    FlowState* flow = nullptr;
     uint32_t* flags = nullptr;
     size_t flag_capacity = 0;
-    uint32_t epoch = 0;  // last call number handed out (0 is never used: fresh flags are 0)
+    uint32_t epoch = 0;  // last dataflow call number handed out (0 is never used: fresh flags are 0)
+    BarrierState* barrier = nullptr;
+    // Two words of pinned host memory that the device writes when a bounded wait expires ([0] dataflow: the call's
+    // number, [1] persistent: the stream's count of aborted launches), and the values the host has reported so far.
+    uint32_t* note = nullptr;
+    uint32_t* note_dev = nullptr;  // the same words as the device addresses them
+    uint32_t reported[2] = {0, 0};
 };
 
 // Allgatherv: explicit byte-offset copy lists for one (schedule, p, counts, displs, row_bytes).
@@ -131,15 +178,15 @@ struct DeviceState {
     std::map<const void*, int> occupancy;              // resident workgroups per CU, per kernel
     std::vector<std::unique_ptr<VarPlan>> var_plans;  // small most-recently-used cache
     uint64_t var_clock = 0;
-    std::map<hipStream_t, FlowStream> flows;
+    std::map<hipStream_t, StreamState> streams;
     std::map<std::pair<int, int>, std::unique_ptr<DevicePlan>> plans;  // (algo, p)
-    std::map<hipStream_t, BarrierState*> barriers;
     void* work = nullptr;  // Bruck's rotated working buffer
     size_t work_bytes = 0;
 };
 
 std::mutex g_mutex;
 std::map<int, std::unique_ptr<DeviceState>> g_devices;
+std::atomic<int> g_stream_states{0};  // how many StreamState objects hold note words (0: nothing can have expired)
 
 int get_device_state(DeviceState** out)
 {
@@ -201,57 +248,107 @@ int get_plan(DeviceState* ds, int algo, int p, bool may_build, DevicePlan** out)
     return SPARBIT_OK;
 }
 
-int get_barrier(DeviceState* ds, hipStream_t stream, BarrierState** out)
+// The first self-waiting launch on a stream allocates that stream's state (device memory and two pinned host words)
+// and synchronises the device once; growing the flag array synchronises the stream.
+int get_stream_state(DeviceState* ds, hipStream_t stream, StreamState** out)
 {
-    auto it = ds->barriers.find(stream);
-    if (it == ds->barriers.end()) {
-        BarrierState* b = nullptr;
-        SB_HIP(hipMalloc(reinterpret_cast<void**>(&b), sizeof(BarrierState)));
-        SB_HIP(hipMemset(b, 0, sizeof(BarrierState)));
-        SB_HIP(hipDeviceSynchronize());
-        it = ds->barriers.emplace(stream, b).first;
+    StreamState& ss = ds->streams[stream];
+    if (!ss.note) {
+        void* host = nullptr;
+        SB_HIP(hipHostMalloc(&host, 2 * sizeof(uint32_t), hipHostMallocDefault));
+        std::memset(host, 0, 2 * sizeof(uint32_t));
+        void* dev = nullptr;
+        if (hipHostGetDevicePointer(&dev, host, 0) != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipHostFree(host);
+            return SPARBIT_ERR_HIP;
+        }
+        ss.note = static_cast<uint32_t*>(host);
+        ss.note_dev = static_cast<uint32_t*>(dev);
+        g_stream_states.fetch_add(1);
     }
-    *out = it->second;
+    *out = &ss;
     return SPARBIT_OK;
 }
 
-int get_flow(DeviceState* ds, hipStream_t stream, size_t nflags, FlowStream** out)
+int get_barrier(DeviceState* ds, hipStream_t stream, StreamState** out)
 {
-    FlowStream& fs = ds->flows[stream];
-    if (!fs.state) {
-        SB_HIP(hipMalloc(reinterpret_cast<void**>(&fs.state), sizeof(FlowState)));
-        SB_HIP(hipMemset(fs.state, 0, sizeof(FlowState)));
+    StreamState* ss = nullptr;
+    int rc = get_stream_state(ds, stream, &ss);
+    if (rc != SPARBIT_OK) return rc;
+    if (!ss->barrier) {
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&ss->barrier), sizeof(BarrierState)));
+        SB_HIP(hipMemset(ss->barrier, 0, sizeof(BarrierState)));
         SB_HIP(hipDeviceSynchronize());
     }
-    if (fs.flag_capacity < nflags) {
-        if (fs.flags) {
+    *out = ss;
+    return SPARBIT_OK;
+}
+
+int get_flow(DeviceState* ds, hipStream_t stream, size_t nflags, StreamState** out)
+{
+    StreamState* ss = nullptr;
+    int rc = get_stream_state(ds, stream, &ss);
+    if (rc != SPARBIT_OK) return rc;
+    if (!ss->flow) {
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&ss->flow), sizeof(FlowState)));
+        SB_HIP(hipMemset(ss->flow, 0, sizeof(FlowState)));
+        SB_HIP(hipDeviceSynchronize());
+    }
+    if (ss->flag_capacity < nflags) {
+        if (ss->flags) {
             SB_HIP(hipStreamSynchronize(stream));
-            SB_HIP(hipFree(fs.flags));
-            fs.flags = nullptr;
-            fs.flag_capacity = 0;
+            SB_HIP(hipFree(ss->flags));
+            ss->flags = nullptr;
+            ss->flag_capacity = 0;
         }
-        SB_HIP(hipMalloc(reinterpret_cast<void**>(&fs.flags), nflags * sizeof(uint32_t)));
-        SB_HIP(hipMemset(fs.flags, 0, nflags * sizeof(uint32_t)));
+        SB_HIP(hipMalloc(reinterpret_cast<void**>(&ss->flags), nflags * sizeof(uint32_t)));
+        SB_HIP(hipMemset(ss->flags, 0, nflags * sizeof(uint32_t)));
         SB_HIP(hipDeviceSynchronize());
-        fs.flag_capacity = nflags;
-        fs.epoch = 0;
+        ss->flag_capacity = nflags;
+        // The call numbers go on counting: fresh flags are 0, which no call uses, and a number that an expired
+        // wait of an earlier call left in FlowState::abort can then never be handed out again before the wrap.
     }
-    *out = &fs;
+    *out = ss;
     return SPARBIT_OK;
 }
 
 // The number of the next call on this stream; flags hold the number of the call that last set them, 0 = never.
 // After 2^32 calls the numbers start over, so the flags are cleared first (in stream order, ahead of the launch
 // that uses the new number; a dataflow launch is never recorded into a graph, so the memset is not either).
-int next_epoch(FlowStream* fs, hipStream_t stream, uint32_t* epoch)
+int next_epoch(StreamState* ss, hipStream_t stream, uint32_t* epoch)
 {
-    if (++fs->epoch == 0) {
-        SB_HIP(hipMemsetAsync(fs->flags, 0, fs->flag_capacity * sizeof(uint32_t), stream));
-        SB_HIP(hipMemsetAsync(&fs->state->abort, 0, sizeof(uint32_t), stream));
-        fs->epoch = 1;
+    if (++ss->epoch == 0) {
+        SB_HIP(hipMemsetAsync(ss->flags, 0, ss->flag_capacity * sizeof(uint32_t), stream));
+        SB_HIP(hipMemsetAsync(&ss->flow->abort, 0, sizeof(uint32_t), stream));
+        ss->epoch = 1;
     }
-    *epoch = fs->epoch;
+    *epoch = ss->epoch;
     return SPARBIT_OK;
+}
+
+// SPARBIT_ERR_TIMEOUT once for every self-waiting launch on `stream` that ended with an expired wait since the
+// last report.  Reads two words of host memory; no synchronisation.
+int report_expired_waits(hipStream_t stream)
+{
+    if (g_stream_states.load() == 0) return SPARBIT_OK;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int dev = 0;
+    SB_HIP(hipGetDevice(&dev));
+    auto d = g_devices.find(dev);
+    if (d == g_devices.end()) return SPARBIT_OK;
+    auto it = d->second->streams.find(stream);
+    if (it == d->second->streams.end() || !it->second.note) return SPARBIT_OK;
+    StreamState& ss = it->second;
+    bool moved = false;
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t now = __atomic_load_n(&ss.note[i], __ATOMIC_RELAXED);
+        if (now != ss.reported[i]) {
+            ss.reported[i] = now;
+            moved = true;
+        }
+    }
+    return moved ? SPARBIT_ERR_TIMEOUT : SPARBIT_OK;
 }
 
 int get_work(DeviceState* ds, size_t bytes, bool may_allocate, void** out)
@@ -311,6 +408,9 @@ int launch_tiles(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t 
     uint32_t lg_g = 0;
     bool loop = false;  // blocks with more tiles than the grid holds: the kernel takes several trips
     if (!tile_grid((vpb + U - 1) / U, ncopies, T, &grid, &lg_g, &loop)) return SPARBIT_ERR_ARG;
+    const bool plain_nt = nt && ((uintptr_t(dst) | uintptr_t(B)) & 127) != 0;
+    note_launch(uint64_t(ncopies) * B, "sparbit::copy_tiles_kernel<%s, %s, %d, %d, %s, %s, %s>", type_label<V>(),
+                type_label<Index>(), T, U, bool_label(loop || nt), bool_label(loop), bool_label(loop || !plain_nt));
     if (loop)
         hipLaunchKernelGGL((copy_tiles_kernel<V, Index, T, U, true, true>), grid, dim3(T), 0, stream, src, dst, copies,
                            ncopies, uint64_t(B), lg_g);
@@ -338,6 +438,7 @@ int launch_flat(const uint8_t* src, uint8_t* dst, const Copy* copies, uint32_t n
     const uint64_t total = uint64_t(vpb) * ncopies;
     const uint64_t ntiles = (total + WG * U - 1) / (WG * U);
     if (total + WG * U > 0xffffffffull) return SPARBIT_ERR_ARG;  // cannot happen: ncopies < 2^25, vpb < 64
+    note_launch(uint64_t(ncopies) * B, "sparbit::copy_flat_kernel<%s, unsigned int, %d, %s>", type_label<V>(), U, bool_label(nt));
     if (nt)
         hipLaunchKernelGGL((copy_flat_kernel<V, uint32_t, U, true>), dim3(uint32_t(ntiles)), dim3(WG), 0, stream, src,
                            dst, copies, uint64_t(B), vpb, uint32_t(total));
@@ -356,6 +457,7 @@ int launch_realign_t(const uint8_t* src, uint8_t* dst, const Copy* copies, uint3
     uint32_t lg_g = 0;
     bool capped = false;  // the kernel loops, so a capped grid is fine
     if (!tile_grid(B >> 4, ncopies, T, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
+    note_launch(uint64_t(ncopies) * B, "sparbit::copy_tiles_realign_kernel<%d, %s>", T, bool_label(nt));
     if (nt)
         hipLaunchKernelGGL((copy_tiles_realign_kernel<T, true>), grid, dim3(T), 0, stream, src, dst, copies, ncopies,
                            uint64_t(B), lg_g);
@@ -446,6 +548,8 @@ int resident_per_cu(DeviceState* ds, Kernel kernel, int* out)
     return SPARBIT_OK;
 }
 
+// A grid of more than one workgroup meets at device-wide barriers, so all of it must be resident at once: it goes
+// out as a cooperative launch, which the runtime co-schedules or refuses.  A single workgroup needs no such care.
 template <typename V>
 int launch_persistent_v(const PersistentArgs& a, DeviceState* ds, uint64_t max_tiles, hipStream_t stream)
 {
@@ -459,34 +563,107 @@ int launch_persistent_v(const PersistentArgs& a, DeviceState* ds, uint64_t max_t
     long long want = g_wgs_per_cu.load();
     if (want < 1) want = 1;
     if (per_cu < 1) return SPARBIT_ERR_HIP;
-    const int half = per_cu > 1 ? per_cu / 2 : 1;
-    if (want > half) want = half;  // every workgroup must be resident, and the rest of the GPU stays usable
+    if (want > per_cu) want = per_cu;
     uint64_t grid = uint64_t(num_cus) * uint64_t(want);
     if (grid > max_tiles) grid = max_tiles ? max_tiles : 1;  // no more workgroups than the largest phase has tiles
-    if (nt)
-        hipLaunchKernelGGL((persistent_kernel<V, U, true>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
-    else
-        hipLaunchKernelGGL((persistent_kernel<V, U, false>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    note_launch(max_tiles * uint64_t(WG * U) * sizeof(V), "sparbit::persistent_kernel<%s, %d, %s>", type_label<V>(), U, bool_label(nt));
+    const void* fn = nt ? reinterpret_cast<const void*>(persistent_kernel<V, U, true>)
+                        : reinterpret_cast<const void*>(persistent_kernel<V, U, false>);
+    if (grid == 1) {
+        if (nt)
+            hipLaunchKernelGGL((persistent_kernel<V, U, true>), dim3(1), dim3(WG), 0, stream, a);
+        else
+            hipLaunchKernelGGL((persistent_kernel<V, U, false>), dim3(1), dim3(WG), 0, stream, a);
+        SB_HIP(hipGetLastError());
+        return SPARBIT_OK;
+    }
+    PersistentArgs args = a;
+    void* params[] = {&args};
+    const hipError_t e = hipLaunchCooperativeKernel(fn, dim3(uint32_t(grid)), dim3(WG), params, 0, stream);
+    if (e == hipErrorCooperativeLaunchTooLarge) {
+        (void)hipGetLastError();
+        return SPARBIT_ERR_UNSUPPORTED;
+    }
+    SB_HIP(e);
+    return SPARBIT_OK;
+}
+
+// The dataflow grid has exactly one workgroup per work item.  An item only waits for an item with a lower number,
+// and the dispatcher starts the workgroups of a grid in increasing order (each XCD its share of them), so whatever
+// a resident workgroup waits for is resident too or has finished: the grid makes progress whatever part of it is
+// resident and whatever else runs on the GPU, including other such grids.
+constexpr uint64_t kMaxFlowItems = (uint64_t(1) << 32) / WG - 1;  // a grid's x extent times its block size stays below 2^32
+
+template <typename V, bool REALIGN = false>
+int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
+{
+    note_launch(uint64_t(a.total_items / a.chunks_per_block) * a.block_bytes, "sparbit::dataflow_kernel<%s, %s>", type_label<V>(),
+                bool_label(REALIGN));
+    hipLaunchKernelGGL((dataflow_kernel<V, REALIGN>), dim3(a.total_items), dim3(WG), 0, stream, a);
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
 
-template <typename V, bool REALIGN = false>
-int launch_dataflow_v(const FlowArgs& a, DeviceState* ds, hipStream_t stream)
+// The tree kernel: one wavefront per (tree, piece of 64 * U vectors).  False in *eligible when the piece count does
+// not fit a grid (blocks of several GiB): the caller falls back to per-step launches.
+template <typename V, int U, int NB>
+int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool load_nt, hipStream_t stream)
 {
-    const int num_cus = ds->num_cus;
-    int per_cu = 0;
-    const int rc = resident_per_cu(ds, dataflow_kernel<V, REALIGN>, &per_cu);
-    if (rc != SPARBIT_OK) return rc;
-    if (per_cu < 1) return SPARBIT_ERR_HIP;
-    long long want = g_flow_wgs_per_cu.load();
-    const int half = per_cu > 1 ? per_cu / 2 : 1;
-    if (want > half) want = half;  // every workgroup must be resident, and the rest of the GPU stays usable
-    uint64_t grid = uint64_t(num_cus) * uint64_t(want);
-    if (grid > a.total_items) grid = a.total_items;
-    hipLaunchKernelGGL((dataflow_kernel<V, REALIGN>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    note_launch(uint64_t(a.p) * a.p * a.block_bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s>", type_label<V>(), U, NB,
+                sizeof(V) == 16 ? store_kind : 0, bool_label(sizeof(V) == 16 && load_nt));
+    const uint32_t lds = uint32_t(g_tree_lds_bytes.load());
+    if constexpr (sizeof(V) == 16) {
+        if (store_kind == 2 && load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 2, true>), grid, dim3(64), lds, stream, a);
+        else if (store_kind == 2) hipLaunchKernelGGL((tree_kernel<V, U, NB, 2, false>), grid, dim3(64), lds, stream, a);
+        else if (store_kind == 1 && load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, true>), grid, dim3(64), lds, stream, a);
+        else if (store_kind == 1) hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, false>), grid, dim3(64), lds, stream, a);
+        else if (load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, true>), grid, dim3(64), lds, stream, a);
+        else hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false>), grid, dim3(64), lds, stream, a);
+    } else {
+        hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false>), grid, dim3(64), lds, stream, a);
+    }
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
+}
+
+int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, int width, hipStream_t stream, bool* eligible)
+{
+    *eligible = false;
+    if (p == 1 && !sendbufs) {  // in place with one rank: nothing moves
+        *eligible = true;
+        return SPARBIT_OK;
+    }
+    int U = width == 16 ? int(g_tree_unroll.load()) : 1;
+    const uint64_t vpb = B / size_t(width);
+    while (U > 1 && vpb <= uint64_t(64 * (U / 2))) U /= 2;  // short blocks: no lanes that only idle
+    const uint64_t pieces = (vpb + uint64_t(64 * U) - 1) / uint64_t(64 * U);
+    uint32_t lg_g = uint32_t(g_interleave_log2.load());
+    while (lg_g > 0 && (1u << lg_g) > uint32_t(p)) --lg_g;
+    if ((pieces << lg_g) > 0x7fffffffull / 64) return SPARBIT_OK;  // the grid's x extent stays below 2^31 lanes
+    const uint32_t groups = (uint32_t(p) + (1u << lg_g) - 1) >> lg_g;  // at most 4096: fits the y extent
+    TreeArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.send = static_cast<const uint8_t*>(sendbufs);
+    a.recv = static_cast<uint8_t*>(recvbufs);
+    a.block_bytes = B;
+    a.vpb = vpb;
+    a.p = uint32_t(p);
+    a.top = p > 1 ? 1u << (ceil_log2(p) - 1) : 0u;
+    // Jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips.
+    const bool small = uint64_t(p) * uint64_t(p) * B <= uint64_t(g_tree_small_bytes.load());
+    a.lg_k = small ? uint32_t(ceil_log2(p)) : uint32_t(g_tree_run_log2.load());
+    a.lg_g = lg_g;
+    const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
+    const int st = int(g_tree_store.load());
+    const bool ldnt = g_tree_load_nt.load() != 0;
+    *eligible = true;
+    if (width == 16) {
+        if (U == 4) return launch_tree_vu<u32x4, 4, 4>(a, grid, st, ldnt, stream);
+        if (U == 2) return launch_tree_vu<u32x4, 2, 8>(a, grid, st, ldnt, stream);
+        return launch_tree_vu<u32x4, 1, 8>(a, grid, st, ldnt, stream);
+    }
+    if (width == 4) return launch_tree_vu<uint32_t, 1, 8>(a, grid, 0, false, stream);
+    return launch_tree_vu<uint8_t, 1, 8>(a, grid, 0, false, stream);
 }
 
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb);
@@ -596,6 +773,7 @@ int launch_var_realign(const uint8_t* src, uint8_t* dst, const VarCopy* copies, 
     uint32_t lg_g = 0;
     bool capped = false;  // the kernel loops, so a capped grid is fine
     if (!tile_grid(max_len >> 4, ncopies, WG, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
+    note_launch(uint64_t(ncopies) * max_len, "sparbit::copy_var_realign_kernel<%s>", bool_label(g_nontemporal.load() != 0));
     if (g_nontemporal.load() != 0)
         hipLaunchKernelGGL((copy_var_realign_kernel<true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
     else
@@ -618,6 +796,8 @@ int launch_var(const uint8_t* src, uint8_t* dst, const VarCopy* copies, uint32_t
     if (!tile_grid(max_len / sizeof(V), ncopies, WG, &grid, &lg_g, &capped)) return SPARBIT_ERR_ARG;
     if (capped)  // a block too long for one tile per workgroup: the looping kernel
         return launch_var_realign(src, dst, copies, ncopies, max_len, stream);
+    note_launch(uint64_t(ncopies) * max_len, "sparbit::copy_var_kernel<%s, %s, %s>", type_label<V>(),
+                bool_label(g_nontemporal.load() != 0), bool_label(g_nontemporal.load() != 0 && write_through));
     if (g_nontemporal.load() != 0 && write_through)
         hipLaunchKernelGGL((copy_var_kernel<V, true, true>), grid, dim3(WG), 0, stream, src, dst, copies, ncopies, lg_g);
     else if (g_nontemporal.load() != 0)
@@ -684,18 +864,10 @@ FlowChoice choose_flow(const std::vector<DevPhase>& phases, uint64_t block)
 }
 
 template <bool ON_GRID>
-int launch_dataflow_var(const FlowVarArgs& a, DeviceState* ds, hipStream_t stream)
+int launch_dataflow_var(const FlowVarArgs& a, hipStream_t stream)
 {
-    int per_cu = 0;
-    const int rc = resident_per_cu(ds, dataflow_var_kernel<ON_GRID>, &per_cu);
-    if (rc != SPARBIT_OK) return rc;
-    if (per_cu < 1) return SPARBIT_ERR_HIP;
-    long long want = g_flow_wgs_per_cu.load();
-    const int half = per_cu > 1 ? per_cu / 2 : 1;
-    if (want > half) want = half;
-    uint64_t grid = uint64_t(ds->num_cus) * uint64_t(want);
-    if (grid > a.f.total_items) grid = a.f.total_items;
-    hipLaunchKernelGGL((dataflow_var_kernel<ON_GRID>), dim3(uint32_t(grid)), dim3(WG), 0, stream, a);
+    note_launch(uint64_t(a.f.total_items) * a.f.chunk_vecs, "sparbit::dataflow_var_kernel<%s>", bool_label(ON_GRID));
+    hipLaunchKernelGGL((dataflow_var_kernel<ON_GRID>), dim3(a.f.total_items), dim3(WG), 0, stream, a);
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
@@ -703,6 +875,7 @@ int launch_dataflow_var(const FlowVarArgs& a, DeviceState* ds, hipStream_t strea
 int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, const size_t* displs, size_t row_bytes,
           int algo, void* stream_v)
 {
+    tl_launch_info = LaunchInfo();
     if (p < 1 || p > SPARBIT_MAX_P || !recvbufs || !counts || !displs) return SPARBIT_ERR_ARG;
     if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
     if (algo == SPARBIT_ALGO_BRUCK) return SPARBIT_ERR_UNSUPPORTED;  // its rotated buffer assumes equal blocks
@@ -732,6 +905,10 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     if (packed) return run(sendbufs, recvbufs, p, counts[0], algo, SPARBIT_MODE_AUTO, true, 0, 0, stream_v);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const bool capturing = stream_is_capturing(stream);
+    if (!capturing) {
+        const int erc = report_expired_waits(stream);
+        if (erc != SPARBIT_OK) return erc;
+    }
 
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState* ds = nullptr;
@@ -755,8 +932,9 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
         const uint64_t cpb = fc.cpb;
         flow_phases = fc.phases;
         const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
-        if (flow_phases && flags_per_buf <= 0x3fffffffull) {
-            FlowStream* fs = nullptr;
+        if (flow_phases && flags_per_buf <= 0x3fffffffull &&
+            (phases[flow_phases - 1].copies_before + phases[flow_phases - 1].ncopies) * cpb <= kMaxFlowItems) {
+            StreamState* fs = nullptr;
             if ((rc = get_flow(ds, stream, size_t(flags_per_buf), &fs)) != SPARBIT_OK) return rc;
             FlowVarArgs a;
             std::memset(&a, 0, sizeof a);
@@ -764,7 +942,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
             a.f.base[1] = base[1];
             a.f.copies = dp->d_copies;
             a.f.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
-            a.f.state = fs->state;
+            a.f.state = fs->flow;
+            a.f.note = fs->note_dev;
             a.f.flags = fs->flags;
             a.f.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
             a.f.nphases = uint32_t(flow_phases);
@@ -778,7 +957,7 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
             a.counts = vp->d_geometry;
             a.displs = vp->d_geometry + p;
             a.row_bytes = row_bytes;
-            rc = width == 16 ? launch_dataflow_var<true>(a, ds, stream) : launch_dataflow_var<false>(a, ds, stream);
+            rc = width == 16 ? launch_dataflow_var<true>(a, stream) : launch_dataflow_var<false>(a, stream);
             if (rc != SPARBIT_OK) return rc;
         } else {
             flow_phases = 0;
@@ -823,9 +1002,10 @@ bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb)
 int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mode, bool whole, int first_step,
         int last_step, void* stream_v)
 {
+    tl_launch_info = LaunchInfo();
     if (p < 1 || p > SPARBIT_MAX_P || !recvbufs) return SPARBIT_ERR_ARG;
     if (algo < SPARBIT_ALGO_SPARBIT || algo > SPARBIT_ALGO_DIRECT) return SPARBIT_ERR_ARG;
-    if (mode < SPARBIT_MODE_AUTO || mode > SPARBIT_MODE_DATAFLOW) return SPARBIT_ERR_ARG;
+    if (mode < SPARBIT_MODE_AUTO || mode > SPARBIT_MODE_TREE) return SPARBIT_ERR_ARG;
     const unsigned __int128 total128 = (unsigned __int128)(uint64_t(p) * uint64_t(p)) * B;
     if (total128 > (unsigned __int128)0x7fffffffffffffffull) return SPARBIT_ERR_ARG;
     const size_t recv_bytes = size_t(p) * size_t(p) * B;
@@ -843,6 +1023,30 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     }
 
     const bool capturing = stream_is_capturing(stream);
+    const bool explicit_mode = mode != SPARBIT_MODE_AUTO;
+    // A self-waiting launch on this stream that gave up since the last report: say so now, and enqueue nothing.
+    if (!capturing) {
+        const int erc = report_expired_waits(stream);
+        if (erc != SPARBIT_OK) return erc;
+    }
+
+    // The tree kernel needs no table, no flag and no state, so it is decided before anything is looked up or built
+    // (and a capturing stream can record it like any other launch).  AUTO takes it for every whole Sparbit call
+    // whose blocks are on the 16-byte grid or too short for the realigning kernel.
+    if (mode == SPARBIT_MODE_TREE && (algo != SPARBIT_ALGO_SPARBIT || !whole)) return SPARBIT_ERR_UNSUPPORTED;
+    if (whole && algo == SPARBIT_ALGO_SPARBIT) {
+        const int w = access_width(sendbufs, recvbufs, nullptr, B);
+        const bool on_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0 || B < size_t(g_line_align_min_bytes.load());
+        if (mode == SPARBIT_MODE_TREE ||
+            (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0 &&
+             (w == 16 ? on_lines : B < size_t(g_realign_min_bytes.load())))) {
+            bool eligible = false;
+            const int trc = launch_tree(sendbufs, recvbufs, p, B, w, stream, &eligible);
+            if (trc != SPARBIT_OK || eligible) return trc;
+            if (mode == SPARBIT_MODE_TREE) return SPARBIT_ERR_UNSUPPORTED;  // blocks of several GiB
+        }
+    }
+
     if (capturing) {
         if (mode == SPARBIT_MODE_PERSISTENT || mode == SPARBIT_MODE_DATAFLOW) return SPARBIT_ERR_UNSUPPORTED;
         mode = SPARBIT_MODE_PER_STEP;
@@ -908,9 +1112,9 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         const size_t unit = realign ? 1 : size_t(width);
         const uint64_t items = (phases[nph - 1].copies_before + phases[nph - 1].ncopies) * cpb;
         const uint64_t flags_per_buf = uint64_t(p) * uint64_t(p) * cpb;
-        if (items > 0x7fffffffull || flags_per_buf > 0x3fffffffull || B / unit > 0xffffffffull)
+        if (items > kMaxFlowItems || flags_per_buf > 0x3fffffffull || B / unit > 0xffffffffull)
             return SPARBIT_OK;  // too many items for one grid, or offsets inside a block beyond the kernel's 32 bits
-        FlowStream* fs = nullptr;
+        StreamState* fs = nullptr;
         int frc = get_flow(ds, stream, size_t(2 * flags_per_buf), &fs);
         if (frc != SPARBIT_OK) return frc;
         FlowArgs a;
@@ -920,7 +1124,8 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         a.base[2] = base[2];
         a.copies = dp->d_copies;
         a.phases = in_place ? dp->d_phases_in_place : dp->d_phases;
-        a.state = fs->state;
+        a.state = fs->flow;
+        a.note = fs->note_dev;
         a.flags = fs->flags;
         a.block_bytes = B;
         a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;
@@ -933,16 +1138,17 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         a.p = uint32_t(p);
         a.in_place = in_place ? 1u : 0u;
         *launched = true;
-        if (realign) return launch_dataflow_v<uint8_t, true>(a, ds, stream);
+        if (realign) return launch_dataflow_v<uint8_t, true>(a, stream);
         switch (width) {
-        case 16: return launch_dataflow_v<u32x4>(a, ds, stream);
-        case 4: return launch_dataflow_v<uint32_t>(a, ds, stream);
-        default: return launch_dataflow_v<uint8_t>(a, ds, stream);
+        case 16: return launch_dataflow_v<u32x4>(a, stream);
+        case 4: return launch_dataflow_v<uint32_t>(a, stream);
+        default: return launch_dataflow_v<uint8_t>(a, stream);
         }
     };
     if (whole && mode == SPARBIT_MODE_DATAFLOW && !phases.empty()) {
         bool launched = false;
         if ((rc = launch_flow(phases.size(), &launched)) != SPARBIT_OK || launched) return rc;
+        if (explicit_mode) return SPARBIT_ERR_UNSUPPORTED;  // more work items than one grid holds
         mode = SPARBIT_MODE_PER_STEP;
     }
     if (flow_prefix) {
@@ -962,7 +1168,10 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
         a.block_bytes = B;
         a.nphases = uint32_t(phases.size());
         a.spin_limit_ticks = uint64_t(g_spin_limit_ms.load()) * 100000ull;  // 100 MHz counter
-        if ((rc = get_barrier(ds, stream, &a.bar)) != SPARBIT_OK) return rc;
+        StreamState* bs = nullptr;
+        if ((rc = get_barrier(ds, stream, &bs)) != SPARBIT_OK) return rc;
+        a.bar = bs->barrier;
+        a.note = bs->note_dev + 1;
         uint64_t max_tiles = 1;
         for (const DevPhase& ph : phases) {
             const uint64_t t = ((B / size_t(width)) * ph.ncopies + WG * 4 - 1) / (WG * 4);
@@ -1045,10 +1254,14 @@ void sparbit_finalize(void)
         (void)hipDeviceSynchronize();  // queued launches may still read the tables
         ds->plans.clear();  // frees the device tables while this device is current
         ds->var_plans.clear();
-        for (auto& bk : ds->barriers) (void)hipFree(bk.second);
-        for (auto& fk : ds->flows) {
-            (void)hipFree(fk.second.state);
-            (void)hipFree(fk.second.flags);
+        for (auto& sk : ds->streams) {
+            (void)hipFree(sk.second.barrier);
+            (void)hipFree(sk.second.flow);
+            (void)hipFree(sk.second.flags);
+            if (sk.second.note) {
+                (void)hipHostFree(sk.second.note);
+                sparbit::g_stream_states.fetch_sub(1);
+            }
         }
         if (ds->work) (void)hipFree(ds->work);
     }
@@ -1065,11 +1278,41 @@ const char* sparbit_strerror(int code)
     case SPARBIT_ERR_UNSUPPORTED: return "schedule does not support this call";
     case SPARBIT_ERR_HIP: return "HIP runtime error";
     case SPARBIT_ERR_NOMEM: return "out of host memory";
+    case SPARBIT_ERR_TIMEOUT: return "an earlier self-waiting launch on this stream gave up a bounded wait; its results are incomplete";
     default: return "unknown error";
     }
 }
 
 int sparbit_last_hip_error(void) { return sparbit::tl_last_hip_error; }
+
+int sparbit_last_launch_info(char* kernel, size_t cap, int* launches)
+{
+    const sparbit::LaunchInfo& li = sparbit::tl_launch_info;
+    if (launches) *launches = li.launches;
+    if (kernel && cap) {
+        std::strncpy(kernel, li.kernel, cap - 1);
+        kernel[cap - 1] = '\0';
+    }
+    return SPARBIT_OK;
+}
+
+// Test hook, deliberately absent from sparbit.h: moves the 32-bit call counter of the dataflow launches of every
+// known stream forward to `value` (they wrap at 2^32), so that a test reaches the wrap without 2^32 calls.  Only
+// forward: a number already handed out may still sit in a ready flag.
+int sparbit_test_set_flow_call_number(long long value)
+{
+    using namespace sparbit;
+    if (value < 0 || value > 0xffffffffll) return SPARBIT_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* ds = nullptr;
+    int rc = get_device_state(&ds);
+    if (rc != SPARBIT_OK) return rc;
+    for (auto& sk : ds->streams)
+        if (sk.second.flow && sk.second.epoch > uint32_t(value)) return SPARBIT_ERR_ARG;
+    for (auto& sk : ds->streams)
+        if (sk.second.flow) sk.second.epoch = uint32_t(value);
+    return SPARBIT_OK;
+}
 
 int sparbit_barrier_timeouts(void* stream_v, uint64_t* count)
 {
@@ -1083,16 +1326,15 @@ int sparbit_barrier_timeouts(void* stream_v, uint64_t* count)
         int rc = get_device_state(&ds);
         if (rc != SPARBIT_OK) return rc;
         SB_HIP(hipStreamSynchronize(stream));
-        auto it = ds->barriers.find(stream);
-        if (it != ds->barriers.end()) {
+        auto it = ds->streams.find(stream);
+        if (it != ds->streams.end() && it->second.barrier) {
             BarrierState host;
-            SB_HIP(hipMemcpy(&host, it->second, sizeof host, hipMemcpyDeviceToHost));
+            SB_HIP(hipMemcpy(&host, it->second.barrier, sizeof host, hipMemcpyDeviceToHost));
             *count += host.errors;
         }
-        auto jt = ds->flows.find(stream);
-        if (jt != ds->flows.end() && jt->second.state) {
+        if (it != ds->streams.end() && it->second.flow) {
             FlowState host;
-            SB_HIP(hipMemcpy(&host, jt->second.state, sizeof host, hipMemcpyDeviceToHost));
+            SB_HIP(hipMemcpy(&host, it->second.flow, sizeof host, hipMemcpyDeviceToHost));
             *count += host.errors;
         }
         return SPARBIT_OK;
@@ -1121,9 +1363,6 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "dataflow_max_items")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_dataflow_max_items = value;
-    } else if (!std::strcmp(key, "flow_wgs_per_cu")) {
-        if (value < 1 || value > 16) return SPARBIT_ERR_ARG;
-        g_flow_wgs_per_cu = value;
     } else if (!std::strcmp(key, "flow_chunk_bytes")) {
         if (value < 16 || (value & 15)) return SPARBIT_ERR_ARG;
         g_flow_chunk_bytes = value;
@@ -1141,12 +1380,25 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "realign_min_bytes")) {
         if (value < 16) return SPARBIT_ERR_ARG;
         g_realign_min_bytes = value;
-    } else if (!std::strcmp(key, "flow_call_number")) {
-        // Test hook: the number the dataflow launches of every known stream count on from (they wrap at 2^32).
-        if (value < 0 || value > 0xffffffffll) return SPARBIT_ERR_ARG;
-        std::lock_guard<std::mutex> lock(g_mutex);
-        for (auto& dev : g_devices)
-            for (auto& fk : dev.second->flows) fk.second.epoch = uint32_t(value);
+    } else if (!std::strcmp(key, "tree_auto")) {
+        g_tree_auto = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_run_log2")) {
+        if (value < 0 || value > 12) return SPARBIT_ERR_ARG;
+        g_tree_run_log2 = value;
+    } else if (!std::strcmp(key, "tree_small_bytes")) {
+        if (value < 0) return SPARBIT_ERR_ARG;
+        g_tree_small_bytes = value;
+    } else if (!std::strcmp(key, "tree_unroll")) {
+        if (value != 1 && value != 2 && value != 4) return SPARBIT_ERR_ARG;
+        g_tree_unroll = value;
+    } else if (!std::strcmp(key, "tree_store")) {
+        if (value < 0 || value > 2) return SPARBIT_ERR_ARG;
+        g_tree_store = value;
+    } else if (!std::strcmp(key, "tree_load_nt")) {
+        g_tree_load_nt = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_lds_bytes")) {
+        if (value < 0 || value > 65536) return SPARBIT_ERR_ARG;
+        g_tree_lds_bytes = value;
     } else if (!std::strcmp(key, "spin_limit_ms")) {
         if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;
         g_spin_limit_ms = value;

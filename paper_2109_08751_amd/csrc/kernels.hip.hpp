@@ -90,6 +90,121 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
 }
 
 // ---------------------------------------------------------------------------
+// Tree form of Sparbit (Section III-B: p binomial trees, the tree of block b
+// shifted by b, all advancing together).  The trees never touch each other's
+// data -- tree b only reads and writes slot b of the receive buffers -- and
+// neither do different byte ranges of one block, so one wavefront can carry
+// one piece of one block through its whole tree with no flag, no barrier and
+// no table: lane l moves the same 16 bytes of the piece in every message, and
+// a load that follows the same lane's store to the same address sees that
+// store (program order of one thread).
+//
+// The messages of tree b, in relative ranks rho = (rank - b) mod p: the step
+// with distance d sends from every rho that is a multiple of 2d to rho + d, as
+// long as rho + d < p (that bound is the "ignore" rule: the stripe kept back is
+// the one whose destination would pass the root again).  So rho received the
+// block in the step whose distance is the lowest set bit of rho, and forwards it
+// to rho + d' for every smaller power of two d' with rho + d' < p.  A forwarder
+// is read once, when its turn comes, and the value is stored to all of its
+// destinations: the reads that its forwards of different steps would make of
+// the same slot are merged.
+//
+// Order.  Any order in which a rank is read after it was written is valid; the
+// parent of rho is rho minus its lowest set bit, so increasing rho is one.  The
+// kernel walks runs of K = 2^lg_k consecutive relative ranks; inside a run it
+// goes level by level (the run's first rank, then +K/2, then +K/4 and +3K/4,
+// ...), loading a batch of forwarders at once.  Small K keeps the distance
+// between the write and the read of a slot short (the read hits the cache that
+// holds the write); K >= p is the step order of Algorithm 1 (all forwards of a
+// step before the next step), which has the fewest dependent round trips.
+//
+// Workgroups are single wavefronts; blockIdx.x interleaves 2^lg_g trees so that
+// each XCD streams through the pieces of one tree at a time.
+// ---------------------------------------------------------------------------
+struct TreeArgs {
+    const uint8_t* send;  // nullptr: in place, slot r of rank r already holds rank r's block
+    uint8_t* recv;
+    uint64_t block_bytes;
+    uint64_t vpb;   // vectors per block
+    uint32_t p;
+    uint32_t top;   // distance of the first step: 2^(ceil(log2 p) - 1), 0 for p = 1
+    uint32_t lg_k;
+    uint32_t lg_g;
+};
+
+template <typename V, int ST>
+__device__ __forceinline__ void tree_store(V* p, V v)
+{
+    if constexpr (ST == 2 && sizeof(V) == 16)
+        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+    else if constexpr (ST == 1)
+        __builtin_nontemporal_store(v, p);
+    else
+        *p = v;
+}
+
+template <typename V, int U, int NB, int ST, bool LDNT>
+__global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
+{
+    const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
+    const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
+    if (b >= a.p) return;
+    const uint64_t v0 = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U) + threadIdx.x;
+    const uint32_t p = a.p;
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) ok[u] = v0 + uint64_t(u * 64) < a.vpb;
+    // Slot b of the rank at relative rank rho.  No __restrict__ anywhere: a slot is written and later read.
+    auto slot = [&](uint32_t rho) -> V* {
+        uint32_t r = b + rho;
+        if (r >= p) r -= p;
+        return reinterpret_cast<V*>(a.recv + (uint64_t(r) * p + b) * a.block_bytes) + v0;
+    };
+    auto load = [&](const V* s, V (&x)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) x[u] = ld<V, LDNT>(s + u * 64);
+    };
+    auto store = [&](V* d, const V (&x)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (ok[u]) tree_store<V, ST>(d + u * 64, x[u]);
+    };
+    const uint32_t K = 1u << a.lg_k;
+    for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
+        const uint32_t end = (p - h < K) ? p : h + K;
+        {
+            V x[U];
+            if (h == 0 && a.send) {
+                load(reinterpret_cast<const V*>(a.send + uint64_t(b) * a.block_bytes) + v0, x);
+                store(slot(0), x);  // own-block placement
+            } else if ((h & 1u) == 0 && h + 1 < p) {  // it forwards: even, and rank h + 1 exists
+                load(slot(h), x);
+            }
+            for (uint32_t d = h ? ((h & (0u - h)) >> 1) : a.top; d >= 1; d >>= 1)
+                if (d < p - h) store(slot(h + d), x);
+        }
+        for (uint32_t st = K >> 1; st >= 2; st >>= 1) {  // forwarders whose lowest set bit is st
+            for (uint32_t n0 = h + st; n0 < end; n0 += 2 * st * NB) {
+                V x[NB][U];
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const uint32_t n = n0 + 2 * st * i;
+                    if (n < end && n + 1 < p) load(slot(n), x[i]);
+                }
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const uint32_t n = n0 + 2 * st * i;
+                    if (n < end)
+                        for (uint32_t d = st >> 1; d >= 1; d >>= 1)
+                            if (d < p - n) store(slot(n + d), x[i]);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Blocks of different sizes (Allgatherv): every copy carries its own byte
 // offsets and length.  Same shape as copy_tiles_kernel -- one tile per
 // workgroup, copies dealt round-robin to consecutive workgroups -- with the
@@ -285,6 +400,7 @@ struct PersistentArgs {
     const Copy* copies;
     const DevPhase* phases;
     BarrierState* bar;
+    uint32_t* note;  // host-visible word: receives the stream's count of aborted launches when this one aborts
     uint64_t block_bytes;
     uint64_t spin_limit_ticks;  // bounded wait, in 100 MHz wall-clock ticks
     uint32_t nphases;
@@ -345,7 +461,9 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
         const uint32_t n = __hip_atomic_fetch_add(&a.bar->left, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
         if (n == nwg - 1) {
             if (__hip_atomic_load(&a.bar->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                __hip_atomic_fetch_add(&a.bar->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t n_aborted =
+                    __hip_atomic_fetch_add(&a.bar->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1u;
+                __hip_atomic_store(a.note, n_aborted, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // the host's next call sees it
                 __hip_atomic_store(&a.bar->abort, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
             __hip_atomic_store(&a.bar->arrived, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -359,14 +477,14 @@ __global__ __launch_bounds__(WG) void persistent_kernel(const PersistentArgs a)
 // its conclusion): one launch, no device-wide barrier.  The unit of work is
 // one piece of one block copy (a block is cut into round(block_bytes / chunk_bytes) equal pieces); every chunk of a receive slot
 // has a ready flag that holds the number of the call that last filled it.
-// Items are numbered in phase order and dealt round-robin to the workgroups of
-// a grid that the host sizes to be fully resident; a workgroup takes its items
-// in increasing order, waits for the flag of the item's source chunk (unless
-// the source is the send buffer or, in place, a rank's own slot), copies, and
-// publishes the flag of the destination chunk.  An item only waits for an
-// item of an earlier phase, i.e. a lower number, so the lowest unfinished item
-// can always run: no deadlock while all workgroups are resident.  Waits are
-// bounded all the same.
+// Items are numbered in phase order, one workgroup per item; a workgroup waits
+// for the flag of its item's source chunk (unless the source is the send buffer
+// or, in place, a rank's own slot), copies, and publishes the flag of the
+// destination chunk.  An item only waits for an item of an earlier phase, i.e.
+// a lower-numbered workgroup, and workgroups are started in increasing order,
+// so whatever a resident workgroup waits for is itself resident or done: the
+// grid makes progress whatever part of it is resident.  Waits are bounded all
+// the same.
 //
 // What this machine makes expensive, and how the kernel avoids it:
 //  - a device-scope atomic read-modify-write on one address costs ~70 ns and
@@ -433,6 +551,7 @@ struct FlowArgs {
     const Copy* copies;
     const DevPhase* phases;
     FlowState* state;
+    uint32_t* note;          // host-visible word: receives this call's number when one of its waits expires
     uint32_t* flags;         // [2][p * p * chunks_per_block]: receive buffer, then the working buffer
     uint64_t block_bytes;
     uint64_t spin_limit_ticks;
@@ -492,8 +611,10 @@ __device__ __forceinline__ bool flow_wait(const FlowArgs& a, const uint32_t* fla
             const bool expired = uint64_t(wall_clock64()) - t0 > a.spin_limit_ticks;
             if (expired || __hip_atomic_load(&a.state->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == a.epoch) {
                 if (expired && __hip_atomic_exchange(&a.state->abort, a.epoch, __ATOMIC_RELAXED,
-                                                     __HIP_MEMORY_SCOPE_AGENT) != a.epoch)
+                                                     __HIP_MEMORY_SCOPE_AGENT) != a.epoch) {
                     __hip_atomic_fetch_add(&a.state->errors, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(a.note, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);  // the host's next call sees it
+                }
                 good = 0;
                 break;
             }
@@ -528,48 +649,58 @@ __device__ __forceinline__ void coherent_copy_vectors(const u32x4* __restrict__ 
     for (v += threadIdx.x; v < n; v += WG) coherent_st<u32x4>(d + v, coherent_ld<u32x4>(s + v));
 }
 
-// REALIGN (with V = uint8_t): chunks of blocks that are off the 16-byte grid move through coherent_realign_chunk.
+// The phase that copy ordinal k (counted over the call) belongs to: the last one that starts at or before k.
+__device__ __forceinline__ uint32_t phase_of_copy(const DevPhase* __restrict__ phases, uint32_t nphases, uint32_t k)
+{
+    uint32_t lo = 0, hi = nphases - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (phases[mid].copies_before <= k) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// One workgroup per item.  REALIGN (with V = uint8_t): chunks of blocks that are off the 16-byte grid move through
+// coherent_realign_chunk.
 template <typename V, bool REALIGN = false>
 __global__ __launch_bounds__(WG) void dataflow_kernel(const FlowArgs a)
 {
     const uint32_t vpb = uint32_t(a.block_bytes / sizeof(V));
-    uint32_t ph = 0;  // items come in phase order, so the phase index only moves forward
-    for (uint32_t item = blockIdx.x; item < a.total_items; item += gridDim.x) {
-        const uint32_t k = item / a.chunks_per_block;  // copy ordinal within the call
-        const uint32_t q = item - k * a.chunks_per_block;
-        while (ph + 1 < a.nphases && a.phases[ph + 1].copies_before <= k) ++ph;
-        const DevPhase P = a.phases[ph];
-        const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
-        const uint32_t v0 = q * a.chunk_vecs;
-        if (v0 >= vpb) continue;  // uniform; only with pieces of a few vectors, where rounding them up can use the block up early
-        const uint32_t v1 = (q + 1 == a.chunks_per_block || vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
-        // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
-        // the own slot of every rank (block index rank * p + rank of the receive buffer).
-        const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
-        if (P.src_buf != BUF_SEND && !own_slot &&
-            !flow_wait(a, a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.src_block * a.chunks_per_block + q))
-            break;  // uniform: the whole workgroup leaves
-        const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
-        V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
-        if constexpr (REALIGN) {
-            static_assert(sizeof(V) == 1, "chunk bounds are byte offsets");
-            coherent_realign_chunk(reinterpret_cast<const uint8_t*>(s) + v0, reinterpret_cast<uint8_t*>(d) + v0, v1 - v0);
-        } else if constexpr (sizeof(V) == 16) {
-            coherent_copy_vectors(s + v0, d + v0, v1 - v0);
-        } else {
-            constexpr int U = 8;
-            for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
-                V x[U];
+    const uint32_t item = blockIdx.x;
+    if (item >= a.total_items) return;
+    const uint32_t k = item / a.chunks_per_block;  // copy ordinal within the call
+    const uint32_t q = item - k * a.chunks_per_block;
+    const DevPhase P = a.phases[phase_of_copy(a.phases, a.nphases, k)];
+    const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
+    const uint32_t v0 = q * a.chunk_vecs;
+    if (v0 >= vpb) return;  // uniform; only with pieces of a few vectors, where rounding them up can use the block up early
+    const uint32_t v1 = (q + 1 == a.chunks_per_block || vpb - v0 < a.chunk_vecs) ? vpb : v0 + a.chunk_vecs;
+    // Sources that were complete before the launch need no wait: the send buffer, and in an in-place call
+    // the own slot of every rank (block index rank * p + rank of the receive buffer).
+    const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
+    if (P.src_buf != BUF_SEND && !own_slot &&
+        !flow_wait(a, a.flags + (P.src_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.src_block * a.chunks_per_block + q))
+        return;  // uniform: the whole workgroup leaves
+    const V* __restrict__ s = reinterpret_cast<const V*>(a.base[P.src_buf] + uint64_t(cp.src_block) * a.block_bytes);
+    V* __restrict__ d = reinterpret_cast<V*>(const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(cp.dst_block) * a.block_bytes);
+    if constexpr (REALIGN) {
+        static_assert(sizeof(V) == 1, "chunk bounds are byte offsets");
+        coherent_realign_chunk(reinterpret_cast<const uint8_t*>(s) + v0, reinterpret_cast<uint8_t*>(d) + v0, v1 - v0);
+    } else if constexpr (sizeof(V) == 16) {
+        coherent_copy_vectors(s + v0, d + v0, v1 - v0);
+    } else {
+        constexpr int U = 8;
+        for (uint32_t v = v0 + threadIdx.x; v < v1; v += WG * U) {
+            V x[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (v + u * WG < v1) x[u] = coherent_ld<V>(s + v + u * WG);
+            for (int u = 0; u < U; ++u)
+                if (v + u * WG < v1) x[u] = coherent_ld<V>(s + v + u * WG);
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
-            }
+            for (int u = 0; u < U; ++u)
+                if (v + u * WG < v1) coherent_st<V>(d + v + u * WG, x[u]);
         }
-        flow_publish(a, a.flags + (P.dst_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.dst_block * a.chunks_per_block + q);
     }
+    flow_publish(a, a.flags + (P.dst_buf == BUF_WORK ? a.flags_per_buf : 0u) + cp.dst_block * a.chunks_per_block + q);
 }
 
 // ---------------------------------------------------------------------------
@@ -591,36 +722,34 @@ template <bool ON_GRID>
 __global__ __launch_bounds__(WG) void dataflow_var_kernel(const FlowVarArgs va)
 {
     const FlowArgs& a = va.f;
-    uint32_t ph = 0;
-    for (uint32_t item = blockIdx.x; item < a.total_items; item += gridDim.x) {
-        const uint32_t k = item / a.chunks_per_block;
-        const uint32_t q = item - k * a.chunks_per_block;
-        while (ph + 1 < a.nphases && a.phases[ph + 1].copies_before <= k) ++ph;
-        const DevPhase P = a.phases[ph];
-        const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
-        const uint32_t dst_rank = cp.dst_block / a.p, slot = cp.dst_block - dst_rank * a.p;
-        const uint64_t len = va.counts[slot];
-        // The block's own number of pieces: round(len / chunk), at least one, at most what the longest block has.
-        uint64_t npieces = (len + a.chunk_vecs / 2) / a.chunk_vecs;
-        npieces = npieces > a.chunks_per_block ? a.chunks_per_block : (npieces ? npieces : (len ? 1u : 0u));
-        if (q >= npieces) continue;  // uniform: this block has no piece q
-        const uint64_t piece = ((len + npieces - 1) / npieces + 15) / 16 * 16;  // equal pieces, whole 16-byte vectors
-        const uint64_t at = uint64_t(q) * piece;
-        if (at >= len) continue;
-        const uint32_t n = uint32_t((q + 1 == npieces || len - at < piece ? len : at + piece) - at);  // below 1.5 chunks
-        const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
-        if (P.src_buf != BUF_SEND && !own_slot && !flow_wait(a, a.flags + cp.src_block * a.chunks_per_block + q)) break;
-        const uint64_t src_off = P.src_buf == BUF_SEND
-                                     ? va.displs[cp.src_block]
-                                     : uint64_t(cp.src_block / a.p) * va.row_bytes + va.displs[cp.src_block % a.p];
-        const uint8_t* __restrict__ s = a.base[P.src_buf] + src_off + at;
-        uint8_t* __restrict__ d = const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(dst_rank) * va.row_bytes + va.displs[slot] + at;
-        if constexpr (ON_GRID)
-            coherent_copy_vectors(reinterpret_cast<const u32x4*>(s), reinterpret_cast<u32x4*>(d), n >> 4);
-        else
-            coherent_realign_chunk(s, d, n);
-        flow_publish(a, a.flags + cp.dst_block * a.chunks_per_block + q);
-    }
+    const uint32_t item = blockIdx.x;
+    if (item >= a.total_items) return;
+    const uint32_t k = item / a.chunks_per_block;
+    const uint32_t q = item - k * a.chunks_per_block;
+    const DevPhase P = a.phases[phase_of_copy(a.phases, a.nphases, k)];
+    const Copy cp = a.copies[P.first_copy + (k - P.copies_before)];
+    const uint32_t dst_rank = cp.dst_block / a.p, slot = cp.dst_block - dst_rank * a.p;
+    const uint64_t len = va.counts[slot];
+    // The block's own number of pieces: round(len / chunk), at least one, at most what the longest block has.
+    uint64_t npieces = (len + a.chunk_vecs / 2) / a.chunk_vecs;
+    npieces = npieces > a.chunks_per_block ? a.chunks_per_block : (npieces ? npieces : (len ? 1u : 0u));
+    if (q >= npieces) return;  // uniform: this block has no piece q
+    const uint64_t piece = ((len + npieces - 1) / npieces + 15) / 16 * 16;  // equal pieces, whole 16-byte vectors
+    const uint64_t at = uint64_t(q) * piece;
+    if (at >= len) return;
+    const uint32_t n = uint32_t((q + 1 == npieces || len - at < piece ? len : at + piece) - at);  // below 1.5 chunks
+    const bool own_slot = a.in_place != 0 && P.src_buf == BUF_RECV && cp.src_block / a.p == cp.src_block % a.p;
+    if (P.src_buf != BUF_SEND && !own_slot && !flow_wait(a, a.flags + cp.src_block * a.chunks_per_block + q)) return;
+    const uint64_t src_off = P.src_buf == BUF_SEND
+                                 ? va.displs[cp.src_block]
+                                 : uint64_t(cp.src_block / a.p) * va.row_bytes + va.displs[cp.src_block % a.p];
+    const uint8_t* __restrict__ s = a.base[P.src_buf] + src_off + at;
+    uint8_t* __restrict__ d = const_cast<uint8_t*>(a.base[P.dst_buf]) + uint64_t(dst_rank) * va.row_bytes + va.displs[slot] + at;
+    if constexpr (ON_GRID)
+        coherent_copy_vectors(reinterpret_cast<const u32x4*>(s), reinterpret_cast<u32x4*>(d), n >> 4);
+    else
+        coherent_realign_chunk(s, d, n);
+    flow_publish(a, a.flags + cp.dst_block * a.chunks_per_block + q);
 }
 
 }  // namespace sparbit

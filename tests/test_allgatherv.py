@@ -397,9 +397,10 @@ def test_gpu_allgatherv_capture_in_a_hip_graph():
 
 
 @pytest.mark.gpu
-def test_gpu_allgatherv_expired_waits_are_counted_and_the_next_call_is_clean():
+def test_gpu_allgatherv_expired_waits_are_reported_and_the_next_call_is_clean():
     """Same bounded waits in the Allgatherv dataflow launch: a zero bound makes them give up, the launches end and
-    are counted, and the next call with the normal bound is correct."""
+    are counted, the next call on the stream answers SPARBIT_ERR_TIMEOUT once, and the call after it, with the
+    normal bound, is correct."""
     import torch
     p = 12
     counts, displs, row = geometry(p, seed=5, align=16, max_len=3000)
@@ -410,17 +411,29 @@ def test_gpu_allgatherv_expired_waits_are_counted_and_the_next_call_is_clean():
     d_send = torch.from_numpy(send).to(dev)
     d_recv = torch.full((p * row,), POISON, dtype=torch.uint8, device=dev)
     st = torch.cuda.Stream()
+    call = lambda: sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
     before = sb.sparbit_barrier_timeouts(st)
     sb.sparbit_tune("spin_limit_ms", 0)
+    reports = 0
     try:
         for _ in range(5):
-            sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+            try:
+                call()
+            except sb.SparbitError as e:  # an earlier one of the five already ended with an expired wait
+                assert e.code == -6
+                reports += 1
         expired = sb.sparbit_barrier_timeouts(st) - before
     finally:
         sb.sparbit_tune("spin_limit_ms", 2000)
-    print("[case] allgatherv expired waits", expired, flush=True)
+    print("[case] allgatherv expired waits", expired, "reported while issuing", reports, flush=True)
     assert 0 <= expired <= 5
     d_recv.fill_(POISON)
-    sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+    torch.cuda.synchronize()
+    try:
+        call()
+        assert expired == 0 or reports > 0
+    except sb.SparbitError as e:
+        assert e.code == -6 and expired > 0
+        call()
     assert sb.sparbit_barrier_timeouts(st) - before == expired
     assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want)

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 POISON = workloads.POISON
 MODES = {"per_step": sb.MODE_PER_STEP, "persistent": sb.MODE_PERSISTENT, "auto": sb.MODE_AUTO,
-         "dataflow": sb.MODE_DATAFLOW}
+         "dataflow": sb.MODE_DATAFLOW, "tree": sb.MODE_TREE}
 ORACLE_ALGO = {sb.SPARBIT: oracle.SPARBIT, sb.RING: oracle.RING,
                sb.RECURSIVE_DOUBLING: oracle.RECURSIVE_DOUBLING, sb.BRUCK: oracle.BRUCK,
                sb.DIRECT: oracle.NAIVE}
@@ -69,7 +69,7 @@ def gpu_result(torch, algo, p, B, send, mode, in_place=False, misalign=0, send_m
 
 
 # ------------------------------------------------------------------ the configs
-@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "auto"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "tree", "auto"])
 @pytest.mark.parametrize("cfg", ["cfg1", "cfg3", "cfg2"])
 def test_config_matches_oracle_element_by_element(torch, cfg, mode):
     w = workloads.WORKLOADS[cfg]
@@ -98,7 +98,7 @@ def test_every_step_boundary_matches_oracle(torch, cfg):
 
 
 # ------------------------------------------------------------------ sweeps
-@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "tree"])
 def test_every_p_up_to_33_and_ragged_block_sizes(torch, mode):
     for p in list(range(1, 34)) + [63, 65, 100]:
         for B in (1, 3, 20, 100, 4096 + 16):
@@ -111,7 +111,7 @@ def test_every_p_up_to_33_and_ragged_block_sizes(torch, mode):
             assert np.array_equal(got, want), (p, B)
 
 
-@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "tree"])
 @pytest.mark.parametrize("misalign", [1, 4, 16])
 def test_misaligned_base_pointers(torch, mode, misalign):
     for p, B in ((6, 1024), (21, 48), (5, 70000), (33, 4100)):
@@ -158,7 +158,7 @@ def test_realigning_kernel_on_tiny_blocks(torch):
         sb.sparbit_tune("realign_min_bytes", 512)
 
 
-@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow"])
+@pytest.mark.parametrize("mode", ["per_step", "persistent", "dataflow", "tree"])
 def test_in_place(torch, mode):
     for p, B in ((1, 64), (6, 1024), (21, 48), (64, 4096), (257, 16)):
         announce("in place", mode, p, B)
@@ -173,7 +173,7 @@ def test_large_rank_count(torch):
     announce("p=1000")
     send = workloads.make_send_raw(p, B, seed=5)
     want = np.broadcast_to(send[None], (p, p, B))  # oracle pinned to this at p=1000 in the CPU tests
-    for mode in ("per_step", "persistent", "dataflow"):
+    for mode in ("per_step", "persistent", "dataflow", "tree"):
         got = gpu_result(torch, sb.SPARBIT, p, B, send, MODES[mode])
         assert np.array_equal(got, want)
 
@@ -234,9 +234,11 @@ def expected_origins(p, max_steps=-1):
     return recv
 
 
+@pytest.mark.parametrize("mode", ["auto", "per_step"])
 @pytest.mark.parametrize("cfg", ["cfg4", "cfg5"])
-def test_full_size_configs(torch, cfg):
-    """16 GiB receive buffers, launch configuration of the benchmark (AUTO).
+def test_full_size_configs(torch, cfg, mode):
+    """16 GiB receive buffers, in the launch configuration the benchmark times (AUTO: the tree kernel) and as one
+    launch per step.
     Every slot is compared on the device with the block the oracle says it must
     hold (oracle run on rank tags), after the last-but-one step (unreceived
     slots still poison) and at the end; sampled slots are also copied back and
@@ -262,9 +264,12 @@ def test_full_size_configs(torch, cfg):
         assert torch.equal(d_recv[r], want), (cfg, "intermediate", r)
         del want
 
-    announce(cfg, "whole call, AUTO mode")
+    announce(cfg, "whole call,", mode)
     d_recv.fill_(POISON)
-    sb.sparbit_allgather(d_send, d_recv, p, B)
+    if mode == "auto":
+        sb.sparbit_allgather(d_send, d_recv, p, B)
+    else:
+        sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode])
     torch.cuda.synchronize()
     origin = expected_origins(p)
     assert (origin == np.arange(p)[None, :]).all()
@@ -279,6 +284,8 @@ def test_full_size_configs(torch, cfg):
     for line in open("/proc/meminfo"):
         if line.startswith("MemAvailable:"):
             avail = int(line.split()[1]) * 1024
+    if mode != "auto":
+        return  # the byte-for-byte oracle run once per configuration is enough
     if avail < 3 * w.recv_bytes:
         print("[case]", cfg, "full-size oracle run skipped: host memory", avail >> 30, "GiB", flush=True)
         return
@@ -332,10 +339,20 @@ def test_two_host_threads(torch):
         assert np.array_equal(results[i], want)
 
 
-def test_auto_calls_on_eight_streams_beside_a_heavy_kernel(torch):
-    """AUTO sends small jobs and the leading steps of larger ones through grids that wait on ready flags.  Eight
+@pytest.mark.parametrize("tree_auto", [0, 1])
+def test_auto_calls_on_eight_streams_beside_a_heavy_kernel(torch, tree_auto):
+    """With the tree kernel switched off AUTO sends small jobs and the leading steps of larger ones through grids
+    that wait on ready flags (as it does for the other schedules); with it on, every call is one tree launch.  Eight
     streams issue such calls at once while another stream keeps the whole GPU busy with writes: every result must
     match the oracle and no bounded wait may expire."""
+    sb.sparbit_tune("tree_auto", tree_auto)
+    try:
+        _eight_streams(torch)
+    finally:
+        sb.sparbit_tune("tree_auto", 1)
+
+
+def _eight_streams(torch):
     dev = torch.device("cuda:0")
     cases = [(96, 4096), (64, 16384), (125, 512), (32, 65536), (12, 1024), (6, 1024), (256, 64), (16, 262144)]
     streams = [torch.cuda.Stream() for _ in cases]
@@ -366,30 +383,105 @@ def test_auto_calls_on_eight_streams_beside_a_heavy_kernel(torch):
     torch.cuda.empty_cache()
 
 
+def _calls_until_quiet(call, limit=8):
+    """Issues `call` until it neither raises nor leaves anything to report; returns how many times the library
+    answered SPARBIT_ERR_TIMEOUT (-6)."""
+    reports = 0
+    for _ in range(limit):
+        try:
+            call()
+            return reports
+        except sb.SparbitError as e:
+            assert e.code == -6, e
+            reports += 1
+    raise AssertionError("the stream never became quiet")
+
+
 @pytest.mark.parametrize("mode", ["persistent", "dataflow"])
-def test_expired_waits_are_counted_and_the_next_call_is_clean(torch, mode):
+def test_expired_waits_are_reported_and_the_next_call_is_clean(torch, mode):
     """The waits of the self-waiting kernels are bounded.  With the bound set to zero a wait that does not find its
-    condition met at the first look gives up: the launch still ends normally (every workgroup leaves), the result is
-    declared unusable through the per-stream counter, and the next call with the normal bound is correct again."""
+    condition met at the first look gives up: the launch still ends normally (every workgroup leaves), the per-stream
+    counter moves, the next call on that stream answers SPARBIT_ERR_TIMEOUT once and enqueues nothing, and the call
+    after that, with the normal bound, is correct again."""
     p, B = 64, 4096
     send = workloads.make_send_raw(p, B, seed=11)
     want = oracle_result(sb.SPARBIT, p, B, send)
     d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
     st = torch.cuda.Stream()
+    call = lambda: sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode], st)
+    call()  # allocates the stream's state with the normal bound
     before = sb.sparbit_barrier_timeouts(st)
     sb.sparbit_tune("spin_limit_ms", 0)
+    reports = 0
     try:
         for _ in range(5):
-            sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode], st)
-        expired = sb.sparbit_barrier_timeouts(st) - before  # synchronises the stream: all five launches ended
+            try:
+                call()
+            except sb.SparbitError as e:  # an earlier one of the five already ended with an expired wait
+                assert e.code == -6
+                reports += 1
+        expired = sb.sparbit_barrier_timeouts(st) - before  # synchronises the stream: all launches ended
     finally:
         sb.sparbit_tune("spin_limit_ms", 2000)
-    announce("expired waits", mode, expired)
+    announce("expired waits", mode, expired, "reported while issuing", reports)
     assert 0 <= expired <= 5
     d_recv.fill_(POISON)
-    sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode], st)
+    torch.cuda.synchronize()
+    # Every launch has ended, so whatever expired is visible to the host now: reported by the next call (one report
+    # covers all launches since the last one), which enqueues nothing.
+    try:
+        call()
+        assert expired == 0 or reports > 0
+    except sb.SparbitError as e:
+        assert e.code == -6 and expired > 0
+        torch.cuda.synchronize()
+        assert bool((d_recv == POISON).all())  # nothing was enqueued
+        call()
     assert sb.sparbit_barrier_timeouts(st) - before == expired  # the clean call adds none
     assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want)
+    # other entry points on that stream are quiet as well
+    sb.sparbit_allgather(d_send, d_recv, p, B, st)
+    st.synchronize()
+
+
+def test_call_numbers_go_on_when_the_flag_array_grows(torch):
+    """An expired wait leaves its call's number in the stream's abort word.  When a later, larger call makes the
+    library allocate a bigger flag array, the numbers must not start over: the call that would get that number again
+    would take every unsatisfied wait for aborted and return incomplete results without any error."""
+    st = torch.cuda.Stream()
+    small = (12, 4096)
+    large = (64, 4096)
+    bufs = {}
+    for p, B in (small, large):
+        send = workloads.make_send_raw(p, B, seed=p)
+        bufs[(p, B)] = (send, *gpu_buffers(torch, p, B, send)[:2])
+    def call(pb):
+        p, B = pb
+        sb.sparbit_allgather_mode(bufs[pb][1], bufs[pb][2], p, B, sb.SPARBIT, sb.MODE_DATAFLOW, st)
+    call(small)  # call number 1 of this stream
+    st.synchronize()
+    sb.sparbit_tune("spin_limit_ms", 0)
+    try:
+        for _ in range(3):  # numbers 2 .. 4; whichever expire leave their number behind
+            try:
+                call(small)
+            except sb.SparbitError as e:
+                assert e.code == -6
+        st.synchronize()
+    finally:
+        sb.sparbit_tune("spin_limit_ms", 2000)
+    expired = sb.sparbit_barrier_timeouts(st)
+    announce("expired before the growth", expired)
+    _calls_until_quiet(lambda: call(small))
+    for k in range(6):  # the first of these grows the flag array; none may reuse a number from above
+        p, B = large
+        bufs[large][2].fill_(POISON)
+        torch.cuda.synchronize()
+        call(large)
+        st.synchronize()
+        want = oracle_result(sb.SPARBIT, p, B, bufs[large][0])
+        assert np.array_equal(bufs[large][2].cpu().numpy().reshape(p, p, B), want), k
+    assert sb.sparbit_barrier_timeouts(st) == expired
 
 
 def test_dataflow_call_counter_wraps(torch):
@@ -403,7 +495,11 @@ def test_dataflow_call_counter_wraps(torch):
     for _ in range(3):  # calls 1..3 on this stream: flags now hold 1, 2 or 3
         sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_DATAFLOW, st)
     st.synchronize()
-    sb.sparbit_tune("flow_call_number", 0xfffffffe)
+    import ctypes
+    hook = sb.lib.sparbit_test_set_flow_call_number  # exported for this test only, not declared in sparbit.h
+    hook.argtypes, hook.restype = [ctypes.c_longlong], ctypes.c_int
+    assert hook(2) == -1  # only forward: numbers already handed out may still sit in ready flags
+    assert hook(0xfffffffe) == 0
     for k in range(5):  # numbers 0xffffffff, then 1 (after the clearing), 2, 3, 4
         announce("call counter wrap", k)
         d_recv.fill_(POISON)
@@ -439,10 +535,19 @@ def test_capture_in_a_hip_graph(torch):
 
 
 def test_capture_of_an_auto_call_records_the_per_step_form(torch):
-    """A small AUTO call runs the dataflow kernel when issued eagerly; that kernel's call number is a launch
+    """With the tree kernel switched off (AUTO as it is for the other schedules), a small AUTO call runs the
+    dataflow kernel when issued eagerly; that kernel's call number is a launch
     argument, so a replay would find every ready flag already set.  On a capturing stream AUTO therefore records
     the per-step launches, the self-waiting modes are refused, and so is a call whose tables do not exist yet;
     the refused calls record nothing, so the graph still replays correctly."""
+    sb.sparbit_tune("tree_auto", 0)
+    try:
+        _capture_of_an_auto_call(torch)
+    finally:
+        sb.sparbit_tune("tree_auto", 1)
+
+
+def _capture_of_an_auto_call(torch):
     w = workloads.WORKLOADS["cfg1"]
     p, B = w.p, w.block_bytes
     send = workloads.make_send(w)
@@ -484,6 +589,7 @@ def test_auto_merges_leading_steps_into_one_dataflow_launch(torch):
     cases = ((sb.SPARBIT, 125, 512, False), (sb.SPARBIT, 64, 16384, False), (sb.SPARBIT, 33, 40000, True),
              (sb.RING, 40, 4096, False), (sb.RING, 17, 70000, True), (sb.BRUCK, 96, 4096, False),
              (sb.RECURSIVE_DOUBLING, 32, 65536, False), (sb.SPARBIT, 257, 1040, False), (sb.SPARBIT, 21, 4100, False))
+    sb.sparbit_tune("tree_auto", 0)  # Sparbit too goes the way of the other schedules here
     try:
         for limit in (0, 64, 300, 1024):
             sb.sparbit_tune("hybrid_max_items", limit)
@@ -496,6 +602,7 @@ def test_auto_merges_leading_steps_into_one_dataflow_launch(torch):
                 assert np.array_equal(got, want), (limit, algo, p, B, in_place)
     finally:
         sb.sparbit_tune("hybrid_max_items", 512)
+        sb.sparbit_tune("tree_auto", 1)
 
 
 def test_maximum_rank_count(torch):
@@ -508,10 +615,13 @@ def test_maximum_rank_count(torch):
     got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_PER_STEP)
     assert np.array_equal(got, want)
     sb.sparbit_finalize()  # drop the 134 MB table
+    got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE)  # needs no table
+    assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("mode", ["per_step", "tree"])
 @pytest.mark.parametrize("extra,in_place", [(4112, False), (4112, True), (4, False)])
-def test_blocks_larger_than_4_gib(torch, extra, in_place):
+def test_blocks_larger_than_4_gib(torch, extra, in_place, mode):
     """Offsets inside one block beyond 32 bits: p = 2 with blocks of 4 GiB + a ragged tail
     (16-byte path, and a size that is only a multiple of 4: the realigning kernel).  The expected
     state is the oracle's, taken from its run on rank tags."""
@@ -525,7 +635,17 @@ def test_blocks_larger_than_4_gib(torch, extra, in_place):
     if in_place:
         for r in range(p):
             d_recv[r, r] = d_send[r]
-    sb.sparbit_allgather_mode(None if in_place else d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_PER_STEP)
+    if mode == "tree" and extra % 16:
+        # 2^30 four-byte elements per block are more pieces than one grid holds: the tree form says so
+        with pytest.raises(sb.SparbitError) as e:
+            sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode])
+        assert e.value.code == -3
+        torch.cuda.synchronize()
+        assert bool((d_recv[0, 0, :4096] == POISON).all())
+        del d_send, d_recv
+        torch.cuda.empty_cache()
+        return
+    sb.sparbit_allgather_mode(None if in_place else d_send, d_recv, p, B, sb.SPARBIT, MODES[mode])
     torch.cuda.synchronize()
     for r in range(p):
         for k in range(p):
@@ -568,8 +688,8 @@ def test_blocks_with_more_tiles_than_the_grid_holds(torch, shift):
 
 
 def test_randomized_cases(torch):
-    """400 seeded random (schedule, p, block size, mode, in-place, misalignment, AUTO limits) cases against the
-    oracle."""
+    """400 seeded random (schedule, p, block size, mode, in-place, misalignment, AUTO limits, tree-kernel
+    settings) cases against the oracle."""
     rng = np.random.default_rng(20210908)
     algos = [sb.SPARBIT, sb.SPARBIT, sb.SPARBIT, sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT]
     modes = ["per_step", "persistent", "dataflow", "auto"]
@@ -585,6 +705,12 @@ def test_randomized_cases(torch):
         if p * p * B > (64 << 20):
             continue
         mode = modes[rng.integers(len(modes))]
+        if algo == sb.SPARBIT and rng.integers(0, 3) == 0:
+            mode = "tree"
+            sb.sparbit_tune("tree_run_log2", int(rng.integers(0, 8)))
+            sb.sparbit_tune("tree_small_bytes", [0, 64 << 20][rng.integers(2)])
+            sb.sparbit_tune("tree_unroll", [1, 2, 4][rng.integers(3)])
+            sb.sparbit_tune("tree_store", int(rng.integers(0, 3)))
         in_place = bool(rng.integers(0, 4) == 0) and algo != sb.BRUCK
         misalign = [0, 0, 0, 1, 4, 8, 16][rng.integers(7)]
         sb.sparbit_tune("hybrid_max_items", [0, 64, 1024, 1024][rng.integers(4)])
@@ -597,6 +723,10 @@ def test_randomized_cases(torch):
         finally:
             sb.sparbit_tune("hybrid_max_items", 512)
             sb.sparbit_tune("dataflow_max_items", 256)
+            sb.sparbit_tune("tree_run_log2", 5)
+            sb.sparbit_tune("tree_small_bytes", 64 << 20)
+            sb.sparbit_tune("tree_unroll", 1)
+            sb.sparbit_tune("tree_store", 0)
         assert np.array_equal(got, want), (algo, p, B, mode, in_place, misalign)
         done += 1
 

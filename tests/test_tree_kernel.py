@@ -1,0 +1,124 @@
+"""GPU parity of the tree form (SPARBIT_MODE_TREE) beyond what the mode-parametrised tests of
+test_gpu_parity.py cover: every traversal order, piece size and store form of the kernel, the refusals, and
+recording into a HIP graph.  Bit-exact against the CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2109_08751_amd as sb
+from paper_2109_08751_amd import workloads
+
+from test_gpu_parity import POISON, announce, gpu_buffers, gpu_result, oracle_result
+
+pytestmark = pytest.mark.gpu
+
+DEFAULTS = {"tree_run_log2": 5, "tree_small_bytes": 64 << 20, "tree_unroll": 1, "tree_store": 0, "tree_load_nt": 0}
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    assert t.cuda.is_available()
+    return t
+
+
+@pytest.fixture(autouse=True)
+def default_knobs():
+    yield
+    for k, v in DEFAULTS.items():
+        sb.sparbit_tune(k, v)
+
+
+@pytest.mark.parametrize("run_log2", [0, 1, 2, 3, 4, 5, 7, 12])
+def test_every_traversal_order(torch, run_log2):
+    """Runs of 1, 2, 4, ... relative ranks up to the whole tree (= step order), for rank counts around every
+    power of two and the paper's examples (5, 21), with ragged pieces."""
+    sb.sparbit_tune("tree_small_bytes", 0)  # the run length under test applies to every size
+    sb.sparbit_tune("tree_run_log2", run_log2)
+    for p in (1, 2, 3, 5, 6, 7, 8, 9, 15, 16, 17, 21, 31, 32, 33, 63, 64, 65, 96, 100, 127, 129, 257):
+        for B in (16, 1040, 4096 + 16) if p <= 65 else (1040,):
+            announce("tree order", run_log2, p, B)
+            send = workloads.make_send_raw(p, B, seed=p * 7 + run_log2)
+            want = oracle_result(sb.SPARBIT, p, B, send)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE)
+            assert np.array_equal(got, want), (run_log2, p, B)
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4])
+@pytest.mark.parametrize("store", [0, 1, 2])
+def test_piece_sizes_and_store_forms(torch, unroll, store):
+    sb.sparbit_tune("tree_unroll", unroll)
+    sb.sparbit_tune("tree_store", store)
+    sb.sparbit_tune("tree_load_nt", store & 1)
+    for small in (0, 64 << 20):
+        sb.sparbit_tune("tree_small_bytes", small)
+        for p, B, in_place in ((6, 1024, False), (21, 5008, False), (33, 2048 + 1024 * unroll + 16, True),
+                               (96, 4096, False), (64, 65536, False), (257, 48, True), (13, 1 << 18, False)):
+            announce("tree pieces", unroll, store, small, p, B, in_place)
+            send = workloads.make_send_raw(p, B, seed=B % 1000 + unroll)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place)
+            assert np.array_equal(got, want), (unroll, store, p, B, in_place)
+
+
+def test_narrow_accesses(torch):
+    """Blocks or base addresses off the 16-byte grid: the same kernel with 4- and 1-byte elements."""
+    for p, B, mis in ((5, 20, 0), (9, 4100, 4), (6, 1023, 0), (33, 100, 1), (17, 70001, 3), (64, 4096, 8)):
+        for in_place in (False, True):
+            announce("tree narrow", p, B, mis, in_place)
+            send = workloads.make_send_raw(p, B, seed=B)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place, misalign=mis)
+            assert np.array_equal(got, want), (p, B, mis, in_place)
+
+
+def test_refusals(torch):
+    """The tree form is Sparbit's own structure: the other schedules, and step ranges, are refused."""
+    d = torch.full((4096,), POISON, dtype=torch.uint8, device="cuda:0")
+    for algo in (sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT):
+        with pytest.raises(sb.SparbitError) as e:
+            sb.sparbit_allgather_mode(d[:64], d[1024:], 4, 16, algo, sb.MODE_TREE)
+        assert e.value.code == -3
+    torch.cuda.synchronize()
+    assert bool((d == POISON).all())
+
+
+def test_capture_records_the_tree_launch_and_needs_no_tables(torch):
+    """The tree kernel has no table, flag or state, so an AUTO call can be recorded into a HIP graph even when
+    the library has never seen its (schedule, p); every replay must reproduce the oracle's result, with eager
+    work and synchronisation in between."""
+    w = workloads.WORKLOADS["cfg3"]
+    p, B = w.p, w.block_bytes
+    send = workloads.make_send(w)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    sb.sparbit_finalize()  # no cached tables at all
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            sb.sparbit_allgather(d_send, d_recv, p, B, torch.cuda.current_stream())
+    for rep in range(3):
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
+
+
+def test_many_streams_at_once(torch):
+    """Nothing in the tree form waits, so any number of calls may run side by side."""
+    cases = [(96, 4096), (64, 16384), (125, 512), (32, 65536), (12, 1024), (257, 1040)]
+    streams = [torch.cuda.Stream() for _ in cases]
+    jobs = []
+    for i, (p, B) in enumerate(cases):
+        send = workloads.make_send_raw(p, B, seed=90 + i)
+        want = torch.from_numpy(oracle_result(sb.SPARBIT, p, B, send)).to("cuda:0")
+        jobs.append((p, B, *gpu_buffers(torch, p, B, send), want))
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for st, (p, B, d_send, d_recv, _, _) in zip(streams, jobs):
+            sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, sb.MODE_TREE, st)
+    torch.cuda.synchronize()
+    for p, B, _, d_recv, _, want in jobs:
+        assert torch.equal(d_recv.view(p, p, B), want), (p, B)
