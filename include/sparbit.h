@@ -72,8 +72,10 @@ extern "C" {
                                         it wrote is incomplete.  Reported once, by the next call on that stream, which
                                         enqueues nothing */
 
+#define SPARBIT_ERR_TOO_LARGE (-7)   /* sparbit_allgather_static: p beyond SPARBIT_STATIC_MAX_P */
 
 #define SPARBIT_MAX_P 4096 /* the tables hold p * (p - 1) entries of 8 bytes */
+#define SPARBIT_STATIC_MAX_P 512 /* most ranks sparbit_allgather_static accepts: its fixed 2 MiB table holds p * p entries */
 
 /* ---- schedules (Section II-A and Section III of the paper) --------------- */
 #define SPARBIT_ALGO_SPARBIT 0            /* Algorithm 1: distance halves, data doubles */
@@ -143,6 +145,27 @@ int sparbit_allgather_mode(const void *sendbufs, void *recvbufs, int p, size_t b
  */
 int sparbit_allgather_steps(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
                             int algo, int first_step, int last_step, void *stream);
+
+/*
+ * For callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): sparbit_allgather_steps over the
+ * whole range (-1 .. num_steps - 1) of the Sparbit schedule -- own-block
+ * placement and one launch per step -- with the copy table in a fixed 2 MiB
+ * array inside the library's device image instead of allocated memory.  The
+ * call allocates and frees nothing, on the device or through any library, and
+ * caches nothing: a small kernel at its head rebuilds the table on the device.
+ *   p > SPARBIT_STATIC_MAX_P returns SPARBIT_ERR_TOO_LARGE; every block_bytes
+ *   and alignment the other entry points take is accepted.
+ *   Each GPU has ONE such array, shared by every call on it and kept until the
+ *   process ends: calls to this entry point that overlap in time on one GPU
+ *   (different streams, or replays of graphs that recorded it) race on the
+ *   table and give wrong results; calls in stream order are fine.
+ *   The first call on a device looks up the array's address and is best made
+ *   outside a capture.
+ * Arguments and result as sparbit_allgather.
+ */
+int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t block_bytes,
+                             void *stream);
 
 /*
  * MPI_Allgatherv over the same schedules -- the extension to blocks of

@@ -10,7 +10,7 @@ _BINDING_NAMES = {
     "SPARBIT", "RING", "RECURSIVE_DOUBLING", "BRUCK", "DIRECT",
     "MODE_AUTO", "MODE_PER_STEP", "MODE_PERSISTENT", "MODE_DATAFLOW", "MODE_TREE",
     "SparbitError", "Plan", "lib", "lib_path",
-    "sparbit_allgather", "sparbit_last_launch_info", "sparbit_allgather_algo",
+    "sparbit_allgather", "sparbit_allgather_static", "sparbit_last_launch_info", "sparbit_allgather_algo",
     "sparbit_allgather_steps",
     "sparbit_allgather_mode", "sparbit_allgatherv", "sparbit_finalize", "sparbit_strerror",
     "sparbit_tune", "sparbit_barrier_timeouts", "ALGOS",

@@ -64,6 +64,7 @@ def _load() -> ctypes.CDLL:
     L = ctypes.CDLL(_build.LIB_PATH)
     vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
     L.sparbit_allgather.argtypes = [vp, vp, ci, sz, vp]
+    L.sparbit_allgather_static.argtypes = [vp, vp, ci, sz, vp]
     L.sparbit_last_launch_info.argtypes = [ctypes.c_char_p, sz, ctypes.POINTER(ci)]
     L.sparbit_allgather_algo.argtypes = [vp, vp, ci, sz, ci, vp]
     L.sparbit_allgather_mode.argtypes = [vp, vp, ci, sz, ci, ci, vp]
@@ -81,7 +82,7 @@ def _load() -> ctypes.CDLL:
     L.sparbit_last_hip_error.argtypes = []
     L.sparbit_tune.argtypes = [ctypes.c_char_p, ctypes.c_longlong]
     L.sparbit_barrier_timeouts.argtypes = [vp, ctypes.POINTER(ctypes.c_uint64)]
-    for name in ("sparbit_allgather", "sparbit_last_launch_info", "sparbit_allgather_algo", "sparbit_allgather_mode",
+    for name in ("sparbit_allgather", "sparbit_allgather_static", "sparbit_last_launch_info", "sparbit_allgather_algo", "sparbit_allgather_mode",
                  "sparbit_allgather_steps", "sparbit_allgatherv", "sparbit_plan_create", "sparbit_plan_num_steps",
                  "sparbit_plan_step", "sparbit_last_hip_error", "sparbit_tune",
                  "sparbit_barrier_timeouts"):
@@ -126,6 +127,11 @@ def _check(rc: int, where: str) -> None:
 def sparbit_allgather(sendbufs, recvbufs, p: int, block_bytes: int, stream=None) -> None:
     _check(lib.sparbit_allgather(_ptr(sendbufs), _ptr(recvbufs), p, block_bytes, _stream(stream)),
            "sparbit_allgather")
+
+
+def sparbit_allgather_static(sendbufs, recvbufs, p: int, block_bytes: int, stream=None) -> None:
+    _check(lib.sparbit_allgather_static(_ptr(sendbufs), _ptr(recvbufs), p, block_bytes, _stream(stream)),
+           "sparbit_allgather_static")
 
 
 def sparbit_last_launch_info() -> tuple:

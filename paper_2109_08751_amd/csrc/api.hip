@@ -18,6 +18,12 @@
 #include "kernels.hip.hpp"
 #include "plan.hpp"
 
+// Table memory of sparbit_allgather_static, the entry point that allocates nothing: room for the p own-block
+// copies and the p (p - 1) forwarding copies of a Sparbit call with p <= SPARBIT_STATIC_MAX_P.  Every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.  In host code the
+// name below is only a handle for hipGetSymbolAddress; the address it yields (per device) is what kernels get.
+static __device__ __align__(256) unsigned char scratch[size_t(SPARBIT_STATIC_MAX_P) * SPARBIT_STATIC_MAX_P * sizeof(sparbit::Copy)];
+
 namespace sparbit {
 namespace {
 
@@ -182,6 +188,7 @@ struct DeviceState {
     std::map<std::pair<int, int>, std::unique_ptr<DevicePlan>> plans;  // (algo, p)
     void* work = nullptr;  // Bruck's rotated working buffer
     size_t work_bytes = 0;
+    Copy* static_tables = nullptr;  // this device's address of `scratch` (sparbit_allgather_static)
 };
 
 std::mutex g_mutex;
@@ -1201,6 +1208,64 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     return SPARBIT_OK;
 }
 
+// ---- the entry point that allocates nothing -----------------------------------------------------------------
+// Per-step form with the copy table in the file-scope device array instead of library-allocated memory.  The
+// table is rebuilt on the device, from the stripe closed form, by a small kernel at the head of every call (the
+// array keeps the last call's contents and every call on a GPU shares it), then the own-block placement and one
+// launch per step read it exactly as they read the cached tables of the other entry points.
+int run_static(const void* sendbufs, void* recvbufs, int p, size_t B, void* stream_v)
+{
+    tl_launch_info = LaunchInfo();
+    if (p < 1 || !recvbufs) return SPARBIT_ERR_ARG;
+    if (p > SPARBIT_STATIC_MAX_P) return SPARBIT_ERR_TOO_LARGE;
+    const size_t recv_bytes = size_t(p) * size_t(p) * B;  // p <= 512: no overflow below 2^45-byte blocks
+    if (B > (size_t(1) << 45)) return SPARBIT_ERR_ARG;
+    const bool in_place = sendbufs == nullptr;
+    if (!in_place && ranges_overlap(sendbufs, size_t(p) * B, recvbufs, recv_bytes)) return SPARBIT_ERR_ALIAS;
+    if (B == 0) return SPARBIT_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+
+    Copy* tables = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState* ds = nullptr;
+        const int rc = get_device_state(&ds);
+        if (rc != SPARBIT_OK) return rc;
+        if (!ds->static_tables) {  // once per device, with that device current
+            void* ptr = nullptr;
+            SB_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            ds->static_tables = static_cast<Copy*>(ptr);
+        }
+        tables = ds->static_tables;
+    }
+
+    StaticSteps st;
+    std::memset(&st, 0, sizeof st);
+    const int L = ceil_log2(p);
+    st.nsteps = uint32_t(L);
+    st.first[0] = uint32_t(p);  // entries 0 .. p - 1: own-block placement
+    for (int s = 0; s < L; ++s) {
+        const uint32_t d = 1u << (L - 1 - s);
+        const uint32_t q = (uint32_t(p) + d - 1) / d;  // comb size after this step
+        st.d[s] = d;
+        st.n[s] = q / 2;
+        st.first[s + 1] = st.first[s] + uint32_t(p) * st.n[s];
+    }
+    const uint32_t total = st.first[L];  // p + p (p - 1) = p^2
+    hipLaunchKernelGGL(static_tables_kernel, dim3((total + WG - 1) / WG), dim3(WG), 0, stream, tables, uint32_t(p), st);
+    SB_HIP(hipGetLastError());
+
+    const uint8_t* send = static_cast<const uint8_t*>(sendbufs);
+    uint8_t* recv = static_cast<uint8_t*>(recvbufs);
+    const int width = access_width(sendbufs, recvbufs, nullptr, B);
+    int rc = SPARBIT_OK;
+    if (!in_place && (rc = launch_phase(send, recv, tables, uint32_t(p), B, width, stream)) != SPARBIT_OK) return rc;
+    for (int s = 0; s < L; ++s)
+        if ((rc = launch_phase(recv, recv, tables + st.first[s], uint32_t(p) * st.n[s], B, width, stream)) != SPARBIT_OK)
+            return rc;
+    return SPARBIT_OK;
+}
+
 }  // namespace
 }  // namespace sparbit
 
@@ -1243,6 +1308,11 @@ int sparbit_allgather_steps(const void* sendbufs, void* recvbufs, int p, size_t 
     });
 }
 
+int sparbit_allgather_static(const void* sendbufs, void* recvbufs, int p, size_t block_bytes, void* stream)
+{
+    return sparbit::no_throw([&] { return sparbit::run_static(sendbufs, recvbufs, p, block_bytes, stream); });
+}
+
 void sparbit_finalize(void)
 {
     std::lock_guard<std::mutex> lock(sparbit::g_mutex);
@@ -1278,6 +1348,7 @@ const char* sparbit_strerror(int code)
     case SPARBIT_ERR_UNSUPPORTED: return "schedule does not support this call";
     case SPARBIT_ERR_HIP: return "HIP runtime error";
     case SPARBIT_ERR_NOMEM: return "out of host memory";
+    case SPARBIT_ERR_TOO_LARGE: return "beyond the fixed capacity of the entry point that allocates nothing";
     case SPARBIT_ERR_TIMEOUT: return "an earlier self-waiting launch on this stream gave up a bounded wait; its results are incomplete";
     default: return "unknown error";
     }

@@ -90,6 +90,39 @@ __global__ __launch_bounds__(T) void copy_tiles_kernel(const uint8_t* __restrict
 }
 
 // ---------------------------------------------------------------------------
+// Copy table of a Sparbit call, written on the device from the stripe closed
+// form (the host passes, per step, the distance d and the blocks per rank n):
+// entries 0 .. p-1 place the own blocks, then step s holds, for every rank r and
+// j < n, the copy of slot (r - 2 j d) mod p from rank r to rank (r + d) mod p.
+// Same layout as the tables the host builds for the other entry points.
+// ---------------------------------------------------------------------------
+struct StaticSteps {
+    uint32_t nsteps;
+    uint32_t d[12];
+    uint32_t n[12];
+    uint32_t first[13];  // first[s]: table index of step s; first[nsteps]: one past the end
+};
+
+__global__ __launch_bounds__(WG) void static_tables_kernel(Copy* __restrict__ out, uint32_t p, const StaticSteps st)
+{
+    const uint32_t t = blockIdx.x * WG + threadIdx.x;
+    if (t >= st.first[st.nsteps]) return;
+    if (t < p) {
+        out[t] = Copy{t, t * p + t};
+        return;
+    }
+    uint32_t s = 0;
+    while (t >= st.first[s + 1]) ++s;  // ends: t < first[nsteps]
+    const uint32_t e = t - st.first[s];
+    const uint32_t r = e / st.n[s], j = e - r * st.n[s];
+    const uint32_t back = (2u * j * st.d[s]) % p;
+    const uint32_t slot = r >= back ? r - back : r + p - back;
+    uint32_t to = r + st.d[s];
+    if (to >= p) to -= p;
+    out[t] = Copy{r * p + slot, to * p + slot};
+}
+
+// ---------------------------------------------------------------------------
 // Tree form of Sparbit (Section III-B: p binomial trees, the tree of block b
 // shifted by b, all advancing together).  The trees never touch each other's
 // data -- tree b only reads and writes slot b of the receive buffers -- and
