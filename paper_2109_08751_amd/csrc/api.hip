@@ -112,12 +112,12 @@ std::atomic<long long> g_line_align_min_bytes{64ll << 10};    // 16-byte-aligned
 std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idle workgroups one launch per step may cost before size classes pay
 std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
-std::atomic<long long> g_tree_run_log2{5};                    // tree kernel: relative ranks are walked in runs of 2^this
+std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
 std::atomic<long long> g_tree_small_bytes{64ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
 std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
-std::atomic<long long> g_tree_store{0};                       // its stores: 0 plain, 1 non-temporal hint, 2 write-through
-std::atomic<long long> g_tree_load_nt{0};                     // its loads carry the non-temporal hint
-std::atomic<long long> g_tree_lds_bytes{0};                   // LDS each of its wavefronts reserves (unused: caps the wavefronts per CU)              // blocks at least this long, not 16-byte aligned: realigning kernel
+std::atomic<long long> g_tree_store{2};                       // its stores: 0 plain, 2 write-through, 3 by destination
+std::atomic<long long> g_tree_prefetch{1};                    // it loads the next run's first rank ahead
+std::atomic<long long> g_tree_lds_bytes{-1};                  // LDS each of its wavefronts reserves (unused: caps the wavefronts per CU); -1 = by size              // blocks at least this long, not 16-byte aligned: realigning kernel
 
 struct DevicePlan {
     Plan host;
@@ -611,29 +611,35 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
     return SPARBIT_OK;
 }
 
-// The tree kernel: one wavefront per (tree, piece of 64 * U vectors).  False in *eligible when the piece count does
-// not fit a grid (blocks of several GiB): the caller falls back to per-step launches.
-template <typename V, int U, int NB>
-int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool load_nt, hipStream_t stream)
+// The tree kernel: one wavefront per (tree, piece of 64 * U vectors).
+template <typename V, int U, int NB, bool VAR>
+int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream)
 {
-    note_launch(uint64_t(a.p) * a.p * a.block_bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s>", type_label<V>(), U, NB,
-                sizeof(V) == 16 ? store_kind : 0, bool_label(sizeof(V) == 16 && load_nt));
-    const uint32_t lds = uint32_t(g_tree_lds_bytes.load());
+    if (sizeof(V) != 16) store_kind = 0;
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR));
+#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR>), grid, dim3(64), lds, stream, a)
     if constexpr (sizeof(V) == 16) {
-        if (store_kind == 2 && load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 2, true>), grid, dim3(64), lds, stream, a);
-        else if (store_kind == 2) hipLaunchKernelGGL((tree_kernel<V, U, NB, 2, false>), grid, dim3(64), lds, stream, a);
-        else if (store_kind == 1 && load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, true>), grid, dim3(64), lds, stream, a);
-        else if (store_kind == 1) hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, false>), grid, dim3(64), lds, stream, a);
-        else if (load_nt) hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, true>), grid, dim3(64), lds, stream, a);
-        else hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false>), grid, dim3(64), lds, stream, a);
+        if (store_kind == 3 && prefetch) SB_TREE(3, true);
+        else if (store_kind == 3) SB_TREE(3, false);
+        else if (store_kind == 2 && prefetch) SB_TREE(2, true);
+        else if (store_kind == 2) SB_TREE(2, false);
+        else if (prefetch) SB_TREE(0, true);
+        else SB_TREE(0, false);
     } else {
-        hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false>), grid, dim3(64), lds, stream, a);
+        if (prefetch) SB_TREE(0, true);
+        else SB_TREE(0, false);
     }
+#undef SB_TREE
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
 
-int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, int width, hipStream_t stream, bool* eligible)
+// Equal blocks of B bytes (counts == nullptr; slot k at k * B of a row) or blocks of different sizes (device arrays
+// counts / displs; `B` is then the longest block).  Rows are row_bytes apart.  *eligible stays false when the
+// piece count does not fit a grid (blocks of several GiB): the caller falls back to per-step launches.
+int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t row_bytes, const uint64_t* counts,
+                const uint64_t* displs, uint64_t total_bytes, int width, hipStream_t stream, bool* eligible)
 {
     *eligible = false;
     if (p == 1 && !sendbufs) {  // in place with one rank: nothing moves
@@ -654,23 +660,44 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, int width
     a.recv = static_cast<uint8_t*>(recvbufs);
     a.block_bytes = B;
     a.vpb = vpb;
+    a.row_bytes = row_bytes;
+    a.counts = counts;
+    a.displs = displs;
     a.p = uint32_t(p);
     a.top = p > 1 ? 1u << (ceil_log2(p) - 1) : 0u;
-    // Jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips.
-    const bool small = uint64_t(p) * uint64_t(p) * B <= uint64_t(g_tree_small_bytes.load());
-    a.lg_k = small ? uint32_t(ceil_log2(p)) : uint32_t(g_tree_run_log2.load());
+    // How the tree is walked (all measured on MI355X, see the kernel's comment for the terms):
+    //  - jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips;
+    //  - otherwise short runs, which keep a slot's read close to its write; the fewer wavefronts the grid has, the
+    //    longer the runs, for more loads in flight per wavefront (p = 256, 4 KiB: 57 us with runs of 16, 67 us with
+    //    runs of 4; p = 64, 64 KiB: 52 us against 48 us);
+    //  - when there are more wavefronts than the GPU holds at 16 per compute unit, that many are enough, and fewer
+    //    resident wavefronts mean fewer bytes between a write and its read-back (p = 128, 1 MiB: 3.20 ms against
+    //    3.46 ms): each wavefront then reserves a sixteenth of the unit's LDS.
+    const uint64_t waves = pieces * uint64_t(p);
+    const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
+    const long long run_knob = g_tree_run_log2.load();
+    a.lg_k = run_knob >= 0 ? uint32_t(run_knob) : small ? uint32_t(ceil_log2(p)) : waves < 2048 ? 4u : waves < 4096 ? 3u : 2u;
     a.lg_g = lg_g;
+    const long long lds_knob = g_tree_lds_bytes.load();
+    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : waves >= 8192 ? 10240u : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
     const int st = int(g_tree_store.load());
-    const bool ldnt = g_tree_load_nt.load() != 0;
+    const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
-    if (width == 16) {
-        if (U == 4) return launch_tree_vu<u32x4, 4, 4>(a, grid, st, ldnt, stream);
-        if (U == 2) return launch_tree_vu<u32x4, 2, 8>(a, grid, st, ldnt, stream);
-        return launch_tree_vu<u32x4, 1, 8>(a, grid, st, ldnt, stream);
+    if (counts) {
+        if (width == 16) {
+            if (U == 2) return launch_tree_vu<u32x4, 2, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
+            return launch_tree_vu<u32x4, 1, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
+        }
+        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
+        return launch_tree_vu<uint8_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
     }
-    if (width == 4) return launch_tree_vu<uint32_t, 1, 8>(a, grid, 0, false, stream);
-    return launch_tree_vu<uint8_t, 1, 8>(a, grid, 0, false, stream);
+    if (width == 16) {
+        if (U == 2) return launch_tree_vu<u32x4, 2, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
+        return launch_tree_vu<u32x4, 1, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
+    }
+    if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
+    return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
 }
 
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb);
@@ -916,6 +943,29 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
         const int erc = report_expired_waits(stream);
         if (erc != SPARBIT_OK) return erc;
     }
+    const int width = (bits & 15) == 0 ? 16 : (bits & 3) == 0 ? 4 : 1;
+    size_t longest = 0;
+    uint64_t total_bytes = 0;
+    for (int k = 0; k < p; ++k) {
+        if (counts[k] > longest) longest = counts[k];
+        total_bytes += counts[k];
+    }
+    total_bytes *= uint64_t(p);
+    // Sparbit as the tree kernel, as for equal blocks: when every block is on the 16-byte grid, or all are too
+    // short for the realigning kernel.
+    const bool tree = algo == SPARBIT_ALGO_SPARBIT && g_tree_auto.load() != 0 &&
+                      (width == 16 || longest < size_t(g_realign_min_bytes.load()));
+    // Equal blocks at their packed positions in rows that are longer than p blocks (padded rows): the equal-block
+    // tree kernel takes the row length as it is, and needs no table at all.
+    bool padded = tree && counts[0] != 0 && row_bytes > size_t(p) * counts[0];
+    for (int k = 0; k < p && padded; ++k) padded = counts[k] == counts[0] && displs[k] == size_t(k) * counts[0];
+    if (padded) {
+        tl_launch_info = LaunchInfo();
+        bool eligible = false;
+        const int trc = launch_tree(sendbufs, recvbufs, p, counts[0], row_bytes, nullptr, nullptr, total_bytes, width, stream,
+                                    &eligible);
+        if (trc != SPARBIT_OK || eligible) return trc;
+    }
 
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState* ds = nullptr;
@@ -926,8 +976,13 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     VarPlan* vp = nullptr;
     if ((rc = get_var_plan(ds, dp, algo, p, counts, displs, row_bytes, !capturing, &vp)) != SPARBIT_OK) return rc;
     const uint8_t* base[3] = {static_cast<const uint8_t*>(sendbufs), static_cast<const uint8_t*>(recvbufs), nullptr};
-    const int width = (bits & 15) == 0 ? 16 : (bits & 3) == 0 ? 4 : 1;
     const bool on_lines = (bits & 127) == 0;  // every block starts and ends on a 128-byte line
+    if (tree) {  // sizes and offsets come from the geometry's device copy
+        bool eligible = false;
+        const int trc = launch_tree(sendbufs, recvbufs, p, longest, row_bytes, vp->d_geometry, vp->d_geometry + p, total_bytes,
+                                    width, stream, &eligible);
+        if (trc != SPARBIT_OK || eligible) return trc;
+    }
 
     // As for equal blocks: a call of a few work items goes out as one dataflow launch, and in a larger one the
     // leading small steps share one.  A copy of an empty block still counts as an item (it exits at once).
@@ -1048,7 +1103,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
             (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0 &&
              (w == 16 ? on_lines : B < size_t(g_realign_min_bytes.load())))) {
             bool eligible = false;
-            const int trc = launch_tree(sendbufs, recvbufs, p, B, w, stream, &eligible);
+            const int trc = launch_tree(sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, w, stream, &eligible);
             if (trc != SPARBIT_OK || eligible) return trc;
             if (mode == SPARBIT_MODE_TREE) return SPARBIT_ERR_UNSUPPORTED;  // blocks of several GiB
         }
@@ -1454,21 +1509,21 @@ int sparbit_tune(const char* key, long long value)
     } else if (!std::strcmp(key, "tree_auto")) {
         g_tree_auto = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_run_log2")) {
-        if (value < 0 || value > 12) return SPARBIT_ERR_ARG;
+        if (value < -1 || value > 12) return SPARBIT_ERR_ARG;
         g_tree_run_log2 = value;
     } else if (!std::strcmp(key, "tree_small_bytes")) {
         if (value < 0) return SPARBIT_ERR_ARG;
         g_tree_small_bytes = value;
     } else if (!std::strcmp(key, "tree_unroll")) {
-        if (value != 1 && value != 2 && value != 4) return SPARBIT_ERR_ARG;
+        if (value != 1 && value != 2) return SPARBIT_ERR_ARG;
         g_tree_unroll = value;
     } else if (!std::strcmp(key, "tree_store")) {
-        if (value < 0 || value > 2) return SPARBIT_ERR_ARG;
+        if (value != 0 && value != 2 && value != 3) return SPARBIT_ERR_ARG;
         g_tree_store = value;
-    } else if (!std::strcmp(key, "tree_load_nt")) {
-        g_tree_load_nt = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_prefetch")) {
+        g_tree_prefetch = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_lds_bytes")) {
-        if (value < 0 || value > 65536) return SPARBIT_ERR_ARG;
+        if (value < -1 || value > 65536) return SPARBIT_ERR_ARG;
         g_tree_lds_bytes = value;
     } else if (!std::strcmp(key, "spin_limit_ms")) {
         if (value < 0 || value > 60000) return SPARBIT_ERR_ARG;

@@ -146,7 +146,8 @@ __global__ __launch_bounds__(WG) void static_tables_kernel(Copy* __restrict__ ou
 // parent of rho is rho minus its lowest set bit, so increasing rho is one.  The
 // kernel walks runs of K = 2^lg_k consecutive relative ranks; inside a run it
 // goes level by level (the run's first rank, then +K/2, then +K/4 and +3K/4,
-// ...), loading a batch of forwarders at once.  Small K keeps the distance
+// ...), loading a batch of forwarders at once, and the next run's first rank is
+// loaded ahead, while the current run is served.  Small K keeps the distance
 // between the write and the read of a slot short (the read hits the cache that
 // holds the write); K >= p is the step order of Algorithm 1 (all forwards of a
 // step before the next step), which has the fewest dependent round trips.
@@ -157,82 +158,146 @@ __global__ __launch_bounds__(WG) void static_tables_kernel(Copy* __restrict__ ou
 struct TreeArgs {
     const uint8_t* send;  // nullptr: in place, slot r of rank r already holds rank r's block
     uint8_t* recv;
-    uint64_t block_bytes;
-    uint64_t vpb;   // vectors per block
+    uint64_t block_bytes;  // equal blocks: slot k at byte k * block_bytes of a row
+    uint64_t vpb;          // equal blocks: vectors per block
+    uint64_t row_bytes;    // distance between two ranks' receive buffers
+    // Blocks of different sizes (Allgatherv): bytes of slot k and its offset in a row (and of rank k's block in the
+    // send buffer); nullptr for equal blocks.
+    const uint64_t* counts;
+    const uint64_t* displs;
     uint32_t p;
     uint32_t top;   // distance of the first step: 2^(ceil(log2 p) - 1), 0 for p = 1
     uint32_t lg_k;
     uint32_t lg_g;
 };
 
-template <typename V, int ST>
-__device__ __forceinline__ void tree_store(V* p, V v)
+// Store forms of the tree kernel (ST), for 16-byte vectors.  0: plain, the line is allocated in the XCD's L2 and
+// written back later.  2: write-through at system scope (sc0 sc1), the line goes straight to the memory side.
+// 3: by destination -- plain for a rank that forwards and is read again soon, write-through for the others.
+// The 16-byte accesses are raw buffer loads and stores: the base of a slot's piece is wave-uniform and sits in
+// scalar registers (no per-lane 64-bit address arithmetic), the piece's length is the buffer's size, so lanes past
+// a block's ragged end are dropped by the bounds check, and the cache-policy bits are an operand of the
+// instruction the compiler knows, so it counts these stores like any others when it places its waits (stores
+// issued from inline assembly are invisible to it, and it then waits for everything before every access).
+constexpr int kBufferSc0Sc1 = 1 | 16;  // cache-policy operand: bit 0 = sc0, bit 4 = sc1
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t piece_buffer(const uint8_t* base, uint32_t bytes)
 {
-    if constexpr (ST == 2 && sizeof(V) == 16)
-        asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
-    else if constexpr (ST == 1)
-        __builtin_nontemporal_store(v, p);
-    else
-        *p = v;
+    // stride 0 (raw), `bytes` addressable, third descriptor word for untyped 32-bit accesses on gfx9-class targets
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, int(bytes), 0x00020000);
 }
 
-template <typename V, int U, int NB, int ST, bool LDNT>
+// s_waitcnt vmcnt(0): every vector-memory access issued so far has completed (loads and stores count together and
+// complete in order on this target).  The operand leaves the export and scalar/LDS counters at "no wait".
+__device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// PF: the first rank of the next run is loaded ahead, while the current run is served.
+template <typename V, int U, int NB, int ST, bool PF, bool VAR = false>
 __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
 {
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
     if (b >= a.p) return;
-    const uint64_t v0 = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U) + threadIdx.x;
     const uint32_t p = a.p;
+    uint64_t vectors = a.vpb, offset = uint64_t(b) * a.block_bytes;  // this tree's block inside a row
+    if constexpr (VAR) {
+        vectors = a.counts[b] / sizeof(V);
+        offset = a.displs[b];
+    }
+    const uint64_t piece_at = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U);  // first vector of this wavefront's piece
+    if (piece_at >= vectors) return;  // uniform: a shorter block has no such piece
+    offset += piece_at * sizeof(V);
+    const uint64_t left = vectors - piece_at;
+    const uint32_t piece_vectors = left < uint64_t(64 * U) ? uint32_t(left) : uint32_t(64 * U);
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = v0 + uint64_t(u * 64) < a.vpb;
-    // Slot b of the rank at relative rank rho.  No __restrict__ anywhere: a slot is written and later read.
-    auto slot = [&](uint32_t rho) -> V* {
+    for (int u = 0; u < U; ++u) ok[u] = threadIdx.x + uint32_t(u * 64) < piece_vectors;
+    // The piece of slot b held by the rank at relative rank rho (wave-uniform).  No __restrict__ anywhere: a slot
+    // is written and later read.
+    auto slot = [&](uint32_t rho) -> uint8_t* {
         uint32_t r = b + rho;
         if (r >= p) r -= p;
-        return reinterpret_cast<V*>(a.recv + (uint64_t(r) * p + b) * a.block_bytes) + v0;
+        return a.recv + uint64_t(r) * a.row_bytes + offset;
     };
-    auto load = [&](const V* s, V (&x)[U]) {
+    auto load = [&](const uint8_t* s, V (&x)[U]) {
+        if constexpr (sizeof(V) == 16) {
+            const __amdgpu_buffer_rsrc_t rs = piece_buffer(s, piece_vectors * 16u);
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) x[u] = ld<V, LDNT>(s + u * 64);
+            for (int u = 0; u < U; ++u)
+                x[u] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, int(threadIdx.x * 16u + u * 1024u), 0, 0));
+        } else {
+            const V* sv = reinterpret_cast<const V*>(s) + threadIdx.x;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ok[u]) x[u] = sv[u * 64];
+        }
     };
-    auto store = [&](V* d, const V (&x)[U]) {
+    auto store = [&](uint8_t* d, const V (&x)[U], bool read_again_soon) {
+        if constexpr (sizeof(V) == 16) {
+            const __amdgpu_buffer_rsrc_t rd = piece_buffer(d, piece_vectors * 16u);
+            typedef uint32_t raw4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (ok[u]) tree_store<V, ST>(d + u * 64, x[u]);
+            for (int u = 0; u < U; ++u) {
+                const int at = int(threadIdx.x * 16u + u * 1024u);
+                const raw4 v = __builtin_bit_cast(raw4, x[u]);
+                if (ST == 0 || (ST == 3 && read_again_soon))
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
+                else
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, kBufferSc0Sc1);
+            }
+        } else {
+            V* dv = reinterpret_cast<V*>(d) + threadIdx.x;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (ok[u]) dv[u * 64] = x[u];
+        }
     };
     const uint32_t K = 1u << a.lg_k;
+    // From relative rank rho to rho + d.  The destination is read again soon if it forwards (d >= 2: it is even)
+    // and belongs to this run or is the first rank of the next one.
+    auto send_to = [&](uint32_t rho, uint32_t d, const V (&x)[U]) { store(slot(rho + d), x, d >= 2 && d <= K); };
+    // A rank forwards if it is even in the tree and the next relative rank exists (its nearest destination).
+    auto forwards = [&](uint32_t rho) { return (rho & 1u) == 0 && rho + 1 < p; };
+    V xh[U];  // the block as the run's first rank holds it
+    if (a.send) {
+        load(a.send + offset, xh);
+        store(slot(0), xh, false);  // own-block placement; read again only in an in-place call
+    } else {
+        load(slot(0), xh);
+    }
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;
-        {
-            V x[U];
-            if (h == 0 && a.send) {
-                load(reinterpret_cast<const V*>(a.send + uint64_t(b) * a.block_bytes) + v0, x);
-                store(slot(0), x);  // own-block placement
-            } else if ((h & 1u) == 0 && h + 1 < p) {  // it forwards: even, and rank h + 1 exists
-                load(slot(h), x);
-            }
-            for (uint32_t d = h ? ((h & (0u - h)) >> 1) : a.top; d >= 1; d >>= 1)
-                if (d < p - h) store(slot(h + d), x);
-        }
+        if (!PF && h != 0 && forwards(h)) load(slot(h), xh);
+        for (uint32_t d = h ? ((h & (0u - h)) >> 1) : a.top; d >= 1; d >>= 1)
+            if (d < p - h) send_to(h, d, xh);
+        // The next run's first rank got the block from this run's first rank (just above) or from an earlier run,
+        // so its load can already travel while this run's other forwarders are served.
+        V xn[U];
+        const uint32_t hn = h + K;
+        if (PF && hn < p && forwards(hn)) load(slot(hn), xn);
         for (uint32_t st = K >> 1; st >= 2; st >>= 1) {  // forwarders whose lowest set bit is st
             for (uint32_t n0 = h + st; n0 < end; n0 += 2 * st * NB) {
                 V x[NB][U];
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
                     const uint32_t n = n0 + 2 * st * i;
-                    if (n < end && n + 1 < p) load(slot(n), x[i]);
+                    if (n < end && forwards(n)) load(slot(n), x[i]);
                 }
+                // One wait for the whole batch, stated here: behind the conditions above the compiler would
+                // otherwise wait before each forwarder's stores, i.e. for the previous forwarder's stores.
+                wait_for_loads();
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
                     const uint32_t n = n0 + 2 * st * i;
                     if (n < end)
                         for (uint32_t d = st >> 1; d >= 1; d >>= 1)
-                            if (d < p - n) store(slot(n + d), x[i]);
+                            if (d < p - n) send_to(n, d, x[i]);
                 }
             }
+        }
+        if constexpr (PF) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) xh[u] = xn[u];
         }
     }
 }

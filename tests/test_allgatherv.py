@@ -123,13 +123,25 @@ import contextlib
 
 
 @contextlib.contextmanager
+def without_tree_kernel():
+    """Sparbit as the other schedules go: dataflow launches for small calls and leading steps, else per step."""
+    sb.sparbit_tune("tree_auto", 0)
+    try:
+        yield
+    finally:
+        sb.sparbit_tune("tree_auto", 1)
+
+
+@contextlib.contextmanager
 def launch_per_step_only():
-    """AUTO without the dataflow launches (small calls and leading steps): one launch per step and size class."""
+    """AUTO without the tree kernel and without the dataflow launches: one launch per step and size class."""
+    sb.sparbit_tune("tree_auto", 0)
     sb.sparbit_tune("hybrid_max_items", 0)
     sb.sparbit_tune("dataflow_max_items", 0)
     try:
         yield
     finally:
+        sb.sparbit_tune("tree_auto", 1)
         sb.sparbit_tune("hybrid_max_items", 512)
         sb.sparbit_tune("dataflow_max_items", 256)
 
@@ -171,9 +183,13 @@ def test_gpu_allgatherv_matches_oracle():
                 oracle.allgatherv(oalgo, p, counts, displs, row, send, want)
                 got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
                 assert np.array_equal(got, want), (p, align, algo)
-                with launch_per_step_only():  # the same call without the dataflow launch
+                with launch_per_step_only():  # the same call without the tree and dataflow launches
                     got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
                 assert np.array_equal(got, want), (p, align, algo, "per step")
+                if algo == sb.SPARBIT:
+                    with without_tree_kernel():  # and as the other schedules go
+                        got = gpu_allgatherv(torch, algo, p, counts, displs, row, send)
+                    assert np.array_equal(got, want), (p, align, algo, "without the tree kernel")
 
 
 @pytest.mark.gpu
@@ -351,8 +367,12 @@ def test_gpu_allgatherv_randomized_geometries():
                 want[r, d:d + c] = send[d:d + c]
         # the plain all-to-all definition needs the send buffer; in place it yields the same state
         oracle.allgatherv(oalgo, p, counts, displs, row, None if (in_place and algo != sb.DIRECT) else send, want)
-        if rng.integers(3) == 0:
+        form = rng.integers(4)
+        if form == 0:
             with launch_per_step_only():
+                got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+        elif form == 1:
+            with without_tree_kernel():
                 got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
         else:
             got = gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=in_place, misalign=mis)
@@ -365,6 +385,14 @@ def test_gpu_allgatherv_capture_in_a_hip_graph():
     """A geometry that was used once outside a capture can be recorded (per-step launches only, although the same
     call issued eagerly takes the dataflow launch) and replayed; a new geometry is refused with nothing recorded."""
     import torch
+    sb.sparbit_tune("tree_auto", 0)
+    try:
+        _capture_without_the_tree_kernel(torch)
+    finally:
+        sb.sparbit_tune("tree_auto", 1)
+
+
+def _capture_without_the_tree_kernel(torch):
     p = 6
     counts, displs, row = geometry(p, seed=77, align=16, max_len=2000)
     send = payload(row, 3)
@@ -402,6 +430,14 @@ def test_gpu_allgatherv_expired_waits_are_reported_and_the_next_call_is_clean():
     are counted, the next call on the stream answers SPARBIT_ERR_TIMEOUT once, and the call after it, with the
     normal bound, is correct."""
     import torch
+    sb.sparbit_tune("tree_auto", 0)  # the tree kernel never waits
+    try:
+        _expired_waits(torch)
+    finally:
+        sb.sparbit_tune("tree_auto", 1)
+
+
+def _expired_waits(torch):
     p = 12
     counts, displs, row = geometry(p, seed=5, align=16, max_len=3000)
     send = payload(row, 8)
@@ -437,3 +473,56 @@ def test_gpu_allgatherv_expired_waits_are_reported_and_the_next_call_is_clean():
         call()
     assert sb.sparbit_barrier_timeouts(st) - before == expired
     assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want)
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_equal_blocks_in_padded_rows():
+    """Equal blocks at their packed positions in rows longer than p blocks: the equal-block tree kernel with the row
+    length as its stride (no table), for power-of-two rank counts where padding the rows is the remedy for the
+    stripe pattern meeting the address interleaving.  Also in place, and with the padding not a multiple of 16."""
+    import torch
+    for p, B, pad in ((8, 1024, 128), (64, 4096, 128), (128, 4096, 256), (16, 48, 16), (32, 1040, 4), (5, 4100, 7)):
+        for in_place in (False, True):
+            row = p * B + pad
+            counts = np.full(p, B, dtype=np.uint64)
+            displs = np.arange(p, dtype=np.uint64) * B
+            send = payload(row, p)
+            print("[case] padded rows", p, B, pad, in_place, flush=True)
+            want = np.full((p, row), POISON, dtype=np.uint8)
+            if in_place:
+                for r in range(p):
+                    want[r, r * B:(r + 1) * B] = send[r * B:(r + 1) * B]
+            oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
+            got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place)
+            assert np.array_equal(got, want), (p, B, pad, in_place)
+            if row % 16 == 0 or B < 512:  # else the blocks are off the 16-byte grid: realigning per-step kernels
+                assert "tree_kernel" in sb.sparbit_last_launch_info()[0]
+
+
+@pytest.mark.gpu
+def test_gpu_allgatherv_capture_of_the_tree_kernel():
+    """With the tree kernel a Sparbit Allgatherv call is one launch that reads the geometry's device copy; once the
+    geometry is cached the call can be recorded and replayed."""
+    import torch
+    p = 21
+    counts, displs, row = geometry(p, seed=78, align=16, max_len=5000)
+    send = payload(row, 3)
+    want = np.full((p, row), POISON, dtype=np.uint8)
+    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, send, want)
+    dev = torch.device("cuda:0")
+    d_send = torch.from_numpy(send).to(dev)
+    d_recv = torch.full((p * row,), POISON, dtype=torch.uint8, device=dev)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, st)
+        st.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            sb.sparbit_allgatherv(d_send, d_recv, p, counts, displs, row, sb.SPARBIT, torch.cuda.current_stream())
+    for rep in range(3):
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, row), want), rep

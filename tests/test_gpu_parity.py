@@ -709,8 +709,9 @@ def test_randomized_cases(torch):
             mode = "tree"
             sb.sparbit_tune("tree_run_log2", int(rng.integers(0, 8)))
             sb.sparbit_tune("tree_small_bytes", [0, 64 << 20][rng.integers(2)])
-            sb.sparbit_tune("tree_unroll", [1, 2, 4][rng.integers(3)])
-            sb.sparbit_tune("tree_store", int(rng.integers(0, 3)))
+            sb.sparbit_tune("tree_unroll", [1, 2][rng.integers(2)])
+            sb.sparbit_tune("tree_store", [0, 2, 3][rng.integers(3)])
+            sb.sparbit_tune("tree_prefetch", int(rng.integers(0, 2)))
         in_place = bool(rng.integers(0, 4) == 0) and algo != sb.BRUCK
         misalign = [0, 0, 0, 1, 4, 8, 16][rng.integers(7)]
         sb.sparbit_tune("hybrid_max_items", [0, 64, 1024, 1024][rng.integers(4)])
@@ -723,10 +724,11 @@ def test_randomized_cases(torch):
         finally:
             sb.sparbit_tune("hybrid_max_items", 512)
             sb.sparbit_tune("dataflow_max_items", 256)
-            sb.sparbit_tune("tree_run_log2", 5)
+            sb.sparbit_tune("tree_run_log2", -1)
             sb.sparbit_tune("tree_small_bytes", 64 << 20)
             sb.sparbit_tune("tree_unroll", 1)
-            sb.sparbit_tune("tree_store", 0)
+            sb.sparbit_tune("tree_store", 2)
+            sb.sparbit_tune("tree_prefetch", 1)
         assert np.array_equal(got, want), (algo, p, B, mode, in_place, misalign)
         done += 1
 

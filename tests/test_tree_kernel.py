@@ -12,7 +12,8 @@ from test_gpu_parity import POISON, announce, gpu_buffers, gpu_result, oracle_re
 
 pytestmark = pytest.mark.gpu
 
-DEFAULTS = {"tree_run_log2": 5, "tree_small_bytes": 64 << 20, "tree_unroll": 1, "tree_store": 0, "tree_load_nt": 0}
+DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 64 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
+            "tree_lds_bytes": -1}
 
 
 @pytest.fixture(scope="module")
@@ -29,12 +30,15 @@ def default_knobs():
         sb.sparbit_tune(k, v)
 
 
+@pytest.mark.parametrize("prefetch", [0, 1])
 @pytest.mark.parametrize("run_log2", [0, 1, 2, 3, 4, 5, 7, 12])
-def test_every_traversal_order(torch, run_log2):
+def test_every_traversal_order(torch, run_log2, prefetch):
     """Runs of 1, 2, 4, ... relative ranks up to the whole tree (= step order), for rank counts around every
     power of two and the paper's examples (5, 21), with ragged pieces."""
     sb.sparbit_tune("tree_small_bytes", 0)  # the run length under test applies to every size
     sb.sparbit_tune("tree_run_log2", run_log2)
+    sb.sparbit_tune("tree_prefetch", prefetch)
+    sb.sparbit_tune("tree_store", 3 if prefetch else 2)
     for p in (1, 2, 3, 5, 6, 7, 8, 9, 15, 16, 17, 21, 31, 32, 33, 63, 64, 65, 96, 100, 127, 129, 257):
         for B in (16, 1040, 4096 + 16) if p <= 65 else (1040,):
             announce("tree order", run_log2, p, B)
@@ -44,12 +48,12 @@ def test_every_traversal_order(torch, run_log2):
             assert np.array_equal(got, want), (run_log2, p, B)
 
 
-@pytest.mark.parametrize("unroll", [1, 2, 4])
-@pytest.mark.parametrize("store", [0, 1, 2])
+@pytest.mark.parametrize("unroll", [1, 2])
+@pytest.mark.parametrize("store", [0, 2, 3])
 def test_piece_sizes_and_store_forms(torch, unroll, store):
     sb.sparbit_tune("tree_unroll", unroll)
     sb.sparbit_tune("tree_store", store)
-    sb.sparbit_tune("tree_load_nt", store & 1)
+    sb.sparbit_tune("tree_lds_bytes", 10240 if store == 2 else 0)
     for small in (0, 64 << 20):
         sb.sparbit_tune("tree_small_bytes", small)
         for p, B, in_place in ((6, 1024, False), (21, 5008, False), (33, 2048 + 1024 * unroll + 16, True),
