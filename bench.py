@@ -615,11 +615,13 @@ def main():
             t = time_calls(torch, lambda: sb.sparbit_allgatherv(s_, r_, pv, counts, displs, row, sb.SPARBIT, stream),
                            stream, 3, 10)
             per[label] = {
-                "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6, "form": "per_step",
-                "model_GBps": 2 * pv * row / t["avg_ms"] / 1e6,
-                "model_frac": 2 * pv * row / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+                "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6,
                 "kernel": sb.sparbit_last_launch_info()[0],
                 "ok": bool(torch.equal(r_[pv - 1], s_))}
+            vform = form_of(per[label]["kernel"])
+            vbytes = row + pv * row if vform == "tree" else 2 * pv * row
+            per[label].update({"form": vform, "model_bytes": vbytes, "model_GBps": vbytes / t["avg_ms"] / 1e6,
+                               "model_frac": vbytes / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS})
             del s_, r_
             torch.cuda.empty_cache()
         # Equal blocks off the 16-byte grid: cfg4's shape with 4 more bytes per block

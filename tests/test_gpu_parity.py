@@ -234,11 +234,12 @@ def expected_origins(p, max_steps=-1):
     return recv
 
 
-@pytest.mark.parametrize("mode", ["auto", "per_step"])
-@pytest.mark.parametrize("cfg", ["cfg4", "cfg5"])
+@pytest.mark.parametrize("cfg,mode", [("cfg4", "auto"), ("cfg4", "per_step"), ("cfg5", "auto"), ("cfg5", "per_step"),
+                                      ("cfg5", "dataflow"), ("cfg5", "persistent")])
 def test_full_size_configs(torch, cfg, mode):
-    """16 GiB receive buffers, in the launch configuration the benchmark times (AUTO: the tree kernel) and as one
-    launch per step.
+    """16 GiB receive buffers, in the launch configuration the benchmark times (AUTO: the tree kernel), as one
+    launch per step, and, on the largest configuration, in the two self-waiting forms, which are accepted at any
+    size (dataflow: one workgroup per 16 KiB piece, over a million of them; persistent: a cooperative launch).
     Every slot is compared on the device with the block the oracle says it must
     hold (oracle run on rank tags), after the last-but-one step (unreceived
     slots still poison) and at the end; sampled slots are also copied back and
@@ -271,6 +272,7 @@ def test_full_size_configs(torch, cfg, mode):
     else:
         sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode])
     torch.cuda.synchronize()
+    assert sb.sparbit_barrier_timeouts() == 0
     origin = expected_origins(p)
     assert (origin == np.arange(p)[None, :]).all()
     for r in range(p):
