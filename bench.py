@@ -50,11 +50,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 
-# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (one run each,
-# scaled by a plain 1 GiB copy through the library).  A figure is reported only when the library launched exactly
-# the kernel the profile was taken with, on the workload it was taken on.
+# Traffic through the L2-to-fabric interface per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (one run each, scaled by a plain 1 GiB copy through the library).  A figure is reported only when the
+# library launched exactly the kernel the profile was taken with, on the workload it was taken on, with default
+# tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false>"):
+        (20492913475, "profiles/tree_kernel_cfg4_cfg5.md"),
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false>"):
+        (20332541905, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
 
@@ -239,6 +244,10 @@ def sweep(torch, sb, workloads, stream, path):
     dev = torch.device("cuda:0")
     ps = [8, 16, 32, 64, 128, 256, 5, 13, 29, 61, 125, 253]
     sizes = [1 << k for k in range(0, 21)]
+    if os.environ.get("SPARBIT_SWEEP_PS"):  # a subset, e.g. "128,256"
+        ps = [int(x) for x in os.environ["SPARBIT_SWEEP_PS"].split(",")]
+    if os.environ.get("SPARBIT_SWEEP_SIZES"):
+        sizes = [int(x) for x in os.environ["SPARBIT_SWEEP_SIZES"].split(",")]
     algos = [("sparbit", sb.SPARBIT, sb.MODE_AUTO), ("sparbit_per_step", sb.SPARBIT, sb.MODE_PER_STEP),
              ("ring", sb.RING, sb.MODE_AUTO), ("recursive_doubling", sb.RECURSIVE_DOUBLING, sb.MODE_AUTO),
              ("bruck", sb.BRUCK, sb.MODE_AUTO), ("direct", sb.DIRECT, sb.MODE_AUTO)]
@@ -279,12 +288,20 @@ def sweep(torch, sb, workloads, stream, path):
                         displs = np.arange(p, dtype=np.uint64) * B
                         s_ = torch.randint(0, 256, (row,), dtype=torch.uint8, device=dev)
                         r_ = torch.full((p, row), workloads.POISON, dtype=torch.uint8, device=dev)
-                        for label, algo in (("sparbit_padded_rows", sb.SPARBIT), ("recursive_doubling_padded_rows",
-                                                                               sb.RECURSIVE_DOUBLING)):
+                        for label, algo, tree in (("sparbit_padded_rows", sb.SPARBIT, 1),
+                                                  ("sparbit_per_step_padded_rows", sb.SPARBIT, 0),
+                                                  ("recursive_doubling_padded_rows", sb.RECURSIVE_DOUBLING, 1)):
+                            sb.sparbit_tune("tree_auto", tree)  # 0: the per-step kernels for blocks of given offsets
+                            sb.sparbit_tune("hybrid_max_items", 512 if tree else 0)
                             fn = lambda: sb.sparbit_allgatherv(s_, r_, p, counts, displs, row, algo, stream)
                             t = time_calls(torch, fn, stream, 3, 10)
+                            sb.sparbit_tune("tree_auto", 1)
+                            sb.sparbit_tune("hybrid_max_items", 512)
                             ok = bool(torch.equal(r_[p - 1, :p * B], s_[:p * B]))
                             emit(p, B, label, t, ok, row_pad=pad)
+                            with torch.cuda.stream(stream):
+                                r_.fill_(workloads.POISON)
+                            torch.cuda.synchronize()
                         del s_, r_
             print(f"sweep: p={p} done ({n} cases)", file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
@@ -356,13 +373,14 @@ def sweep_summary(path):
     padded = [(k, c) for k, c in sorted(by.items()) if any("+" in a for a in c)]
     if padded:
         out.append("\n## Power-of-two p, 4 and 16 KiB blocks: packed rows against rows padded by 128 / 256 bytes (Allgatherv)\n")
-        out.append("| p | bytes | Sparbit AUTO | Sparbit per step | Recursive Doubling | Sparbit +128 | Sparbit +256 | "
-                   "Rec. Doubling +128 | Rec. Doubling +256 |")
-        out.append("|---|---|---|---|---|---|---|---|---|")
+        out.append("| p | bytes | Sparbit AUTO | Sparbit per step | Recursive Doubling | Sparbit AUTO +128 | Sparbit AUTO +256 | "
+                   "Sparbit per step +128 | Sparbit per step +256 | Rec. Doubling +128 | Rec. Doubling +256 |")
+        out.append("|---|---|---|---|---|---|---|---|---|---|---|")
         for (p, s), c in padded:
             g = lambda a: f"{c[a]:.0f}" if a in c else ""
             out.append(f"| {p} | {s} | {g('sparbit')} | {g('sparbit_per_step')} | {g('recursive_doubling')} | "
                        f"{g('sparbit_padded_rows+128')} | {g('sparbit_padded_rows+256')} | "
+                       f"{g('sparbit_per_step_padded_rows+128')} | {g('sparbit_per_step_padded_rows+256')} | "
                        f"{g('recursive_doubling_padded_rows+128')} | {g('recursive_doubling_padded_rows+256')} |")
     return "\n".join(out) + "\n"
 
@@ -373,9 +391,11 @@ def _size_label(s):
 
 # --------------------------------------------------------------------------- rocprofv3 CSV reduction
 def profile_summary(folder):
-    """Markdown from the CSV files rocprofv3 leaves under `folder` (searched recursively): the kernel statistics,
-    the mean duration per (kernel, grid size) from the kernel trace, and the mean of every counter per (kernel, grid
-    size).  Kernel names are cut after their template arguments."""
+    """Markdown from the CSV files rocprofv3 leaves under `folder` (searched recursively; the runs of one workload
+    are expected side by side in sub-folders): the kernel statistics, then one table per kernel that joins, per grid
+    size, the mean duration from the kernel trace with the mean of every counter collected for that kernel and
+    grid size in any of the runs.  Kernel names are cut after their template arguments; only kernels of this library
+    are listed in the joined tables."""
     def short(name):
         name = name.replace("void ", "")
         return name[:name.rindex(">(") + 1] if ">(" in name else name.split("(")[0]
@@ -388,24 +408,28 @@ def profile_summary(folder):
             out.append(f"| {short(r['Name'])} | {r['Calls']} | {r['TotalDurationNs']} | {float(r['AverageNs']):.1f} | "
                        f"{r['Percentage']} | {r['MinNs']} | {r['MaxNs']} |")
         out.append("")
+    durations = collections.defaultdict(list)   # (kernel, threads) -> ns
+    counters = collections.defaultdict(lambda: collections.defaultdict(list))  # (kernel, threads) -> counter -> values
     for path in sorted(glob.glob(os.path.join(folder, "**", "*kernel_trace.csv"), recursive=True)):
-        shapes = collections.defaultdict(list)
         for r in csv.DictReader(open(path)):
             grid = int(r["Grid_Size_X"]) * int(r["Grid_Size_Y"]) * int(r["Grid_Size_Z"])
-            shapes[(short(r["Kernel_Name"]), grid)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
-        out.append(f"### {os.path.relpath(path, folder)}: duration per (kernel, threads in the grid)\n")
-        out.append("| kernel | threads in the grid | launches | mean us | min us | max us |\n|---|---|---|---|---|---|")
-        for (k, g), v in sorted(shapes.items()):
-            out.append(f"| {k} | {g} | {len(v)} | {sum(v) / len(v) / 1e3:.1f} | {min(v) / 1e3:.1f} | {max(v) / 1e3:.1f} |")
-        out.append("")
+            durations[(short(r["Kernel_Name"]), grid)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
     for path in sorted(glob.glob(os.path.join(folder, "**", "*counter_collection.csv"), recursive=True)):
-        vals = collections.defaultdict(list)
         for r in csv.DictReader(open(path)):
-            vals[(short(r["Kernel_Name"]), int(r["Grid_Size"]), r["Counter_Name"])].append(float(r["Counter_Value"]))
-        out.append(f"### {os.path.relpath(path, folder)}: counters per (kernel, threads in the grid)\n")
-        out.append("| kernel | threads in the grid | counter | dispatches | mean value | sum |\n|---|---|---|---|---|---|")
-        for (k, g, c), v in sorted(vals.items()):
-            out.append(f"| {k} | {g} | {c} | {len(v)} | {sum(v) / len(v):.1f} | {sum(v):.1f} |")
+            counters[(short(r["Kernel_Name"]), int(r["Grid_Size"]))][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    kernels = sorted({k for k, _ in list(durations) + list(counters) if k.startswith("sparbit::")})
+    for kernel in kernels:
+        names = sorted({c for (k, _), cs in counters.items() if k == kernel for c in cs})
+        grids = sorted({g for k, g in list(durations) + list(counters) if k == kernel})
+        out.append(f"### `{kernel}`: per grid size (threads), mean duration over the traced launches and mean counter "
+                   f"value per dispatch\n")
+        out.append("| threads | traced launches | mean us | min us | max us |" + "".join(f" {c} |" for c in names))
+        out.append("|---|---|---|---|---|" + "---|" * len(names))
+        for g in grids:
+            v = durations.get((kernel, g), [])
+            t = f"{len(v)} | {sum(v) / len(v) / 1e3:.1f} | {min(v) / 1e3:.1f} | {max(v) / 1e3:.1f}" if v else "0 | | | "
+            cs = counters.get((kernel, g), {})
+            out.append(f"| {g} | {t} |" + "".join(f" {sum(cs[c]) / len(cs[c]):.1f} |" if c in cs else " |" for c in names))
         out.append("")
     return "\n".join(out) + "\n"
 
@@ -585,19 +609,32 @@ def main():
             per[name] = row
             del r_, dst, s_
             torch.cuda.empty_cache()
-        # Copy ceilings through the library's own kernels: a linear 4 GiB copy (p = 1: the own-block placement of
-        # one block) through the per-step kernel and through the tree kernel.
+        # Ceilings through the library's own kernels.  Read + write: a linear 4 GiB copy (p = 1: the own-block placement
+        # of one block) through the per-step kernel.  Write only: DIRECT on p = 64, 256 KiB blocks (1 GiB written, the
+        # 16 MiB send buffer stays in cache), which is what a form that reads nothing back from HBM could reach.
         nbytes = 4 << 30
         src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=dev)
         dst = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
-        for label, md in (("linear_copy_per_step_kernel", sb.MODE_PER_STEP), ("linear_copy_tree_kernel", sb.MODE_TREE)):
-            t = time_calls(torch, lambda: sb.sparbit_allgather_mode(src, dst, 1, nbytes, sb.SPARBIT, md, stream), stream, 3, 10)
-            per[label] = {"bytes_each_way": nbytes, **t, "kernel": sb.sparbit_last_launch_info()[0],
-                          "read_plus_write_GBps": 2 * nbytes / t["avg_ms"] / 1e6,
-                          "frac_of_peak": 2 * nbytes / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
-                          "ok": bool(torch.equal(src, dst))}
+        t = time_calls(torch, lambda: sb.sparbit_allgather_mode(src, dst, 1, nbytes, sb.SPARBIT, sb.MODE_PER_STEP, stream),
+                       stream, 3, 10)
+        per["linear_copy_per_step_kernel"] = {"bytes_each_way": nbytes, **t, "kernel": sb.sparbit_last_launch_info()[0],
+                                              "read_plus_write_GBps": 2 * nbytes / t["avg_ms"] / 1e6,
+                                              "frac_of_peak": 2 * nbytes / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+                                              "ok": bool(torch.equal(src, dst))}
         del src, dst
+        torch.cuda.empty_cache()
+        pw, Bw = 64, 256 << 10
+        s_ = torch.randint(0, 256, (pw, Bw), dtype=torch.uint8, device=dev)
+        r_ = torch.full((pw, pw, Bw), workloads.POISON, dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t = time_calls(torch, lambda: sb.sparbit_allgather_mode(s_, r_, pw, Bw, sb.DIRECT, sb.MODE_AUTO, stream), stream, 5, 20)
+        per["write_only_ceiling_direct_p64_256KiB"] = {"bytes_written": pw * pw * Bw, **t,
+                                                       "kernel": sb.sparbit_last_launch_info()[0],
+                                                       "write_GBps": pw * pw * Bw / t["avg_ms"] / 1e6,
+                                                       "frac_of_peak": pw * pw * Bw / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+                                                       "ok": bool(torch.equal(r_[pw - 1], s_))}
+        del s_, r_
         torch.cuda.empty_cache()
         # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB), at three
         # granularities: 4 KiB (every block on the 16-byte grid), 4 bytes and 1 byte (the realigning kernel).

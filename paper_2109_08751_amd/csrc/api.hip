@@ -669,17 +669,20 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     //  - jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips;
     //  - otherwise short runs, which keep a slot's read close to its write; the fewer wavefronts the grid has, the
     //    longer the runs, for more loads in flight per wavefront (p = 256, 4 KiB: 57 us with runs of 16, 67 us with
-    //    runs of 4; p = 64, 64 KiB: 52 us against 48 us);
-    //  - when there are more wavefronts than the GPU holds at 16 per compute unit, that many are enough, and fewer
-    //    resident wavefronts mean fewer bytes between a write and its read-back (p = 128, 1 MiB: 3.20 ms against
-    //    3.46 ms): each wavefront then reserves a sixteenth of the unit's LDS.
+    //    runs of 4; p = 64, 64 KiB: 52 us with runs of 8, 48 us with runs of 4);
+    //  - when the grid has more wavefronts than the GPU holds, 11 resident ones per compute unit are enough to keep
+    //    the memory side busy, and fewer resident wavefronts mean fewer bytes between a write and its read-back:
+    //    each wavefront then reserves an eleventh of the unit's LDS, and the runs are 8 ranks (p = 128, 1 MiB:
+    //    3.12 ms; uncapped 3.45 ms; capped at 16 with runs of 4: 3.23 ms).
     const uint64_t waves = pieces * uint64_t(p);
     const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
+    const bool capped = waves >= 8192;
     const long long run_knob = g_tree_run_log2.load();
-    a.lg_k = run_knob >= 0 ? uint32_t(run_knob) : small ? uint32_t(ceil_log2(p)) : waves < 2048 ? 4u : waves < 4096 ? 3u : 2u;
+    a.lg_k = run_knob >= 0 ? uint32_t(run_knob)
+                           : small ? uint32_t(ceil_log2(p)) : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
     const long long lds_knob = g_tree_lds_bytes.load();
-    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : waves >= 8192 ? 10240u : 0u;
+    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? 14336u : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
     const int st = int(g_tree_store.load());
     const bool pf = g_tree_prefetch.load() != 0;
@@ -1094,14 +1097,15 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
 
     // The tree kernel needs no table, no flag and no state, so it is decided before anything is looked up or built
     // (and a capturing stream can record it like any other launch).  AUTO takes it for every whole Sparbit call
-    // whose blocks are on the 16-byte grid or too short for the realigning kernel.
+    // whose blocks are on the 16-byte grid or too short for the realigning kernel; with single-byte accesses only up
+    // to 128 ranks (a lane then walks its tree byte by byte: p = 256, B = 1: 47 us against 39 us per step).
     if (mode == SPARBIT_MODE_TREE && (algo != SPARBIT_ALGO_SPARBIT || !whole)) return SPARBIT_ERR_UNSUPPORTED;
     if (whole && algo == SPARBIT_ALGO_SPARBIT) {
         const int w = access_width(sendbufs, recvbufs, nullptr, B);
         const bool on_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0 || B < size_t(g_line_align_min_bytes.load());
         if (mode == SPARBIT_MODE_TREE ||
             (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0 &&
-             (w == 16 ? on_lines : B < size_t(g_realign_min_bytes.load())))) {
+             (w == 16 ? on_lines : B < size_t(g_realign_min_bytes.load()) && (w == 4 || p <= 128)))) {
             bool eligible = false;
             const int trc = launch_tree(sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, w, stream, &eligible);
             if (trc != SPARBIT_OK || eligible) return trc;
