@@ -39,16 +39,20 @@
  *     and uploaded, and evicting the oldest one synchronises the device.
  *
  * Recording into a HIP graph (stream capture).  A call on a capturing stream
- * records one kernel launch per step and nothing else; it is replayed with the
- * pointers it was recorded with.  It cannot allocate or upload, so the same
+ * records kernel launches and nothing else: one for Sparbit in the tree form
+ * (no table, no state, no earlier call needed; Allgatherv with unequal blocks
+ * reads the geometry's device copy, see below), one per step for everything
+ * else.  The graph is replayed with the pointers it was recorded with.  A
+ * capturing call cannot allocate or upload, so where tables are used the same
  * call (same schedule and p; for Allgatherv the same counts, displs and
  * row_bytes; for Bruck a call at least as large) must have run once outside
  * the capture -- otherwise SPARBIT_ERR_UNSUPPORTED, with nothing recorded.
- * SPARBIT_MODE_AUTO records the per-step form; the PERSISTENT and DATAFLOW
- * modes keep per-stream state on the device that replays would share and are
- * refused with SPARBIT_ERR_UNSUPPORTED.  The graph refers to the library's
- * cached tables: destroy it before sparbit_finalize, and (Allgatherv) before
- * more than 7 other geometries have been used on the device.
+ * SPARBIT_MODE_AUTO records the tree or the per-step form; the PERSISTENT and
+ * DATAFLOW modes keep per-stream state on the device that replays would share
+ * and are refused with SPARBIT_ERR_UNSUPPORTED.  A graph of table-driven
+ * launches refers to the library's cached tables: destroy it before
+ * sparbit_finalize, and (Allgatherv) before more than 7 other geometries have
+ * been used on the device.
  */
 #ifndef SPARBIT_H
 #define SPARBIT_H
@@ -185,10 +189,20 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  *               buffer is defined for equal blocks).
  * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
- * Otherwise, as for equal blocks, a call of at most 256 work items is one
- * dataflow launch and the leading small steps of a larger one share one; the
- * rest goes out as one launch per step, or, where the block lengths of a step
- * are very uneven, one per size class (lengths within a factor of two).  The copy lists of the last few (algo, p, counts, displs,
+ * Sparbit with every block on the 16-byte grid (counts, displs, row_bytes and
+ * the base addresses multiples of 16), or with all blocks shorter than 512
+ * bytes, goes out as ONE launch of the tree form (SPARBIT_MODE_TREE), which
+ * reads each block's length and offset from the geometry's device copy.
+ * Equal blocks at their packed offsets in rows that are longer than p blocks
+ * (displs[k] = k * counts[0], row_bytes > p * counts[0]: padded rows, e.g. to
+ * take a power-of-two row off the channel interleave) need no geometry at all:
+ * they run through the equal-block tree kernel with row_bytes as the row
+ * stride, at the cost of the packed call.
+ * Otherwise, as for equal blocks of the other schedules, a call of at most 256
+ * work items is one dataflow launch and the leading small steps of a larger one
+ * share one; the rest goes out as one launch per step, or, where the block
+ * lengths of a step are very uneven, one per size class (lengths within a
+ * factor of two).  The copy lists of the last few (algo, p, counts, displs,
  * row_bytes) geometries are cached per device; a new geometry costs O(p^2) host
  * work and one upload.
  */
