@@ -56,9 +56,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
         (20492913475, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
         (20332541905, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
@@ -637,42 +637,50 @@ def main():
         del s_, r_
         torch.cuda.empty_cache()
         # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB), at three
-        # granularities: 4 KiB (every block on the 16-byte grid), 4 bytes and 1 byte (the realigning kernel).
+        # granularities: 4 KiB (every block on whole 128-byte lines), 4 bytes and 1 byte.  The last two with rows as
+        # long as the blocks need (the rows then lie differently relative to the lines: realigning kernel, one launch
+        # per step) and with rows rounded up to whole lines (any-alignment tree form, one launch).
         import numpy as np
         pv = 128
-        for label, grain in (("allgatherv_p128_0.5-1.5MiB", 4096), ("allgatherv_p128_0.5-1.5MiB_grain4B", 4),
-                             ("allgatherv_p128_0.5-1.5MiB_grain1B", 1)):
+        for label, grain, row_grain in (("allgatherv_p128_0.5-1.5MiB", 4096, 1),
+                                        ("allgatherv_p128_0.5-1.5MiB_grain4B", 4, 1),
+                                        ("allgatherv_p128_0.5-1.5MiB_grain1B", 1, 1),
+                                        ("allgatherv_p128_0.5-1.5MiB_grain4B_rows128", 4, 128),
+                                        ("allgatherv_p128_0.5-1.5MiB_grain1B_rows128", 1, 128)):
             rng = np.random.default_rng(workloads.DEFAULT_SEED)
             counts = (rng.integers(512 << 10, (1536 << 10) + 1, pv) // grain * grain).astype(np.uint64)
             displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)
-            row = int(counts.sum())
+            moved = int(counts.sum())
+            row = (moved + row_grain - 1) // row_grain * row_grain
             s_ = torch.randint(0, 256, (row,), dtype=torch.uint8, device=dev)
             r_ = torch.full((pv, row), workloads.POISON, dtype=torch.uint8, device=dev)
             torch.cuda.synchronize()
             t = time_calls(torch, lambda: sb.sparbit_allgatherv(s_, r_, pv, counts, displs, row, sb.SPARBIT, stream),
                            stream, 3, 10)
             per[label] = {
-                "p": pv, "row_bytes": row, **t, "effective_GBps": pv * row / t["avg_ms"] / 1e6,
+                "p": pv, "row_bytes": row, "block_bytes_per_rank": moved, **t,
+                "effective_GBps": pv * moved / t["avg_ms"] / 1e6,
                 "kernel": sb.sparbit_last_launch_info()[0],
-                "ok": bool(torch.equal(r_[pv - 1], s_))}
+                "ok": bool(torch.equal(r_[pv - 1][:moved], s_[:moved]))}
             vform = form_of(per[label]["kernel"])
-            vbytes = row + pv * row if vform == "tree" else 2 * pv * row
+            vbytes = moved + pv * moved if vform == "tree" else 2 * pv * moved
             per[label].update({"form": vform, "model_bytes": vbytes, "model_GBps": vbytes / t["avg_ms"] / 1e6,
                                "model_frac": vbytes / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS})
             del s_, r_
             torch.cuda.empty_cache()
-        # Equal blocks off the 16-byte grid: cfg4's shape with 4 more bytes per block
-        pu, Bu = 128, (1 << 20) + 4
-        s_ = torch.randint(0, 256, (pu, Bu), dtype=torch.uint8, device=dev)
-        r_ = torch.full((pu, pu, Bu), workloads.POISON, dtype=torch.uint8, device=dev)
-        torch.cuda.synchronize()
-        t = time_calls(torch, lambda: sb.sparbit_allgather_mode(s_, r_, pu, Bu, sb.SPARBIT, sb.MODE_AUTO, stream),
-                       stream, 3, 10)
-        kname = sb.sparbit_last_launch_info()[0]
-        per["sparbit_p128_1MiB+4B"] = {"p": pu, "block_bytes": Bu, **t, **rates(pu, Bu, t["avg_ms"], form_of(kname)),
-                                       "kernel": kname, "ok": bool(torch.equal(r_[pu - 1], s_))}
-        del s_, r_
-        torch.cuda.empty_cache()
+        # Equal blocks off the 16-byte grid: cfg4's shape with 4 more bytes per block (rows a multiple of 128 bytes
+        # apart: any-alignment tree form), and the same blocks on 125 ranks (rows off the lines: realigning kernel)
+        for label, pu, Bu in (("sparbit_p128_1MiB+4B", 128, (1 << 20) + 4), ("sparbit_p125_1MiB+4B", 125, (1 << 20) + 4)):
+            s_ = torch.randint(0, 256, (pu, Bu), dtype=torch.uint8, device=dev)
+            r_ = torch.full((pu, pu, Bu), workloads.POISON, dtype=torch.uint8, device=dev)
+            torch.cuda.synchronize()
+            t = time_calls(torch, lambda: sb.sparbit_allgather_mode(s_, r_, pu, Bu, sb.SPARBIT, sb.MODE_AUTO, stream),
+                           stream, 3, 10)
+            kname = sb.sparbit_last_launch_info()[0]
+            per[label] = {"p": pu, "block_bytes": Bu, **t, **rates(pu, Bu, t["avg_ms"], form_of(kname)),
+                          "kernel": kname, "ok": bool(torch.equal(r_[pu - 1], s_))}
+            del s_, r_
+            torch.cuda.empty_cache()
         out["per_config"] = per
         assert sb.sparbit_barrier_timeouts(stream) == 0
 

@@ -15,12 +15,15 @@
  *             drained) slot k of every rank holds rank k's block: the
  *             MPI_Allgather post-condition of Section II of the paper.
  *   Blocks are opaque bytes; the MPI (count, datatype) pair collapses into
- *   block_bytes.  Any block_bytes and any base alignment is accepted.  The
- *   full rate needs a receive base pointer and a block_bytes that are
- *   multiples of 128 (whole cache lines per store); otherwise blocks of 512
- *   bytes and more still move in 16-byte vectors (stores aligned to lines,
- *   loads at the source's alignment, ~80-97 % of the full rate) and shorter
- *   ones with 16-, 4- or single-byte accesses as their alignment allows.
+ *   block_bytes.  Any block_bytes and any base alignment is accepted.  What
+ *   the full rate of a Sparbit call needs is that p * block_bytes, the distance
+ *   between two ranks' receive buffers, is a multiple of 128: blocks of 512
+ *   bytes and more then move in 16-byte vectors that cover whole 128-byte
+ *   lines wherever the blocks start and end (single bytes at their two ends).
+ *   With other row lengths such blocks still move in 16-byte vectors, on
+ *   calls of several GiB at about 60 % of that rate (one launch per step);
+ *   blocks shorter than 512 bytes move with 16-, 4- or single-byte accesses as
+ *   their alignment allows.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
@@ -89,8 +92,10 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit, blocks on the 16-byte grid (and, from 64 KiB on, on the
-                                     128-byte grid) or shorter than 512 bytes: TREE.  Everything else: DATAFLOW for
+#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit: TREE, except for blocks of 512 bytes and more that are
+                                     off the 128-byte grid in rows (p * block_bytes) that are off it too, when the
+                                     call is larger than 512 MiB (and, below 64 KiB per block, off the 16-byte
+                                     grid).  Everything else: DATAFLOW for
                                      calls of at most 256 work items (block copies x 16 KiB pieces) or at most 512
                                      with pieces of up to 64 KiB, PERSISTENT (one workgroup) for other calls of at most
                                      4 KiB, else PER_STEP with the leading small steps (at most 512 work items)
@@ -112,7 +117,11 @@ extern "C" {
                                      trees are independent).  Same messages as Algorithm 1, each read from the
                                      forwarder's receive buffer; a forwarder's reads of one slot for different steps
                                      are merged, and the order is any order in which a rank forwards after it
-                                     received.  No table, flag, barrier or device state: nothing waits. */
+                                     received.  No table, flag, barrier or device state: nothing waits.
+                                     Blocks of 512 bytes and more that do not start and end on 128-byte lines are
+                                     cut into pieces relative to the lines of the owner's receive buffer (the
+                                     same block offsets at every rank): 16-byte chunks, and single bytes at a
+                                     block's two ends. */
 
 /*
  * MPI_Allgather over p virtual ranks with the Sparbit schedule (Algorithm 1 of
@@ -189,10 +198,13 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  *               buffer is defined for equal blocks).
  * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
- * Sparbit with every block on the 16-byte grid (counts, displs, row_bytes and
- * the base addresses multiples of 16), or with all blocks shorter than 512
- * bytes, goes out as ONE launch of the tree form (SPARBIT_MODE_TREE), which
- * reads each block's length and offset from the geometry's device copy.
+ * Sparbit goes out as ONE launch of the tree form (SPARBIT_MODE_TREE), which
+ * reads each block's length and offset from the geometry's device copy, under
+ * the same rules as equal blocks: counts and displs of any granularity run at
+ * the full rate when row_bytes is a multiple of 128 (round the rows up where
+ * the layout is yours to choose); with other row lengths the tree form serves
+ * calls of up to 512 MiB, and larger ones only when everything is on the
+ * 128-byte grid (or, for blocks below 64 KiB, on the 16-byte grid).
  * Equal blocks at their packed offsets in rows that are longer than p blocks
  * (displs[k] = k * counts[0], row_bytes > p * counts[0]: padded rows, e.g. to
  * take a power-of-two row off the channel interleave) need no geometry at all:
@@ -296,6 +308,10 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
  *                          and write-through to the others
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
+ *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the
+ *                          tree kernel's any-alignment form (default 1; 0: one launch per step, realigning kernel)
+ *   "tree_part_line_max_bytes"  ... in rows that are not a multiple of 128 bytes apart only for calls of at most
+ *                          this many receive bytes (default 512 MiB)
  *   "tree_lds_bytes"       LDS each of its wavefronts reserves without using it, which caps the wavefronts per
  *                          compute unit (0..65536; 160 KiB per unit; -1, the default: 14336 for grids of 8192 and
  *                          more wavefronts, else 0)

@@ -117,6 +117,8 @@ std::atomic<long long> g_tree_small_bytes{64ll << 20};        // p*p*B up to thi
 std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
 std::atomic<long long> g_tree_store{2};                       // its stores: 0 plain, 2 write-through, 3 by destination
 std::atomic<long long> g_tree_prefetch{1};                    // it loads the next run's first rank ahead
+std::atomic<long long> g_tree_any_align{1};                   // blocks of 512 bytes and more off the 128-byte grid: the any-alignment tree form
+std::atomic<long long> g_tree_part_line_max_bytes{512ll << 20};  // ... with rows off that grid only for calls up to this size
 std::atomic<long long> g_tree_lds_bytes{-1};                  // LDS each of its wavefronts reserves (unused: caps the wavefronts per CU); -1 = by size              // blocks at least this long, not 16-byte aligned: realigning kernel
 
 struct DevicePlan {
@@ -612,14 +614,19 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
 }
 
 // The tree kernel: one wavefront per (tree, piece of 64 * U vectors).
-template <typename V, int U, int NB, bool VAR>
+template <typename V, int U, int NB, bool VAR, bool ANY = false>
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream)
 {
     if (sizeof(V) != 16) store_kind = 0;
-    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR));
-#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR>), grid, dim3(64), lds, stream, a)
-    if constexpr (sizeof(V) == 16) {
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY));
+#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY>), grid, dim3(64), lds, stream, a)
+    if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
+        if (store_kind != 0 && prefetch) SB_TREE(2, true);
+        else if (store_kind != 0) SB_TREE(2, false);
+        else if (prefetch) SB_TREE(0, true);
+        else SB_TREE(0, false);
+    } else if constexpr (sizeof(V) == 16) {
         if (store_kind == 3 && prefetch) SB_TREE(3, true);
         else if (store_kind == 3) SB_TREE(3, false);
         else if (store_kind == 2 && prefetch) SB_TREE(2, true);
@@ -636,8 +643,10 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
 }
 
 // Equal blocks of B bytes (counts == nullptr; slot k at k * B of a row) or blocks of different sizes (device arrays
-// counts / displs; `B` is then the longest block).  Rows are row_bytes apart.  *eligible stays false when the
-// piece count does not fit a grid (blocks of several GiB): the caller falls back to per-step launches.
+// counts / displs; `B` is then the longest block).  Rows are row_bytes apart.  `width` is the access width the
+// call's addresses and lengths allow; 0 asks for the any-alignment form (16-byte chunks cut relative to the
+// 128-byte lines, single bytes at a block's ends).  *eligible stays false when the piece count does not fit a grid
+// (blocks of several GiB): the caller falls back to per-step launches.
 int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t row_bytes, const uint64_t* counts,
                 const uint64_t* displs, uint64_t total_bytes, int width, hipStream_t stream, bool* eligible)
 {
@@ -646,10 +655,12 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
         *eligible = true;
         return SPARBIT_OK;
     }
+    const bool any = width == 0;
     int U = width == 16 ? int(g_tree_unroll.load()) : 1;
-    const uint64_t vpb = B / size_t(width);
+    const uint64_t vpb = any ? 0 : B / size_t(width);
     while (U > 1 && vpb <= uint64_t(64 * (U / 2))) U /= 2;  // short blocks: no lanes that only idle
-    const uint64_t pieces = (vpb + uint64_t(64 * U) - 1) / uint64_t(64 * U);
+    // any-alignment form: up to 127 bytes ahead of the first line boundary, then 1 KiB pieces
+    const uint64_t pieces = any ? 1 + (uint64_t(B) + 1023) / 1024 : (vpb + uint64_t(64 * U) - 1) / uint64_t(64 * U);
     uint32_t lg_g = uint32_t(g_interleave_log2.load());
     while (lg_g > 0 && (1u << lg_g) > uint32_t(p)) --lg_g;
     if ((pieces << lg_g) > 0x7fffffffull / 64) return SPARBIT_OK;  // the grid's x extent stays below 2^31 lanes
@@ -684,10 +695,15 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     const long long lds_knob = g_tree_lds_bytes.load();
     const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? 14336u : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
-    const int st = int(g_tree_store.load());
+    int st = int(g_tree_store.load());
+    // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
+    // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
+    // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
+    if (any && row_bytes % 128 != 0) st = 0;
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
     if (counts) {
+        if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream);
         if (width == 16) {
             if (U == 2) return launch_tree_vu<u32x4, 2, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
             return launch_tree_vu<u32x4, 1, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
@@ -695,12 +711,39 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
         if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
         return launch_tree_vu<uint8_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
     }
+    if (any) return launch_tree_vu<u32x4, 1, 8, false, true>(a, grid, st, pf, lds, total_bytes, stream);
     if (width == 16) {
         if (U == 2) return launch_tree_vu<u32x4, 2, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
         return launch_tree_vu<u32x4, 1, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
     }
     if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
     return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
+}
+
+// Which form of the tree kernel serves a whole Sparbit call: 16, 4 or 1 = that access width with the pieces cut
+// from the block's start, 0 = the any-alignment form, -1 = none (the call goes out step by step).  `w` is the
+// access width the call's addresses and lengths allow, `whole_lines` says that every block starts and ends on a
+// 128-byte line as it is, `longest` is the longest block, `asked_for` an explicit SPARBIT_MODE_TREE.
+int tree_form(bool asked_for, int w, bool whole_lines, uint64_t row_bytes, size_t longest, uint64_t total_bytes, int p)
+{
+    if (w == 16 && whole_lines) return 16;
+    const bool longish = longest >= size_t(g_realign_min_bytes.load());
+    if (g_tree_any_align.load() != 0 && longish) {
+        // Rows a multiple of 128 bytes apart: every rank's copy of a slot lies the same way relative to the lines,
+        // so the any-alignment form writes whole lines everywhere (p = 128, B = 1 MiB + 4: 3.23 ms against 5.32 ms
+        // step by step; p = 256, B = 4100: 72 against 125 us).
+        if (row_bytes % 128 == 0) return 0;
+        // Other rows: its stores cover part-lines at every piece's ends.  With plain stores it is still ahead
+        // while the job is small (p = 61, B = 64 KiB + 16: 54 against 95 us; p = 253, B = 4100: 88 against 117
+        // us), level from about 1 GiB (p = 125, B = 64 KiB + 16: 350 against 343 us), behind on several GiB (p =
+        // 125, B = 1 MiB + 4: 5.6 against 5.0 ms).
+        if (total_bytes <= uint64_t(g_tree_part_line_max_bytes.load())) return 0;
+    }
+    if (w == 16) return (asked_for || longest < size_t(g_line_align_min_bytes.load())) ? 16 : -1;
+    // single-byte accesses only up to 128 ranks (a lane walks its tree byte by byte: p = 256, B = 1: 47 us against
+    // 39 us step by step)
+    if (!longish) return (asked_for || w == 4 || p <= 128) ? w : -1;
+    return asked_for ? w : -1;
 }
 
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb);
@@ -954,10 +997,11 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
         total_bytes += counts[k];
     }
     total_bytes *= uint64_t(p);
-    // Sparbit as the tree kernel, as for equal blocks: when every block is on the 16-byte grid, or all are too
-    // short for the realigning kernel.
-    const bool tree = algo == SPARBIT_ALGO_SPARBIT && g_tree_auto.load() != 0 &&
-                      (width == 16 || longest < size_t(g_realign_min_bytes.load()));
+    // Sparbit as the tree kernel, by the same rules as for equal blocks.
+    const int form = algo == SPARBIT_ALGO_SPARBIT && g_tree_auto.load() != 0
+                         ? tree_form(false, width, (bits & 127) == 0, row_bytes, longest, total_bytes, p)
+                         : -1;
+    const bool tree = form >= 0;
     // Equal blocks at their packed positions in rows that are longer than p blocks (padded rows): the equal-block
     // tree kernel takes the row length as it is, and needs no table at all.
     bool padded = tree && counts[0] != 0 && row_bytes > size_t(p) * counts[0];
@@ -965,7 +1009,7 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     if (padded) {
         tl_launch_info = LaunchInfo();
         bool eligible = false;
-        const int trc = launch_tree(sendbufs, recvbufs, p, counts[0], row_bytes, nullptr, nullptr, total_bytes, width, stream,
+        const int trc = launch_tree(sendbufs, recvbufs, p, counts[0], row_bytes, nullptr, nullptr, total_bytes, form, stream,
                                     &eligible);
         if (trc != SPARBIT_OK || eligible) return trc;
     }
@@ -982,8 +1026,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     const bool on_lines = (bits & 127) == 0;  // every block starts and ends on a 128-byte line
     if (tree) {  // sizes and offsets come from the geometry's device copy
         bool eligible = false;
-        const int trc = launch_tree(sendbufs, recvbufs, p, longest, row_bytes, vp->d_geometry, vp->d_geometry + p, total_bytes,
-                                    width, stream, &eligible);
+        const int trc = launch_tree(sendbufs, recvbufs, p, longest, row_bytes, vp->d_geometry, vp->d_geometry + p, total_bytes, form, stream,
+                                    &eligible);
         if (trc != SPARBIT_OK || eligible) return trc;
     }
 
@@ -1096,18 +1140,17 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     }
 
     // The tree kernel needs no table, no flag and no state, so it is decided before anything is looked up or built
-    // (and a capturing stream can record it like any other launch).  AUTO takes it for every whole Sparbit call
-    // whose blocks are on the 16-byte grid or too short for the realigning kernel; with single-byte accesses only up
-    // to 128 ranks (a lane then walks its tree byte by byte: p = 256, B = 1: 47 us against 39 us per step).
+    // (and a capturing stream can record it like any other launch).
     if (mode == SPARBIT_MODE_TREE && (algo != SPARBIT_ALGO_SPARBIT || !whole)) return SPARBIT_ERR_UNSUPPORTED;
-    if (whole && algo == SPARBIT_ALGO_SPARBIT) {
+    if (whole && algo == SPARBIT_ALGO_SPARBIT &&
+        (mode == SPARBIT_MODE_TREE || (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0))) {
         const int w = access_width(sendbufs, recvbufs, nullptr, B);
-        const bool on_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0 || B < size_t(g_line_align_min_bytes.load());
-        if (mode == SPARBIT_MODE_TREE ||
-            (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0 &&
-             (w == 16 ? on_lines : B < size_t(g_realign_min_bytes.load()) && (w == 4 || p <= 128)))) {
+        const bool whole_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0;
+        const int form = tree_form(mode == SPARBIT_MODE_TREE, w, whole_lines, uint64_t(p) * B, B, recv_bytes, p);
+        if (form >= 0) {
             bool eligible = false;
-            const int trc = launch_tree(sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, w, stream, &eligible);
+            const int trc = launch_tree(sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, form, stream,
+                                        &eligible);
             if (trc != SPARBIT_OK || eligible) return trc;
             if (mode == SPARBIT_MODE_TREE) return SPARBIT_ERR_UNSUPPORTED;  // blocks of several GiB
         }
@@ -1526,6 +1569,11 @@ int sparbit_tune(const char* key, long long value)
         g_tree_store = value;
     } else if (!std::strcmp(key, "tree_prefetch")) {
         g_tree_prefetch = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_any_align")) {
+        g_tree_any_align = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_part_line_max_bytes")) {
+        if (value < 0) return SPARBIT_ERR_ARG;
+        g_tree_part_line_max_bytes = value;
     } else if (!std::strcmp(key, "tree_lds_bytes")) {
         if (value < -1 || value > 65536) return SPARBIT_ERR_ARG;
         g_tree_lds_bytes = value;

@@ -191,27 +191,57 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t piece_buffer(const uint8_t* ba
 // complete in order on this target).  The operand leaves the export and scalar/LDS counters at "no wait".
 __device__ __forceinline__ void wait_for_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// What a lane holds of one rank's piece: U vectors and, in the ANY form, one byte of the piece's ragged end.
+template <typename V, int U>
+struct Held {
+    V v[U];
+    uint8_t tail;
+};
+
 // PF: the first rank of the next run is loaded ahead, while the current run is served.
-template <typename V, int U, int NB, int ST, bool PF, bool VAR = false>
+// ANY (16-byte vectors, U = 1): blocks of any length at any byte address.  Which bytes of a block a lane moves must
+// not depend on the rank (the lane reads back what it wrote itself), so the pieces are cut in block offsets, the same
+// at every rank: piece 0 ends where the block, as it lies in its own rank's receive buffer, reaches a 128-byte line,
+// the others follow in steps of 1 KiB.  Where all ranks' slots have that same position relative to the lines (rows
+// a multiple of 128 bytes apart) every store covers whole lines; elsewhere the same accesses are unaligned, which the
+// target's buffer loads and stores accept.  A piece is a run of 16-byte chunks, one per lane, and, at the block's
+// first and last piece, up to 15 single bytes, one per lane.
+template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false>
 __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
 {
+    static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
     if (b >= a.p) return;
     const uint32_t p = a.p;
-    uint64_t vectors = a.vpb, offset = uint64_t(b) * a.block_bytes;  // this tree's block inside a row
-    if constexpr (VAR) {
-        vectors = a.counts[b] / sizeof(V);
-        offset = a.displs[b];
+    uint64_t offset = uint64_t(b) * a.block_bytes;  // this tree's block inside a row
+    if constexpr (VAR) offset = a.displs[b];
+    uint32_t piece_vectors;  // V's in this wavefront's piece
+    uint32_t tail_bytes = 0;  // ANY: single bytes after them
+    if constexpr (ANY) {
+        const uint64_t bytes = VAR ? a.counts[b] : a.block_bytes;
+        const uint64_t own = reinterpret_cast<uint64_t>(a.recv) + uint64_t(b) * a.row_bytes + offset;
+        const uint64_t to_line = (0 - own) & 127u;  // block bytes ahead of the first line boundary
+        const uint64_t i = blockIdx.x >> a.lg_g;
+        const uint64_t lo = i ? to_line + (i - 1) * 1024u : 0;
+        uint64_t hi = to_line + i * 1024u;
+        if (hi > bytes) hi = bytes;
+        if (lo >= hi) return;  // uniform: no bytes ahead of the line, or past the block's end
+        offset += lo;
+        piece_vectors = uint32_t(hi - lo) >> 4;
+        tail_bytes = uint32_t(hi - lo) & 15u;
+    } else {
+        const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
+        const uint64_t piece_at = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U);  // first vector of the piece
+        if (piece_at >= vectors) return;  // uniform: a shorter block has no such piece
+        offset += piece_at * sizeof(V);
+        const uint64_t left = vectors - piece_at;
+        piece_vectors = left < uint64_t(64 * U) ? uint32_t(left) : uint32_t(64 * U);
     }
-    const uint64_t piece_at = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U);  // first vector of this wavefront's piece
-    if (piece_at >= vectors) return;  // uniform: a shorter block has no such piece
-    offset += piece_at * sizeof(V);
-    const uint64_t left = vectors - piece_at;
-    const uint32_t piece_vectors = left < uint64_t(64 * U) ? uint32_t(left) : uint32_t(64 * U);
     bool ok[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) ok[u] = threadIdx.x + uint32_t(u * 64) < piece_vectors;
+    typedef Held<V, U> H;
     // The piece of slot b held by the rank at relative rank rho (wave-uniform).  No __restrict__ anywhere: a slot
     // is written and later read.
     auto slot = [&](uint32_t rho) -> uint8_t* {
@@ -219,46 +249,56 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
         if (r >= p) r -= p;
         return a.recv + uint64_t(r) * a.row_bytes + offset;
     };
-    auto load = [&](const uint8_t* s, V (&x)[U]) {
+    auto load = [&](const uint8_t* s, H& x) {
         if constexpr (sizeof(V) == 16) {
             const __amdgpu_buffer_rsrc_t rs = piece_buffer(s, piece_vectors * 16u);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                x[u] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, int(threadIdx.x * 16u + u * 1024u), 0, 0));
+                x.v[u] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, int(threadIdx.x * 16u + u * 1024u), 0, 0));
+            if constexpr (ANY) {
+                if (tail_bytes)
+                    x.tail = __builtin_amdgcn_raw_buffer_load_b8(piece_buffer(s + piece_vectors * 16u, tail_bytes),
+                                                                 int(threadIdx.x), 0, 0);
+            }
         } else {
             const V* sv = reinterpret_cast<const V*>(s) + threadIdx.x;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) x[u] = sv[u * 64];
+                if (ok[u]) x.v[u] = sv[u * 64];
         }
     };
-    auto store = [&](uint8_t* d, const V (&x)[U], bool read_again_soon) {
+    auto store = [&](uint8_t* d, const H& x, bool read_again_soon) {
         if constexpr (sizeof(V) == 16) {
             const __amdgpu_buffer_rsrc_t rd = piece_buffer(d, piece_vectors * 16u);
             typedef uint32_t raw4 __attribute__((ext_vector_type(4)));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int at = int(threadIdx.x * 16u + u * 1024u);
-                const raw4 v = __builtin_bit_cast(raw4, x[u]);
+                const raw4 v = __builtin_bit_cast(raw4, x.v[u]);
                 if (ST == 0 || (ST == 3 && read_again_soon))
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, kBufferSc0Sc1);
             }
+            if constexpr (ANY) {
+                if (tail_bytes)
+                    __builtin_amdgcn_raw_buffer_store_b8(x.tail, piece_buffer(d + piece_vectors * 16u, tail_bytes),
+                                                         int(threadIdx.x), 0, ST == 0 ? 0 : kBufferSc0Sc1);
+            }
         } else {
             V* dv = reinterpret_cast<V*>(d) + threadIdx.x;
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                if (ok[u]) dv[u * 64] = x[u];
+                if (ok[u]) dv[u * 64] = x.v[u];
         }
     };
     const uint32_t K = 1u << a.lg_k;
     // From relative rank rho to rho + d.  The destination is read again soon if it forwards (d >= 2: it is even)
     // and belongs to this run or is the first rank of the next one.
-    auto send_to = [&](uint32_t rho, uint32_t d, const V (&x)[U]) { store(slot(rho + d), x, d >= 2 && d <= K); };
+    auto send_to = [&](uint32_t rho, uint32_t d, const H& x) { store(slot(rho + d), x, d >= 2 && d <= K); };
     // A rank forwards if it is even in the tree and the next relative rank exists (its nearest destination).
     auto forwards = [&](uint32_t rho) { return (rho & 1u) == 0 && rho + 1 < p; };
-    V xh[U];  // the block as the run's first rank holds it
+    H xh;  // the block as the run's first rank holds it
     if (a.send) {
         load(a.send + offset, xh);
         store(slot(0), xh, false);  // own-block placement; read again only in an in-place call
@@ -272,12 +312,12 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
             if (d < p - h) send_to(h, d, xh);
         // The next run's first rank got the block from this run's first rank (just above) or from an earlier run,
         // so its load can already travel while this run's other forwarders are served.
-        V xn[U];
+        H xn;
         const uint32_t hn = h + K;
         if (PF && hn < p && forwards(hn)) load(slot(hn), xn);
         for (uint32_t st = K >> 1; st >= 2; st >>= 1) {  // forwarders whose lowest set bit is st
             for (uint32_t n0 = h + st; n0 < end; n0 += 2 * st * NB) {
-                V x[NB][U];
+                H x[NB];
 #pragma unroll
                 for (int i = 0; i < NB; ++i) {
                     const uint32_t n = n0 + 2 * st * i;
@@ -295,10 +335,7 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
                 }
             }
         }
-        if constexpr (PF) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) xh[u] = xn[u];
-        }
+        if constexpr (PF) xh = xn;
     }
 }
 

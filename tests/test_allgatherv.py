@@ -148,6 +148,7 @@ def launch_per_step_only():
 
 def gpu_allgatherv(torch, algo, p, counts, displs, row, send, in_place=False, misalign=0):
     dev = torch.device("cuda:0")
+    assert 0 <= misalign <= 64  # the views below must lie inside the allocations
     sraw = torch.empty(row + 64, dtype=torch.uint8, device=dev)
     rraw = torch.full((p * row + 64,), POISON, dtype=torch.uint8, device=dev)
     d_send = sraw[misalign:misalign + row]
@@ -247,7 +248,7 @@ def test_gpu_allgatherv_skewed_sizes():
 @pytest.mark.gpu
 def test_gpu_allgatherv_blocks_off_the_16_byte_grid():
     """Byte-granular counts and displacements with blocks from 0 bytes to ~300 KiB: the body of every copy moves
-    in aligned 16-byte stores, head and tail byte-wise; gaps between blocks keep their poison."""
+    in 16-byte vectors, its ends byte-wise; gaps between blocks keep their poison."""
     import torch
     for p, seed, mis in ((5, 1, 0), (12, 2, 3), (33, 3, 8), (64, 4, 1)):
         rng = np.random.default_rng(seed)
@@ -257,18 +258,32 @@ def test_gpu_allgatherv_blocks_off_the_16_byte_grid():
         counts[rng.integers(0, p)] = 513
         gaps = rng.integers(0, 40, p).astype(np.uint64)
         displs = (np.concatenate([[0], np.cumsum(counts[:-1] + gaps[:-1])]) + 5).astype(np.uint64)
-        row = int(displs[-1] + counts[-1] + 9)
-        send = np.tile(workloads.make_send_raw(1, 65536, seed).reshape(-1), row // 65536 + 1)[:row].copy()
-        for in_place in (False, True):
-            print("[case] off-grid allgatherv", p, mis, in_place, flush=True)
-            want = np.full((p, row), POISON, dtype=np.uint8)
-            if in_place:
-                for r in range(p):
-                    d, c = int(displs[r]), int(counts[r])
-                    want[r, d:d + c] = send[d:d + c]
-            oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
-            got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place, misalign=mis)
-            assert np.array_equal(got, want), (p, in_place)
+        # Rows as long as the blocks need, and rounded up to whole 128-byte lines (every rank's slot then lies the
+        # same way relative to the lines).  Both go out as one launch of the any-alignment tree form, the first with
+        # plain stores and only up to a total size; beyond it (limit 0 here) as one launch per step.
+        tight = int(displs[-1] + counts[-1] + 9)
+        for row, limit in ((tight, 512 << 20), (tight, 0), ((tight + 127) // 128 * 128, 512 << 20)):
+            sb.sparbit_tune("tree_part_line_max_bytes", limit)
+            send = np.tile(workloads.make_send_raw(1, 65536, seed).reshape(-1), row // 65536 + 1)[:row].copy()
+            try:
+                for in_place in (False, True):
+                    print("[case] off-grid allgatherv", p, mis, row % 128, limit, in_place, flush=True)
+                    want = np.full((p, row), POISON, dtype=np.uint8)
+                    if in_place:
+                        for r in range(p):
+                            d, c = int(displs[r]), int(counts[r])
+                            want[r, d:d + c] = send[d:d + c]
+                    oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
+                    got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place, misalign=mis)
+                    name, launches = sb.sparbit_last_launch_info()
+                    if limit:
+                        store = 2 if row % 128 == 0 else 0
+                        assert "tree_kernel" in name and name.endswith(f", 8, {store}, true, true, true>") and launches == 1, name
+                    else:
+                        assert "tree_kernel" not in name, name
+                    assert np.array_equal(got, want), (p, row, limit, in_place)
+            finally:
+                sb.sparbit_tune("tree_part_line_max_bytes", 512 << 20)
 
 
 @pytest.mark.gpu

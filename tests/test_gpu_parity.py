@@ -45,9 +45,10 @@ def gpu_buffers(torch, p, B, send, in_place=False, misalign=0, send_misalign=Non
     """Device send / poison-filled recv; `misalign` shifts both base addresses (`send_misalign`: the send
     buffer's own shift)."""
     dev = torch.device("cuda:0")
-    sraw = torch.empty(p * B + 64, dtype=torch.uint8, device=dev)
-    rraw = torch.full((p * p * B + 64,), POISON, dtype=torch.uint8, device=dev)
+    sraw = torch.empty(p * B + 256, dtype=torch.uint8, device=dev)
+    rraw = torch.full((p * p * B + 256,), POISON, dtype=torch.uint8, device=dev)
     ms = misalign if send_misalign is None else send_misalign
+    assert 0 <= misalign <= 256 and 0 <= ms <= 256  # the views below must lie inside the allocations
     d_send = sraw[ms:ms + p * B]
     d_recv = rraw[misalign:misalign + p * p * B]
     d_send.copy_(torch.from_numpy(send.reshape(-1)))

@@ -13,7 +13,8 @@ from test_gpu_parity import POISON, announce, gpu_buffers, gpu_result, oracle_re
 pytestmark = pytest.mark.gpu
 
 DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 64 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
-            "tree_lds_bytes": -1}
+            "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
+            "tree_part_line_max_bytes": 512 << 20}
 
 
 @pytest.fixture(scope="module")
@@ -74,6 +75,101 @@ def test_narrow_accesses(torch):
             want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
             got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place, misalign=mis)
             assert np.array_equal(got, want), (p, B, mis, in_place)
+
+
+def launched_any_alignment_form():
+    name = sb.sparbit_last_launch_info()[0]
+    return "tree_kernel" in name and name.endswith(", true>")
+
+
+@pytest.mark.parametrize("knobs", [{}, {"tree_small_bytes": 0, "tree_run_log2": 0, "tree_prefetch": 0},
+                                   {"tree_small_bytes": 0, "tree_run_log2": 3, "tree_store": 0},
+                                   {"tree_small_bytes": 0, "tree_run_log2": 2, "tree_lds_bytes": 14336}])
+def test_any_alignment_form(torch, knobs):
+    """Blocks of 512 bytes and more that do not start and end on 128-byte lines, in rows that are a multiple of 128
+    bytes apart: pieces cut relative to the lines, 16-byte chunks plus single bytes at a block's two ends.  Block
+    lengths and base addresses at 1-, 4- and 16-byte granularity, a first piece of 0 .. 127 bytes, in place, and
+    what AUTO does with such a call."""
+    for k, v in knobs.items():
+        sb.sparbit_tune(k, v)
+    cases = ((128, 513, 0, 0), (128, 1028, 0, 0), (64, 4100, 0, 0), (32, 1000, 0, 0), (8, 65552, 0, 0), (16, 2072, 3, 5),
+             (64, 4096, 1, 0), (64, 4096, 127, 13), (256, 600, 0, 0), (96, 4100, 0, 8), (257, 1280, 4, 0), (24, 70000, 0, 0),
+             (8, 3 * 1024 + 16, 112, 0), (8, 2048, 16, 0), (40, 16 * 77, 15, 1))
+    for p, B, mis, smis in cases:
+        assert p * B % 128 == 0
+        for mode, in_place in ((sb.MODE_TREE, False), (sb.MODE_AUTO, False), (sb.MODE_TREE, True)):
+            announce("tree any alignment", knobs, p, B, mis, smis, mode, in_place)
+            send = workloads.make_send_raw(p, B, seed=B + p)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, mode, in_place=in_place, misalign=mis, send_misalign=smis)
+            assert launched_any_alignment_form(), sb.sparbit_last_launch_info()
+            assert np.array_equal(got, want), (p, B, mis, smis, mode, in_place)
+
+
+def test_any_alignment_form_on_tiny_blocks(torch):
+    """The same form forced onto blocks of 16 .. 300 bytes: blocks that end before the first line boundary, pieces
+    of single bytes only, a last piece of one byte."""
+    sb.sparbit_tune("realign_min_bytes", 16)
+    for p, B, mis in ((128, 16, 1), (128, 16, 120), (128, 17, 100), (128, 33, 1), (64, 50, 0), (128, 127, 1), (128, 129, 127),
+                      (128, 300, 120), (128, 16, 8), (128, 31, 113), (128, 145, 0), (64, 256 + 2, 126)):
+        assert p * B % 128 == 0
+        for in_place in (False, True):
+            announce("tree any alignment, tiny", p, B, mis, in_place)
+            send = workloads.make_send_raw(p, B, seed=B + mis)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place, misalign=mis)
+            assert launched_any_alignment_form() or (B % 128 == 0 and mis == 0), sb.sparbit_last_launch_info()
+            assert np.array_equal(got, want), (p, B, mis, in_place)
+
+
+def test_rows_off_the_lines(torch):
+    """Rows that are not a multiple of 128 bytes apart: the any-alignment form's stores then cover part-lines, so it
+    stores plainly, and AUTO uses it only up to a total size; beyond that AUTO launches per step and the explicit
+    mode runs narrow elements.  All match the oracle."""
+    for p, B in ((125, 4100), (33, 1000), (61, 65552), (13, (1 << 18) + 1)):
+        for limit in (512 << 20, 0):
+            sb.sparbit_tune("tree_part_line_max_bytes", limit)
+            for mode in (sb.MODE_AUTO, sb.MODE_TREE):
+                announce("tree rows off lines", p, B, limit, mode)
+                send = workloads.make_send_raw(p, B, seed=B)
+                want = oracle_result(sb.SPARBIT, p, B, send)
+                got = gpu_result(torch, sb.SPARBIT, p, B, send, mode)
+                name = sb.sparbit_last_launch_info()[0]
+                if limit:
+                    assert launched_any_alignment_form() and ", 8, 0, " in name, name  # store form 0: plain
+                else:
+                    assert not launched_any_alignment_form(), name
+                    assert ("tree_kernel" in name) == (mode == sb.MODE_TREE or B % 16 == 0 and B < 65536), name
+                assert np.array_equal(got, want), (p, B, limit, mode)
+
+
+@pytest.mark.parametrize("extra", [4, 1])
+def test_any_alignment_form_at_full_size(torch, extra):
+    """128 ranks with blocks of 1 MiB + 4 bytes and 1 MiB + 1 byte (16 GiB of receive buffers), as AUTO launches
+    them and as the benchmark times them: every slot of every rank is compared on the device with the block the
+    oracle says it must hold (oracle run on rank tags), sampled slots on the host, and the bytes behind the
+    receive buffers must be untouched."""
+    from test_gpu_parity import expected_origins
+    p, B = 128, (1 << 20) + extra
+    announce("any alignment at full size", p, B)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(workloads.DEFAULT_SEED + extra)
+    d_send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev, generator=gen)
+    raw = torch.full((p * p * B + 256,), POISON, dtype=torch.uint8, device=dev)
+    d_recv = raw[:p * p * B].view(p, p, B)
+    sb.sparbit_allgather(d_send, d_recv, p, B)
+    torch.cuda.synchronize()
+    assert launched_any_alignment_form(), sb.sparbit_last_launch_info()
+    origin = expected_origins(p)
+    for r in range(p):
+        idx = torch.from_numpy(origin[r].astype(np.int64)).to(dev)
+        assert torch.equal(d_recv[r], d_send[idx]), ("final", r)
+    assert bool((raw[p * p * B:] == POISON).all())
+    send = d_send.cpu().numpy()
+    rng = np.random.default_rng(11)
+    for r, k in zip(rng.integers(0, p, 16), rng.integers(0, p, 16)):
+        assert np.array_equal(d_recv[r, k].cpu().numpy(), send[origin[r, k]])
 
 
 def test_refusals(torch):
