@@ -248,6 +248,9 @@ def sweep(torch, sb, workloads, stream, path):
         ps = [int(x) for x in os.environ["SPARBIT_SWEEP_PS"].split(",")]
     if os.environ.get("SPARBIT_SWEEP_SIZES"):
         sizes = [int(x) for x in os.environ["SPARBIT_SWEEP_SIZES"].split(",")]
+    off_grid_bases = [1 << 10, 1 << 14, 1 << 18, 1 << 20]
+    if os.environ.get("SPARBIT_SWEEP_OFF_GRID_BASES") is not None:  # "" = none
+        off_grid_bases = [int(x) for x in os.environ["SPARBIT_SWEEP_OFF_GRID_BASES"].split(",") if x]
     algos = [("sparbit", sb.SPARBIT, sb.MODE_AUTO), ("sparbit_per_step", sb.SPARBIT, sb.MODE_PER_STEP),
              ("ring", sb.RING, sb.MODE_AUTO), ("recursive_doubling", sb.RECURSIVE_DOUBLING, sb.MODE_AUTO),
              ("bruck", sb.BRUCK, sb.MODE_AUTO), ("direct", sb.DIRECT, sb.MODE_AUTO)]
@@ -303,6 +306,27 @@ def sweep(torch, sb, workloads, stream, path):
                                 r_.fill_(workloads.POISON)
                             torch.cuda.synchronize()
                         del s_, r_
+            # Block sizes off the 16-byte / 128-byte grid (the paper's ladder has powers of two only; MPI counts are
+            # arbitrary): Sparbit as AUTO issues it, per step, and the two schedules that share its launch count.
+            for base in off_grid_bases:
+                for extra in (1, 4, 16):
+                    B = base + extra
+                    if p * p * B > (32 << 30):
+                        continue
+                    send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev)
+                    recv = torch.full((p, p, B), workloads.POISON, dtype=torch.uint8, device=dev)
+                    for label, algo, md in algos:
+                        if label in ("ring", "direct") or (algo == sb.RECURSIVE_DOUBLING and p & (p - 1)):
+                            continue
+                        fn = lambda: sb.sparbit_allgather_mode(send, recv, p, B, algo, md, stream)
+                        t = time_calls(torch, fn, stream, 3, 10)
+                        ok = bool(torch.equal(recv, send.unsqueeze(0).expand(p, p, B))) if p * p * B <= (1 << 28) \
+                            else bool(torch.equal(recv[p - 1], send))
+                        emit(p, B, label, t, ok, off_grid=True, kernel=sb.sparbit_last_launch_info()[0],
+                             rows_on_lines=(p * B) % 128 == 0)
+                        recv.fill_(workloads.POISON)
+                        torch.cuda.synchronize()
+                    del send, recv
             print(f"sweep: p={p} done ({n} cases)", file=sys.stderr, flush=True)
             torch.cuda.empty_cache()
     return n
@@ -314,7 +338,11 @@ def sweep_summary(path):
     rows = [json.loads(l) for l in open(path)]
     assert all(r["ok"] for r in rows), "a case of the sweep failed its result check"
     by = collections.defaultdict(dict)
+    off = collections.defaultdict(dict)
     for r in rows:
+        if r.get("off_grid"):
+            off[(r["p"], r["block_bytes"])][r["algo"]] = r
+            continue
         if "row_pad" in r:
             by[(r["p"], r["block_bytes"])][f"{r['algo']}+{r['row_pad']}"] = r["avg_us"]
         else:
@@ -382,6 +410,22 @@ def sweep_summary(path):
                        f"{g('sparbit_padded_rows+128')} | {g('sparbit_padded_rows+256')} | "
                        f"{g('sparbit_per_step_padded_rows+128')} | {g('sparbit_per_step_padded_rows+256')} | "
                        f"{g('recursive_doubling_padded_rows+128')} | {g('recursive_doubling_padded_rows+256')} |")
+    if off:
+        out.append("\n## Block sizes off the 16-byte / 128-byte grid: microseconds per call\n")
+        out.append("Rows on lines: p * bytes is a multiple of 128, so every rank's receive buffer lies the same way "
+                   "relative to the 128-byte lines.  Form: what AUTO launched (tree* = the tree kernel's any-alignment "
+                   "form, tree = its other forms, steps = one launch per step, flow = dataflow launches).\n")
+        out.append("| p | bytes | rows on lines | form | Sparbit AUTO | Sparbit per step | AUTO / per step | Recursive Doubling | Bruck |")
+        out.append("|---|---|---|---|---|---|---|---|---|")
+        for (p, s), c in sorted(off.items()):
+            k = c["sparbit"]["kernel"]
+            form = ("tree*" if k.endswith(", true>") else "tree") if "tree_kernel" in k else \
+                "flow" if "dataflow" in k else "steps"
+            g = lambda a: f"{c[a]['avg_us']:.0f}" if a in c else ""
+            base = 1 << (s.bit_length() - 1)
+            out.append(f"| {p} | {_size_label(base)}+{s - base} | {'yes' if c['sparbit']['rows_on_lines'] else 'no'} | {form} | "
+                       f"{g('sparbit')} | {g('sparbit_per_step')} | "
+                       f"{c['sparbit']['avg_us'] / c['sparbit_per_step']['avg_us']:.2f} | {g('recursive_doubling')} | {g('bruck')} |")
     return "\n".join(out) + "\n"
 
 

@@ -301,9 +301,9 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  *   "tree_auto"            0/1: AUTO runs whole Sparbit calls as the tree kernel (default 1)
- *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 4, 3,
- *                          2 or 3 as the grid has fewer than 2048, 4096, 8192, or more wavefronts)
- *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead
+ *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 5, 4,
+ *                          3, 2 or 3 as the grid has fewer than 1024, 2048, 4096, 8192, or more wavefronts)
+ *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)
  *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1 or 2
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
  *                          and write-through to the others

@@ -113,7 +113,7 @@ std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idl
 std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
-std::atomic<long long> g_tree_small_bytes{64ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
+std::atomic<long long> g_tree_small_bytes{96ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
 std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
 std::atomic<long long> g_tree_store{2};                       // its stores: 0 plain, 2 write-through, 3 by destination
 std::atomic<long long> g_tree_prefetch{1};                    // it loads the next run's first rank ahead
@@ -679,8 +679,9 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     // How the tree is walked (all measured on MI355X, see the kernel's comment for the terms):
     //  - jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips;
     //  - otherwise short runs, which keep a slot's read close to its write; the fewer wavefronts the grid has, the
-    //    longer the runs, for more loads in flight per wavefront (p = 256, 4 KiB: 57 us with runs of 16, 67 us with
-    //    runs of 4; p = 64, 64 KiB: 52 us with runs of 8, 48 us with runs of 4);
+    //    longer the runs, for more loads in flight per wavefront (p = 256, 2 KiB: 38 us with runs of 32, 43 us with
+    //    runs of 16, 54 us with runs of 4; p = 256, 4 KiB: 55 us with runs of 16, 64 us with runs of 4; p = 64,
+    //    64 KiB: 52 us with runs of 8, 47 us with runs of 4);
     //  - when the grid has more wavefronts than the GPU holds, 11 resident ones per compute unit are enough to keep
     //    the memory side busy, and fewer resident wavefronts mean fewer bytes between a write and its read-back:
     //    each wavefront then reserves an eleventh of the unit's LDS, and the runs are 8 ranks (p = 128, 1 MiB:
@@ -690,7 +691,8 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     const bool capped = waves >= 8192;
     const long long run_knob = g_tree_run_log2.load();
     a.lg_k = run_knob >= 0 ? uint32_t(run_knob)
-                           : small ? uint32_t(ceil_log2(p)) : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
+                           : small ? uint32_t(ceil_log2(p))
+                           : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
     const long long lds_knob = g_tree_lds_bytes.load();
     const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? 14336u : 0u;
@@ -739,7 +741,12 @@ int tree_form(bool asked_for, int w, bool whole_lines, uint64_t row_bytes, size_
         // 125, B = 1 MiB + 4: 5.6 against 5.0 ms).
         if (total_bytes <= uint64_t(g_tree_part_line_max_bytes.load())) return 0;
     }
-    if (w == 16) return (asked_for || longest < size_t(g_line_align_min_bytes.load())) ? 16 : -1;
+    // On the 16-byte grid but off the lines, and not taken above: with write-through stores of part-lines the tree
+    // form loses to one launch per step (p = 253, B = 16 KiB + 16, 1 GiB: 526 against 389 us).
+    if (w == 16) {
+        const bool as_before = g_tree_any_align.load() == 0 && longest < size_t(g_line_align_min_bytes.load());
+        return (asked_for || !longish || as_before) ? 16 : -1;
+    }
     // single-byte accesses only up to 128 ranks (a lane walks its tree byte by byte: p = 256, B = 1: 47 us against
     // 39 us step by step)
     if (!longish) return (asked_for || w == 4 || p <= 128) ? w : -1;

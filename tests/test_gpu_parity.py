@@ -711,7 +711,7 @@ def test_randomized_cases(torch):
         if algo == sb.SPARBIT and rng.integers(0, 3) == 0:
             mode = "tree"
             sb.sparbit_tune("tree_run_log2", int(rng.integers(0, 8)))
-            sb.sparbit_tune("tree_small_bytes", [0, 64 << 20][rng.integers(2)])
+            sb.sparbit_tune("tree_small_bytes", [0, 96 << 20][rng.integers(2)])
             sb.sparbit_tune("tree_unroll", [1, 2][rng.integers(2)])
             sb.sparbit_tune("tree_store", [0, 2, 3][rng.integers(3)])
             sb.sparbit_tune("tree_prefetch", int(rng.integers(0, 2)))
@@ -728,7 +728,7 @@ def test_randomized_cases(torch):
             sb.sparbit_tune("hybrid_max_items", 512)
             sb.sparbit_tune("dataflow_max_items", 256)
             sb.sparbit_tune("tree_run_log2", -1)
-            sb.sparbit_tune("tree_small_bytes", 64 << 20)
+            sb.sparbit_tune("tree_small_bytes", 96 << 20)
             sb.sparbit_tune("tree_unroll", 1)
             sb.sparbit_tune("tree_store", 2)
             sb.sparbit_tune("tree_prefetch", 1)

@@ -12,7 +12,7 @@ from test_gpu_parity import POISON, announce, gpu_buffers, gpu_result, oracle_re
 
 pytestmark = pytest.mark.gpu
 
-DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 64 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
+DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 96 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
             "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
             "tree_part_line_max_bytes": 512 << 20}
 
@@ -55,7 +55,7 @@ def test_piece_sizes_and_store_forms(torch, unroll, store):
     sb.sparbit_tune("tree_unroll", unroll)
     sb.sparbit_tune("tree_store", store)
     sb.sparbit_tune("tree_lds_bytes", 10240 if store == 2 else 0)
-    for small in (0, 64 << 20):
+    for small in (0, 96 << 20):
         sb.sparbit_tune("tree_small_bytes", small)
         for p, B, in_place in ((6, 1024, False), (21, 5008, False), (33, 2048 + 1024 * unroll + 16, True),
                                (96, 4096, False), (64, 65536, False), (257, 48, True), (13, 1 << 18, False)):
