@@ -57,9 +57,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
     ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
-        (20492913475, "profiles/tree_kernel_cfg4_cfg5.md"),
+        (20559675717, "profiles/tree_kernel_cfg4_cfg5.md"),
     ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
-        (20332541905, "profiles/tree_kernel_cfg4_cfg5.md"),
+        (20402495243, "profiles/tree_kernel_cfg4_cfg5.md"),
+    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true>"):
+        (20356496069, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
 
