@@ -56,11 +56,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
         (20559675717, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
         (20402495243, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true>"):
+    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false>"):
         (20356496069, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
@@ -119,11 +119,14 @@ def make_device_send(torch, w, dev):
 
 def algorithmic_bytes(form, p, B):
     """HBM bytes one call has to move, by the form it is issued in (see the module docstring).
-    `form`: "per_step" (also persistent / dataflow: every forward reads what an earlier phase wrote), "tree",
+    `form`: "per_step" (also persistent / dataflow: every forward reads what an earlier phase wrote), "tree"
+    (Sparbit: a forwarder is read back right after it was written), "tree_doubling" (Recursive Doubling in that form),
     "direct" (every slot straight from the send buffer), "copy" (a device-to-device copy of p*p*B bytes)."""
     landed = p * p * B
     if form in ("tree", "direct"):
         return p * B + landed
+    if form == "tree_doubling":  # a forwarder is read a whole step after it was written: p/2 - 1 reads per tree
+        return p * B + landed + (p // 2 - 1) * p * B if p > 1 else 2 * B
     return 2 * landed
 
 
@@ -132,7 +135,15 @@ def form_of(kernel_name, algo_label="sparbit"):
         return "direct"
     if algo_label == "memcpy_d2d":
         return "copy"
-    return "tree" if "tree_kernel" in kernel_name else "per_step"
+    if "tree_kernel" in kernel_name:
+        return "tree_doubling" if tree_kernel_flags(kernel_name)["doubling"] else "tree"
+    return "per_step"
+
+
+def tree_kernel_flags(kernel_name):
+    """The last two template arguments of the tree kernel's name as the library reports it."""
+    args = kernel_name.rstrip(">").split(", ")
+    return {"any_alignment": args[-2] == "true", "doubling": args[-1] == "true"}
 
 
 def rates(p, B, ms, form):
@@ -421,7 +432,7 @@ def sweep_summary(path):
         out.append("|---|---|---|---|---|---|---|---|---|")
         for (p, s), c in sorted(off.items()):
             k = c["sparbit"]["kernel"]
-            form = ("tree*" if k.endswith(", true>") else "tree") if "tree_kernel" in k else \
+            form = ("tree*" if tree_kernel_flags(k)["any_alignment"] else "tree") if "tree_kernel" in k else \
                 "flow" if "dataflow" in k else "steps"
             g = lambda a: f"{c[a]['avg_us']:.0f}" if a in c else ""
             base = 1 << (s.bit_length() - 1)

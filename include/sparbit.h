@@ -92,7 +92,7 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit: TREE, except for blocks of 512 bytes and more that are
+#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit and Recursive Doubling: TREE, except for blocks of 512 bytes and more that are
                                      off the 128-byte grid in rows (p * block_bytes) that are off it too, when the
                                      call is larger than 512 MiB (and, below 64 KiB per block, off the 16-byte
                                      grid).  Everything else: DATAFLOW for
@@ -112,9 +112,10 @@ extern "C" {
                                      first; a call with more than 2^24 - 1 items is refused (SPARBIT_ERR_UNSUPPORTED).
                                      Their waits are bounded all the same (see sparbit_barrier_timeouts).
                                      PER_STEP and TREE never wait on the device. */
-#define SPARBIT_MODE_TREE 4       /* Sparbit only, whole calls only: one launch in which every wavefront carries one
-                                     piece of one block through that block's binomial tree (Section III-B: the p
-                                     trees are independent).  Same messages as Algorithm 1, each read from the
+#define SPARBIT_MODE_TREE 4       /* Sparbit and Recursive Doubling, whole calls only: one launch in which every
+                                     wavefront carries one piece of one block through that block's binomial tree
+                                     (Section III-B: the p trees are independent; Recursive Doubling's messages,
+                                     seen by block, form such trees too, with rank xor origin as the relative rank).  Same messages as Algorithm 1, each read from the
                                      forwarder's receive buffer; a forwarder's reads of one slot for different steps
                                      are merged, and the order is any order in which a rank forwards after it
                                      received.  No table, flag, barrier or device state: nothing waits.
@@ -198,7 +199,8 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  *               buffer is defined for equal blocks).
  * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
- * Sparbit goes out as ONE launch of the tree form (SPARBIT_MODE_TREE), which
+ * Sparbit and Recursive Doubling go out as ONE launch of the tree form
+ * (SPARBIT_MODE_TREE), which
  * reads each block's length and offset from the geometry's device copy, under
  * the same rules as equal blocks: counts and displs of any granularity run at
  * the full rate when row_bytes is a multiple of 128 (round the rows up where
@@ -301,6 +303,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "line_align_min_bytes" so do blocks at least this long that are on the 16-byte grid but off the 128-byte one (>= 16)
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  *   "tree_auto"            0/1: AUTO runs whole Sparbit calls as the tree kernel (default 1)
+ *   "tree_auto_doubling"   0/1: ... and whole Recursive Doubling calls too (default 1; needs tree_auto)
  *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 5, 4,
  *                          3, 2 or 3 as the grid has fewer than 1024, 2048, 4096, 8192, or more wavefronts)
  *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)

@@ -112,6 +112,7 @@ std::atomic<long long> g_line_align_min_bytes{64ll << 10};    // 16-byte-aligned
 std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idle workgroups one launch per step may cost before size classes pay
 std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
+std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
 std::atomic<long long> g_tree_small_bytes{96ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
 std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
@@ -614,14 +615,18 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
 }
 
 // The tree kernel: one wavefront per (tree, piece of 64 * U vectors).
-template <typename V, int U, int NB, bool VAR, bool ANY = false>
+template <typename V, int U, int NB, bool VAR, bool ANY = false, bool DOUBLING = false>
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream)
 {
     if (sizeof(V) != 16) store_kind = 0;
-    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR), bool_label(ANY));
-#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY>), grid, dim3(64), lds, stream, a)
-    if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
+    if (DOUBLING) prefetch = false;
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY), bool_label(DOUBLING));
+#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, DOUBLING>), grid, dim3(64), lds, stream, a)
+    if constexpr (DOUBLING) {  // no look-ahead, and of the store forms plain and write-through
+        if (store_kind != 0) SB_TREE(2, false);
+        else SB_TREE(0, false);
+    } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
         if (store_kind != 0 && prefetch) SB_TREE(2, true);
         else if (store_kind != 0) SB_TREE(2, false);
         else if (prefetch) SB_TREE(0, true);
@@ -647,7 +652,7 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
 // call's addresses and lengths allow; 0 asks for the any-alignment form (16-byte chunks cut relative to the
 // 128-byte lines, single bytes at a block's ends).  *eligible stays false when the piece count does not fit a grid
 // (blocks of several GiB): the caller falls back to per-step launches.
-int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t row_bytes, const uint64_t* counts,
+int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B, size_t row_bytes, const uint64_t* counts,
                 const uint64_t* displs, uint64_t total_bytes, int width, hipStream_t stream, bool* eligible)
 {
     *eligible = false;
@@ -656,7 +661,7 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
         return SPARBIT_OK;
     }
     const bool any = width == 0;
-    int U = width == 16 ? int(g_tree_unroll.load()) : 1;
+    int U = width == 16 && algo == SPARBIT_ALGO_SPARBIT ? int(g_tree_unroll.load()) : 1;
     const uint64_t vpb = any ? 0 : B / size_t(width);
     while (U > 1 && vpb <= uint64_t(64 * (U / 2))) U /= 2;  // short blocks: no lanes that only idle
     // any-alignment form: up to 127 bytes ahead of the first line boundary, then 1 KiB pieces
@@ -695,7 +700,10 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
                            : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
     const long long lds_knob = g_tree_lds_bytes.load();
-    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? 14336u : 0u;
+    // Recursive Doubling has no read that follows its write closely, so more resident wavefronts only help:
+    // 20 per unit (p = 128, 1 MiB: 4.61 ms; 11 per unit 4.99 ms; uncapped 4.66 ms).
+    const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
+    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
     int st = int(g_tree_store.load());
     // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
@@ -704,6 +712,18 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     if (any && row_bytes % 128 != 0) st = 0;
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
+    if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING) {  // one vector per lane, step order
+        if (counts) {
+            if (any) return launch_tree_vu<u32x4, 1, 8, true, true, true>(a, grid, st, pf, lds, total_bytes, stream);
+            if (width == 16) return launch_tree_vu<u32x4, 1, 8, true, false, true>(a, grid, st, pf, lds, total_bytes, stream);
+            if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+            return launch_tree_vu<uint8_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+        }
+        if (any) return launch_tree_vu<u32x4, 1, 8, false, true, true>(a, grid, st, pf, lds, total_bytes, stream);
+        if (width == 16) return launch_tree_vu<u32x4, 1, 8, false, false, true>(a, grid, st, pf, lds, total_bytes, stream);
+        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+        return launch_tree_vu<uint8_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+    }
     if (counts) {
         if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream);
         if (width == 16) {
@@ -720,6 +740,14 @@ int launch_tree(const void* sendbufs, void* recvbufs, int p, size_t B, size_t ro
     }
     if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
     return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
+}
+
+// AUTO runs whole calls of this schedule as the tree kernel where tree_form() finds a form for them.
+bool auto_takes_tree_form(int algo)
+{
+    if (algo == SPARBIT_ALGO_SPARBIT) return g_tree_auto.load() != 0;
+    if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING) return g_tree_auto.load() != 0 && g_tree_auto_doubling.load() != 0;
+    return false;
 }
 
 // Which form of the tree kernel serves a whole Sparbit call: 16, 4 or 1 = that access width with the pieces cut
@@ -1005,9 +1033,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     }
     total_bytes *= uint64_t(p);
     // Sparbit as the tree kernel, by the same rules as for equal blocks.
-    const int form = algo == SPARBIT_ALGO_SPARBIT && g_tree_auto.load() != 0
-                         ? tree_form(false, width, (bits & 127) == 0, row_bytes, longest, total_bytes, p)
-                         : -1;
+    const int form = auto_takes_tree_form(algo) ? tree_form(false, width, (bits & 127) == 0, row_bytes, longest, total_bytes, p)
+                                                : -1;
     const bool tree = form >= 0;
     // Equal blocks at their packed positions in rows that are longer than p blocks (padded rows): the equal-block
     // tree kernel takes the row length as it is, and needs no table at all.
@@ -1016,8 +1043,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     if (padded) {
         tl_launch_info = LaunchInfo();
         bool eligible = false;
-        const int trc = launch_tree(sendbufs, recvbufs, p, counts[0], row_bytes, nullptr, nullptr, total_bytes, form, stream,
-                                    &eligible);
+        const int trc = launch_tree(algo, sendbufs, recvbufs, p, counts[0], row_bytes, nullptr, nullptr, total_bytes, form,
+                                    stream, &eligible);
         if (trc != SPARBIT_OK || eligible) return trc;
     }
 
@@ -1033,8 +1060,8 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     const bool on_lines = (bits & 127) == 0;  // every block starts and ends on a 128-byte line
     if (tree) {  // sizes and offsets come from the geometry's device copy
         bool eligible = false;
-        const int trc = launch_tree(sendbufs, recvbufs, p, longest, row_bytes, vp->d_geometry, vp->d_geometry + p, total_bytes, form, stream,
-                                    &eligible);
+        const int trc = launch_tree(algo, sendbufs, recvbufs, p, longest, row_bytes, vp->d_geometry, vp->d_geometry + p,
+                                    total_bytes, form, stream, &eligible);
         if (trc != SPARBIT_OK || eligible) return trc;
     }
 
@@ -1148,16 +1175,16 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
 
     // The tree kernel needs no table, no flag and no state, so it is decided before anything is looked up or built
     // (and a capturing stream can record it like any other launch).
-    if (mode == SPARBIT_MODE_TREE && (algo != SPARBIT_ALGO_SPARBIT || !whole)) return SPARBIT_ERR_UNSUPPORTED;
-    if (whole && algo == SPARBIT_ALGO_SPARBIT &&
-        (mode == SPARBIT_MODE_TREE || (mode == SPARBIT_MODE_AUTO && g_tree_auto.load() != 0))) {
+    const bool has_tree_form = algo == SPARBIT_ALGO_SPARBIT || algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
+    if (mode == SPARBIT_MODE_TREE && (!has_tree_form || !whole)) return SPARBIT_ERR_UNSUPPORTED;
+    if (whole && has_tree_form && (mode == SPARBIT_MODE_TREE || (mode == SPARBIT_MODE_AUTO && auto_takes_tree_form(algo)))) {
         const int w = access_width(sendbufs, recvbufs, nullptr, B);
         const bool whole_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0;
         const int form = tree_form(mode == SPARBIT_MODE_TREE, w, whole_lines, uint64_t(p) * B, B, recv_bytes, p);
         if (form >= 0) {
             bool eligible = false;
-            const int trc = launch_tree(sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, form, stream,
-                                        &eligible);
+            const int trc = launch_tree(algo, sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, form,
+                                        stream, &eligible);
             if (trc != SPARBIT_OK || eligible) return trc;
             if (mode == SPARBIT_MODE_TREE) return SPARBIT_ERR_UNSUPPORTED;  // blocks of several GiB
         }
@@ -1562,6 +1589,8 @@ int sparbit_tune(const char* key, long long value)
         g_realign_min_bytes = value;
     } else if (!std::strcmp(key, "tree_auto")) {
         g_tree_auto = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_auto_doubling")) {
+        g_tree_auto_doubling = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_run_log2")) {
         if (value < -1 || value > 12) return SPARBIT_ERR_ARG;
         g_tree_run_log2 = value;

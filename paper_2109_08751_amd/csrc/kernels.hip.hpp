@@ -206,10 +206,18 @@ struct Held {
 // a multiple of 128 bytes apart) every store covers whole lines; elsewhere the same accesses are unaligned, which the
 // target's buffer loads and stores accept.  A piece is a run of 16-byte chunks, one per lane, and, at the block's
 // first and last piece, up to 15 single bytes, one per lane.
-template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false>
+//
+// DOUBLING: the same form for Recursive Doubling (Section II-A; p a power of two).  Seen by block, that schedule is
+// a binomial tree as well, with the distances in the opposite order and the rank found by exclusive-or: with rho =
+// rank xor b, step s sends from every rho < 2^s to rho + 2^s.  So rho receives in the step of its highest set bit and
+// forwards in every later step, i.e. every rho below p/2 forwards and its destinations are far away.  The walk is
+// the step order: the ranks that received in one step are loaded in batches and each is stored to all its
+// destinations; the runs of the Sparbit walk have no counterpart (a rank's first forward is a whole step later).
+template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, bool DOUBLING = false>
 __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
 {
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
+    static_assert(!DOUBLING || !PF, "the doubling walk has no run to look ahead of");
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
     if (b >= a.p) return;
@@ -245,7 +253,7 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
     // The piece of slot b held by the rank at relative rank rho (wave-uniform).  No __restrict__ anywhere: a slot
     // is written and later read.
     auto slot = [&](uint32_t rho) -> uint8_t* {
-        uint32_t r = b + rho;
+        uint32_t r = DOUBLING ? (b ^ rho) : b + rho;
         if (r >= p) r -= p;
         return a.recv + uint64_t(r) * a.row_bytes + offset;
     };
@@ -304,6 +312,23 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
         store(slot(0), xh, false);  // own-block placement; read again only in an in-place call
     } else {
         load(slot(0), xh);
+    }
+    if constexpr (DOUBLING) {
+        for (uint32_t d = 1; d < p; d <<= 1) store(slot(d), xh, false);  // the origin sends in every step
+        for (uint32_t lvl = 1; 2 * lvl < p; lvl <<= 1) {  // rho in [lvl, 2 lvl) received in the step with distance lvl
+            for (uint32_t n0 = lvl; n0 < 2 * lvl; n0 += NB) {
+                H x[NB];
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
+                    if (n0 + i < 2 * lvl) load(slot(n0 + i), x[i]);
+                wait_for_loads();
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
+                    if (n0 + i < 2 * lvl)
+                        for (uint32_t d = 2 * lvl; d < p; d <<= 1) store(slot(n0 + i + d), x[i], false);
+            }
+        }
+        return;
     }
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;

@@ -79,7 +79,7 @@ def test_narrow_accesses(torch):
 
 def launched_any_alignment_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.endswith(", true>")
+    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "true"
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_small_bytes": 0, "tree_run_log2": 0, "tree_prefetch": 0},
@@ -172,10 +172,63 @@ def test_any_alignment_form_at_full_size(torch, extra):
         assert np.array_equal(d_recv[r, k].cpu().numpy(), send[origin[r, k]])
 
 
+def launched_doubling_form():
+    name = sb.sparbit_last_launch_info()[0]
+    return "tree_kernel" in name and name.endswith(", true>")
+
+
+@pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}])
+def test_recursive_doubling_in_the_tree_form(torch, knobs):
+    """Recursive Doubling seen by block is a binomial tree as well (relative rank = rank xor origin, a rank forwards
+    in every step after the one it received in); the same one-launch form walks it in step order.  Every power of
+    two up to 256, blocks on and off the grids, in place, explicit mode and AUTO."""
+    for k, v in knobs.items():
+        sb.sparbit_tune(k, v)
+    for p in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+        for B, mis in ((16, 0), (1040, 0), (20, 0), (333, 1), (4100, 0), (4096, 4), (65552, 0)) if p <= 64 else ((1040, 0), (516, 0)):
+            for mode, in_place in ((sb.MODE_TREE, False), (sb.MODE_AUTO, False), (sb.MODE_TREE, True)):
+                announce("doubling tree", knobs, p, B, mis, mode, in_place)
+                send = workloads.make_send_raw(p, B, seed=p + B)
+                want = oracle_result(sb.RECURSIVE_DOUBLING, p, B, send, in_place=in_place)
+                got = gpu_result(torch, sb.RECURSIVE_DOUBLING, p, B, send, mode, in_place=in_place, misalign=mis)
+                if not (p == 1 and in_place):  # one rank in place: nothing moves, nothing is launched
+                    assert launched_doubling_form(), sb.sparbit_last_launch_info()
+                assert np.array_equal(got, want), (p, B, mis, mode, in_place)
+    with pytest.raises(sb.SparbitError) as e:  # not a power of two: no such schedule, in any form
+        d = torch.full((8192,), POISON, dtype=torch.uint8, device="cuda:0")
+        sb.sparbit_allgather_mode(d[:96], d[1024:], 6, 16, sb.RECURSIVE_DOUBLING, sb.MODE_TREE)
+    assert e.value.code == -3
+
+
+def test_recursive_doubling_in_the_tree_form_at_full_size(torch):
+    """cfg4's shape (128 ranks x 1 MiB, 16 GiB of receive buffers) as AUTO issues Recursive Doubling: every rank's
+    receive buffer is compared on the device with the Allgather definition (the final state the oracle's Recursive
+    Doubling is pinned to), sampled slots on the host."""
+    w = workloads.WORKLOADS["cfg4"]
+    p, B = w.p, w.block_bytes
+    announce("doubling tree at full size", p, B)
+    send = workloads.make_send(w)
+    dev = torch.device("cuda:0")
+    d_send = torch.from_numpy(send).to(dev)
+    d_recv = torch.full((p, p, B), POISON, dtype=torch.uint8, device=dev)
+    sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.RECURSIVE_DOUBLING, sb.MODE_AUTO)
+    torch.cuda.synchronize()
+    assert launched_doubling_form(), sb.sparbit_last_launch_info()
+    for r in range(p):
+        assert torch.equal(d_recv[r], d_send), r
+    small = workloads.make_send_raw(p, 4, seed=3)
+    want = oracle_result(sb.RECURSIVE_DOUBLING, p, 4, small)  # slot k of every rank holds rank k's block
+    assert all(np.array_equal(want[r], small) for r in range(p))
+    rng = np.random.default_rng(5)
+    for r, k in zip(rng.integers(0, p, 16), rng.integers(0, p, 16)):
+        assert np.array_equal(d_recv[r, k].cpu().numpy(), send.reshape(p, B)[k])
+
+
 def test_refusals(torch):
-    """The tree form is Sparbit's own structure: the other schedules, and step ranges, are refused."""
+    """The tree form exists for the two schedules whose messages form binomial trees per block and end in the
+    block's own slot, Sparbit and Recursive Doubling; the others, and step ranges, are refused."""
     d = torch.full((4096,), POISON, dtype=torch.uint8, device="cuda:0")
-    for algo in (sb.RING, sb.RECURSIVE_DOUBLING, sb.BRUCK, sb.DIRECT):
+    for algo in (sb.RING, sb.BRUCK, sb.DIRECT):
         with pytest.raises(sb.SparbitError) as e:
             sb.sparbit_allgather_mode(d[:64], d[1024:], 4, 16, algo, sb.MODE_TREE)
         assert e.value.code == -3
