@@ -57,11 +57,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
     ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
-        (20559675717, "profiles/tree_kernel_cfg4_cfg5.md"),
+        (20544415117, "profiles/tree_kernel_cfg4_cfg5.md"),
     ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
-        (20402495243, "profiles/tree_kernel_cfg4_cfg5.md"),
+        (20386839493, "profiles/tree_kernel_cfg4_cfg5.md"),
     ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false>"):
-        (20356496069, "profiles/tree_kernel_cfg4_cfg5.md"),
+        (20328322636, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
 
@@ -266,6 +266,7 @@ def sweep(torch, sb, workloads, stream, path):
         off_grid_bases = [int(x) for x in os.environ["SPARBIT_SWEEP_OFF_GRID_BASES"].split(",") if x]
     algos = [("sparbit", sb.SPARBIT, sb.MODE_AUTO), ("sparbit_per_step", sb.SPARBIT, sb.MODE_PER_STEP),
              ("ring", sb.RING, sb.MODE_AUTO), ("recursive_doubling", sb.RECURSIVE_DOUBLING, sb.MODE_AUTO),
+             ("recursive_doubling_per_step", sb.RECURSIVE_DOUBLING, sb.MODE_PER_STEP),
              ("bruck", sb.BRUCK, sb.MODE_AUTO), ("direct", sb.DIRECT, sb.MODE_AUTO)]
     n = 0
     with open(path, "w") as out:
@@ -329,7 +330,7 @@ def sweep(torch, sb, workloads, stream, path):
                     send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev)
                     recv = torch.full((p, p, B), workloads.POISON, dtype=torch.uint8, device=dev)
                     for label, algo, md in algos:
-                        if label in ("ring", "direct") or (algo == sb.RECURSIVE_DOUBLING and p & (p - 1)):
+                        if label in ("ring", "direct", "recursive_doubling_per_step") or (algo == sb.RECURSIVE_DOUBLING and p & (p - 1)):
                             continue
                         fn = lambda: sb.sparbit_allgather_mode(send, recv, p, B, algo, md, stream)
                         t = time_calls(torch, fn, stream, 3, 10)
@@ -410,6 +411,18 @@ def sweep_summary(path):
         for s in sizes:
             c = by.get((p, s))
             cells.append("" if not c or "recursive_doubling" not in c else f"{c['sparbit'] / c['recursive_doubling']:.2f}")
+        out.append(f"| {p} | " + " | ".join(cells) + " |")
+    out.append("\n## Recursive Doubling as AUTO issues it (tree form) / one launch per step\n")
+    out.append("| p \\ bytes | " + " | ".join(_size_label(s) for s in sizes) + " |")
+    out.append("|---|" + "---|" * len(sizes))
+    for p in ps:
+        if p & (p - 1):
+            continue
+        cells = []
+        for s in sizes:
+            c = by.get((p, s))
+            ok = c and "recursive_doubling" in c and "recursive_doubling_per_step" in c
+            cells.append(f"{c['recursive_doubling'] / c['recursive_doubling_per_step']:.2f}" if ok else "")
         out.append(f"| {p} | " + " | ".join(cells) + " |")
     padded = [(k, c) for k, c in sorted(by.items()) if any("+" in a for a in c)]
     if padded:
