@@ -56,11 +56,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"):
         (20544415117, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"):
         (20386839493, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false>"):
+    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false, false>"):
         (20328322636, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
@@ -141,9 +141,9 @@ def form_of(kernel_name, algo_label="sparbit"):
 
 
 def tree_kernel_flags(kernel_name):
-    """The last two template arguments of the tree kernel's name as the library reports it."""
+    """The last three template arguments of the tree kernel's name as the library reports it."""
     args = kernel_name.rstrip(">").split(", ")
-    return {"any_alignment": args[-2] == "true", "doubling": args[-1] == "true"}
+    return {"any_alignment": args[-3] == "true", "doubling": args[-2] == "true", "team": args[-1] == "true"}
 
 
 def rates(p, B, ms, form):

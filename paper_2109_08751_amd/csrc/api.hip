@@ -113,6 +113,7 @@ std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idl
 std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
+std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
 std::atomic<long long> g_tree_small_bytes{96ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
 std::atomic<long long> g_tree_unroll{1};                      // vectors per lane of the tree kernel (1, 2 or 4)
@@ -614,18 +615,31 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
     return SPARBIT_OK;
 }
 
-// The tree kernel: one wavefront per (tree, piece of 64 * U vectors).
+// The tree kernel: one wavefront, or with `team` > 1 that many, per (tree, piece of 64 * U vectors).
 template <typename V, int U, int NB, bool VAR, bool ANY = false, bool DOUBLING = false>
-int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream)
+int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream,
+                   uint32_t team = 1)
 {
     if (sizeof(V) != 16) store_kind = 0;
-    if (DOUBLING) prefetch = false;
-    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR), bool_label(ANY), bool_label(DOUBLING));
+    if (DOUBLING || team > 1) prefetch = false;
+    if (team > 1 && store_kind == 3) store_kind = 2;
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY), bool_label(DOUBLING), bool_label(team > 1));
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, DOUBLING>), grid, dim3(64), lds, stream, a)
+#define SB_TEAM(ST) \
+    hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, false, true>), grid, dim3(64 * team), lds, stream, a)
     if constexpr (DOUBLING) {  // no look-ahead, and of the store forms plain and write-through
         if (store_kind != 0) SB_TREE(2, false);
         else SB_TREE(0, false);
+    } else if constexpr (U == 1) {
+        if (team > 1) {
+            if (store_kind != 0) SB_TEAM(2);
+            else SB_TEAM(0);
+            SB_HIP(hipGetLastError());
+            return SPARBIT_OK;
+        }
+    }
+    if constexpr (DOUBLING) {
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
         if (store_kind != 0 && prefetch) SB_TREE(2, true);
         else if (store_kind != 0) SB_TREE(2, false);
@@ -643,6 +657,7 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
         else SB_TREE(0, false);
     }
 #undef SB_TREE
+#undef SB_TEAM
     SB_HIP(hipGetLastError());
     return SPARBIT_OK;
 }
@@ -699,6 +714,19 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
                            : small ? uint32_t(ceil_log2(p))
                            : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
+    // Calls that small are one wavefront's walk through the tree, ~100 ns of address arithmetic per rank: from 33
+    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: ? us against 27 us).
+    uint32_t team = 1;
+    if (algo == SPARBIT_ALGO_SPARBIT && U == 1) {
+        const long long team_knob = g_tree_team_log2.load();
+        const int lg_p = ceil_log2(p);
+        int lg_team = team_knob >= 0 ? int(team_knob) : (small && run_knob < 0 && p > 32) ? (p > 64 ? 3 : 2) : 0;
+        if (lg_team > lg_p - 1) lg_team = lg_p > 1 ? lg_p - 1 : 0;  // runs of at least 2 ranks
+        if (lg_team > 0) {
+            team = 1u << lg_team;
+            a.lg_k = uint32_t(lg_p - lg_team);
+        }
+    }
     const long long lds_knob = g_tree_lds_bytes.load();
     // Recursive Doubling has no read that follows its write closely, so more resident wavefronts only help:
     // 20 per unit (p = 128, 1 MiB: 4.61 ms; 11 per unit 4.99 ms; uncapped 4.66 ms).
@@ -725,21 +753,21 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
         return launch_tree_vu<uint8_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
     }
     if (counts) {
-        if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream);
+        if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
         if (width == 16) {
             if (U == 2) return launch_tree_vu<u32x4, 2, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
-            return launch_tree_vu<u32x4, 1, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
+            return launch_tree_vu<u32x4, 1, 8, true>(a, grid, st, pf, lds, total_bytes, stream, team);
         }
-        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
-        return launch_tree_vu<uint8_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream);
+        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
+        return launch_tree_vu<uint8_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
     }
-    if (any) return launch_tree_vu<u32x4, 1, 8, false, true>(a, grid, st, pf, lds, total_bytes, stream);
+    if (any) return launch_tree_vu<u32x4, 1, 8, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
     if (width == 16) {
         if (U == 2) return launch_tree_vu<u32x4, 2, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
-        return launch_tree_vu<u32x4, 1, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
+        return launch_tree_vu<u32x4, 1, 8, false>(a, grid, st, pf, lds, total_bytes, stream, team);
     }
-    if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
-    return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream);
+    if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream, team);
+    return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream, team);
 }
 
 // AUTO runs whole calls of this schedule as the tree kernel where tree_form() finds a form for them.
@@ -1591,6 +1619,9 @@ int sparbit_tune(const char* key, long long value)
         g_tree_auto = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_auto_doubling")) {
         g_tree_auto_doubling = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_team_log2")) {
+        if (value < -1 || value > 4) return SPARBIT_ERR_ARG;
+        g_tree_team_log2 = value;
     } else if (!std::strcmp(key, "tree_run_log2")) {
         if (value < -1 || value > 12) return SPARBIT_ERR_ARG;
         g_tree_run_log2 = value;

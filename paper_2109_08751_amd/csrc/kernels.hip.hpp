@@ -213,11 +213,25 @@ struct Held {
 // forwards in every later step, i.e. every rho below p/2 forwards and its destinations are far away.  The walk is
 // the step order: the ranks that received in one step are loaded in batches and each is stored to all its
 // destinations; the runs of the Sparbit walk have no counterpart (a rank's first forward is a whole step later).
-template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, bool DOUBLING = false>
-__global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
+//
+// TEAM: several wavefronts per workgroup share one piece of one tree, for calls so small that the time is one
+// wavefront's walk through all p ranks (its address arithmetic alone is ~100 ns per rank).  The tree is cut into
+// runs of K = 2^lg_k relative ranks, one per wavefront; a run's first rank receives from the first rank of an earlier
+// run, so the wavefront of that run stores it, waits until the store is done, and raises a flag in LDS, which the
+// receiving wavefront polls before it loads its first rank and walks its run as above.  The chain of such hand-overs
+// is log2(wavefronts) long.  A wavefront only ever waits for a wavefront of its own workgroup that waits for nothing
+// it has not received yet (the first run waits for nothing), so every wait ends; it is bounded all the same.
+constexpr uint32_t kTeamSpinLimit = 1u << 22;  // polls of ~100 cycles each
+
+template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, bool DOUBLING = false,
+          bool TEAM = false>
+__global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a)
 {
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
     static_assert(!DOUBLING || !PF, "the doubling walk has no run to look ahead of");
+    static_assert(!TEAM || (!PF && !DOUBLING && U == 1), "a team's wavefronts walk one run each, one vector per lane");
+    const uint32_t lane = TEAM ? (threadIdx.x & 63u) : threadIdx.x;
+    const uint32_t wave = TEAM ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
     if (b >= a.p) return;
@@ -248,7 +262,7 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
     }
     bool ok[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) ok[u] = threadIdx.x + uint32_t(u * 64) < piece_vectors;
+    for (int u = 0; u < U; ++u) ok[u] = lane + uint32_t(u * 64) < piece_vectors;
     typedef Held<V, U> H;
     // The piece of slot b held by the rank at relative rank rho (wave-uniform).  No __restrict__ anywhere: a slot
     // is written and later read.
@@ -262,14 +276,13 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
             const __amdgpu_buffer_rsrc_t rs = piece_buffer(s, piece_vectors * 16u);
 #pragma unroll
             for (int u = 0; u < U; ++u)
-                x.v[u] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, int(threadIdx.x * 16u + u * 1024u), 0, 0));
+                x.v[u] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, int(lane * 16u + u * 1024u), 0, 0));
             if constexpr (ANY) {
                 if (tail_bytes)
-                    x.tail = __builtin_amdgcn_raw_buffer_load_b8(piece_buffer(s + piece_vectors * 16u, tail_bytes),
-                                                                 int(threadIdx.x), 0, 0);
+                    x.tail = __builtin_amdgcn_raw_buffer_load_b8(piece_buffer(s + piece_vectors * 16u, tail_bytes), int(lane), 0, 0);
             }
         } else {
-            const V* sv = reinterpret_cast<const V*>(s) + threadIdx.x;
+            const V* sv = reinterpret_cast<const V*>(s) + lane;
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (ok[u]) x.v[u] = sv[u * 64];
@@ -281,7 +294,7 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
             typedef uint32_t raw4 __attribute__((ext_vector_type(4)));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int at = int(threadIdx.x * 16u + u * 1024u);
+                const int at = int(lane * 16u + u * 1024u);
                 const raw4 v = __builtin_bit_cast(raw4, x.v[u]);
                 if (ST == 0 || (ST == 3 && read_again_soon))
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
@@ -290,11 +303,11 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
             }
             if constexpr (ANY) {
                 if (tail_bytes)
-                    __builtin_amdgcn_raw_buffer_store_b8(x.tail, piece_buffer(d + piece_vectors * 16u, tail_bytes),
-                                                         int(threadIdx.x), 0, ST == 0 ? 0 : kBufferSc0Sc1);
+                    __builtin_amdgcn_raw_buffer_store_b8(x.tail, piece_buffer(d + piece_vectors * 16u, tail_bytes), int(lane), 0,
+                                                         ST == 0 ? 0 : kBufferSc0Sc1);
             }
         } else {
-            V* dv = reinterpret_cast<V*>(d) + threadIdx.x;
+            V* dv = reinterpret_cast<V*>(d) + lane;
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (ok[u]) dv[u * 64] = x.v[u];
@@ -306,6 +319,63 @@ __global__ __launch_bounds__(64) void tree_kernel(const TreeArgs a)
     auto send_to = [&](uint32_t rho, uint32_t d, const H& x) { store(slot(rho + d), x, d >= 2 && d <= K); };
     // A rank forwards if it is even in the tree and the next relative rank exists (its nearest destination).
     auto forwards = [&](uint32_t rho) { return (rho & 1u) == 0 && rho + 1 < p; };
+    if constexpr (TEAM) {
+        __shared__ uint32_t arrived[16];  // per run of the team: its first rank has been stored
+        if (lane == 0) arrived[wave] = 0;
+        __syncthreads();
+        const uint32_t first = wave << a.lg_k;  // this wavefront's run starts here
+        if (first >= p || (first != 0 && !forwards(first))) return;  // no such run, or nothing to forward in it
+        if (first != 0) {
+            uint32_t polls = 0;
+            while (__hip_atomic_load(&arrived[wave], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
+                if (++polls > kTeamSpinLimit) return;
+                __builtin_amdgcn_s_sleep(1);
+            }
+        }
+        // After its first rank's forwards a run's wavefront tells the runs whose first ranks it stored to.
+        auto hand_over = [&](uint32_t h, uint32_t dmax) {
+            if (dmax < K) return;
+            wait_for_loads();  // the stores are done
+            for (uint32_t d = dmax; d >= K; d >>= 1)
+                if (d < p - h && lane == 0)
+                    __hip_atomic_store(&arrived[(h + d) >> a.lg_k], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
+        H xt;
+        if (first == 0) {
+            if (a.send) {
+                load(a.send + offset, xt);
+                store(slot(0), xt, false);
+            } else {
+                load(slot(0), xt);
+            }
+        } else {
+            load(slot(first), xt);
+        }
+        const uint32_t dmax = first ? ((first & (0u - first)) >> 1) : a.top;
+        for (uint32_t d = dmax; d >= 1; d >>= 1)
+            if (d < p - first) send_to(first, d, xt);
+        hand_over(first, dmax);
+        const uint32_t end = (p - first < K) ? p : first + K;
+        for (uint32_t st = K >> 1; st >= 2; st >>= 1) {
+            for (uint32_t n0 = first + st; n0 < end; n0 += 2 * st * NB) {
+                H x[NB];
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const uint32_t n = n0 + 2 * st * i;
+                    if (n < end && forwards(n)) load(slot(n), x[i]);
+                }
+                wait_for_loads();
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const uint32_t n = n0 + 2 * st * i;
+                    if (n < end)
+                        for (uint32_t d = st >> 1; d >= 1; d >>= 1)
+                            if (d < p - n) send_to(n, d, x[i]);
+                }
+            }
+        }
+        return;
+    }
     H xh;  // the block as the run's first rank holds it
     if (a.send) {
         load(a.send + offset, xh);

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 96 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
             "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
-            "tree_part_line_max_bytes": 512 << 20}
+            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1}
 
 
 @pytest.fixture(scope="module")
@@ -79,7 +79,7 @@ def test_narrow_accesses(torch):
 
 def launched_any_alignment_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "true"
+    return "tree_kernel" in name and name.rstrip(">").split(", ")[-3] == "true"
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_small_bytes": 0, "tree_run_log2": 0, "tree_prefetch": 0},
@@ -172,9 +172,42 @@ def test_any_alignment_form_at_full_size(torch, extra):
         assert np.array_equal(d_recv[r, k].cpu().numpy(), send[origin[r, k]])
 
 
+@pytest.mark.parametrize("team_log2", [1, 2, 3, 4])
+def test_teams_of_wavefronts(torch, team_log2):
+    """Small calls: 2, 4, 8 or 16 wavefronts of one workgroup walk one run of a tree each and hand a run's first
+    rank over through a flag in LDS.  Rank counts around every power of two (runs that do not exist, runs whose first
+    rank has nothing to forward, a last run of one rank), all access widths, the any-alignment form, in place, with
+    plain and write-through stores; and what AUTO does by itself (teams from 33 ranks on in calls up to 96 MiB)."""
+    sb.sparbit_tune("tree_team_log2", team_log2)
+    for p in (1, 2, 3, 4, 5, 7, 8, 9, 15, 16, 17, 21, 31, 32, 33, 47, 48, 49, 63, 64, 65, 96, 97, 127, 128, 129, 255, 256, 257):
+        for B, mis in ((16, 0), (1040, 0), (100, 0), (333, 1), (4100, 0)) if p <= 65 else ((1040, 0), (513, 0)):
+            in_place = (p + B) % 3 == 0
+            sb.sparbit_tune("tree_store", 0 if (p + B) % 2 else 2)
+            announce("tree team", team_log2, p, B, mis, in_place)
+            send = workloads.make_send_raw(p, B, seed=p * 3 + team_log2)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place, misalign=mis)
+            name = sb.sparbit_last_launch_info()[0]
+            if p > 2 and not (p == 1 and in_place):
+                assert name.endswith(", true>"), name  # a team
+            assert np.array_equal(got, want), (team_log2, p, B, mis, in_place)
+
+
+def test_auto_forms_teams_for_small_calls_of_many_ranks(torch):
+    for p, B, team in ((32, 4096, False), (33, 4096, True), (96, 4096, True), (256, 1024, True), (257, 48, True),
+                       (128, 16384, False)):  # the last one is 256 MiB: past the size limit of the step-order walk
+        announce("tree team by itself", p, B)
+        send = workloads.make_send_raw(p, B, seed=p)
+        want = oracle_result(sb.SPARBIT, p, B, send)
+        got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_AUTO)
+        name = sb.sparbit_last_launch_info()[0]
+        assert "tree_kernel" in name and name.endswith(", true>") == team, name
+        assert np.array_equal(got, want), (p, B)
+
+
 def launched_doubling_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.endswith(", true>")
+    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "true"
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}])
