@@ -627,11 +627,8 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
                 bool_label(prefetch), bool_label(VAR), bool_label(ANY), bool_label(DOUBLING), bool_label(team > 1));
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, DOUBLING>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
-    hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, false, true>), grid, dim3(64 * team), lds, stream, a)
-    if constexpr (DOUBLING) {  // no look-ahead, and of the store forms plain and write-through
-        if (store_kind != 0) SB_TREE(2, false);
-        else SB_TREE(0, false);
-    } else if constexpr (U == 1) {
+    hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, DOUBLING, true>), grid, dim3(64 * team), lds, stream, a)
+    if constexpr (U == 1) {
         if (team > 1) {
             if (store_kind != 0) SB_TEAM(2);
             else SB_TEAM(0);
@@ -639,7 +636,9 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
             return SPARBIT_OK;
         }
     }
-    if constexpr (DOUBLING) {
+    if constexpr (DOUBLING) {  // no look-ahead, and of the store forms plain and write-through
+        if (store_kind != 0) SB_TREE(2, false);
+        else SB_TREE(0, false);
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
         if (store_kind != 0 && prefetch) SB_TREE(2, true);
         else if (store_kind != 0) SB_TREE(2, false);
@@ -717,14 +716,15 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // Calls that small are one wavefront's walk through the tree, ~100 ns of address arithmetic per rank: from 33
     // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: ? us against 27 us).
     uint32_t team = 1;
-    if (algo == SPARBIT_ALGO_SPARBIT && U == 1) {
+    if (U == 1) {
         const long long team_knob = g_tree_team_log2.load();
         const int lg_p = ceil_log2(p);
         int lg_team = team_knob >= 0 ? int(team_knob) : (small && run_knob < 0 && p > 32) ? (p > 64 ? 3 : 2) : 0;
-        if (lg_team > lg_p - 1) lg_team = lg_p > 1 ? lg_p - 1 : 0;  // runs of at least 2 ranks
+        if (lg_team > lg_p - 1) lg_team = lg_p > 1 ? lg_p - 1 : 0;  // at least 2 ranks per wavefront
         if (lg_team > 0) {
             team = 1u << lg_team;
-            a.lg_k = uint32_t(lg_p - lg_team);
+            // Sparbit: runs of 2^lg_k ranks, one per wavefront; Recursive Doubling: 2^lg_k sub-trees, by low bits
+            a.lg_k = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING ? uint32_t(lg_team) : uint32_t(lg_p - lg_team);
         }
     }
     const long long lds_knob = g_tree_lds_bytes.load();
@@ -742,15 +742,15 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     *eligible = true;
     if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING) {  // one vector per lane, step order
         if (counts) {
-            if (any) return launch_tree_vu<u32x4, 1, 8, true, true, true>(a, grid, st, pf, lds, total_bytes, stream);
-            if (width == 16) return launch_tree_vu<u32x4, 1, 8, true, false, true>(a, grid, st, pf, lds, total_bytes, stream);
-            if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
-            return launch_tree_vu<uint8_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+            if (any) return launch_tree_vu<u32x4, 1, 8, true, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
+            if (width == 16) return launch_tree_vu<u32x4, 1, 8, true, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
+            if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
+            return launch_tree_vu<uint8_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
         }
-        if (any) return launch_tree_vu<u32x4, 1, 8, false, true, true>(a, grid, st, pf, lds, total_bytes, stream);
-        if (width == 16) return launch_tree_vu<u32x4, 1, 8, false, false, true>(a, grid, st, pf, lds, total_bytes, stream);
-        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
-        return launch_tree_vu<uint8_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream);
+        if (any) return launch_tree_vu<u32x4, 1, 8, false, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
+        if (width == 16) return launch_tree_vu<u32x4, 1, 8, false, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
+        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
+        return launch_tree_vu<uint8_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
     }
     if (counts) {
         if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);

@@ -221,6 +221,7 @@ struct Held {
 // receiving wavefront polls before it loads its first rank and walks its run as above.  The chain of such hand-overs
 // is log2(wavefronts) long.  A wavefront only ever waits for a wavefront of its own workgroup that waits for nothing
 // it has not received yet (the first run waits for nothing), so every wait ends; it is bounded all the same.
+// Recursive Doubling's tree is cut by the low bits of the relative rank instead (see the kernel).
 constexpr uint32_t kTeamSpinLimit = 1u << 22;  // polls of ~100 cycles each
 
 template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, bool DOUBLING = false,
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
 {
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
     static_assert(!DOUBLING || !PF, "the doubling walk has no run to look ahead of");
-    static_assert(!TEAM || (!PF && !DOUBLING && U == 1), "a team's wavefronts walk one run each, one vector per lane");
+    static_assert(!TEAM || (!PF && U == 1), "a team's wavefronts walk one part of the tree each, one vector per lane");
     const uint32_t lane = TEAM ? (threadIdx.x & 63u) : threadIdx.x;
     const uint32_t wave = TEAM ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
@@ -319,7 +320,59 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     auto send_to = [&](uint32_t rho, uint32_t d, const H& x) { store(slot(rho + d), x, d >= 2 && d <= K); };
     // A rank forwards if it is even in the tree and the next relative rank exists (its nearest destination).
     auto forwards = [&](uint32_t rho) { return (rho & 1u) == 0 && rho + 1 < p; };
-    if constexpr (TEAM) {
+    if constexpr (TEAM && DOUBLING) {
+        // Recursive Doubling's tree splits by the low bits of rho: the ranks with rho mod W = c form the sub-tree of
+        // rho = c (every forward of a rank >= W adds a power of two >= W), W = 2^lg_k wavefronts, c = this one's
+        // number.  Rank c receives from rank c minus its highest set bit, which belongs to an earlier wavefront.
+        __shared__ uint32_t arrived[16];  // per wavefront: its sub-tree's first rank has been stored
+        if (lane == 0) arrived[wave] = 0;
+        __syncthreads();
+        const uint32_t W = 1u << a.lg_k, c = wave;
+        if (c >= W || 2 * W > p) return;  // the host launches W wavefronts, W <= p / 2
+        H xt;
+        if (c == 0) {
+            if (a.send) {
+                load(a.send + offset, xt);
+                store(slot(0), xt, false);
+            } else {
+                load(slot(0), xt);
+            }
+        } else {
+            uint32_t polls = 0;
+            while (__hip_atomic_load(&arrived[c], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) == 0) {
+                if (++polls > kTeamSpinLimit) return;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            load(slot(c), xt);
+        }
+        bool handed = false;
+        for (uint32_t d = 1; d < W; d <<= 1)  // the steps after the one c received in, while they leave the sub-tree
+            if (d > c) {
+                store(slot(c + d), xt, false);
+                handed = true;
+            }
+        if (handed) {
+            wait_for_loads();  // those stores are done
+            for (uint32_t d = 1; d < W; d <<= 1)
+                if (d > c && lane == 0)
+                    __hip_atomic_store(&arrived[c + d], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        for (uint32_t d = W; d < p; d <<= 1) store(slot(c + d), xt, false);
+        for (uint32_t lvl = W; 2 * lvl < p; lvl <<= 1) {  // the sub-tree's ranks that received at distance lvl
+            for (uint32_t n0 = c + lvl; n0 < 2 * lvl; n0 += W * NB) {
+                H x[NB];
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
+                    if (n0 + W * i < 2 * lvl) load(slot(n0 + W * i), x[i]);
+                wait_for_loads();
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
+                    if (n0 + W * i < 2 * lvl)
+                        for (uint32_t d = 2 * lvl; d < p; d <<= 1) store(slot(n0 + W * i + d), x[i], false);
+            }
+        }
+        return;
+    } else if constexpr (TEAM) {
         __shared__ uint32_t arrived[16];  // per run of the team: its first rank has been stored
         if (lane == 0) arrived[wave] = 0;
         __syncthreads();

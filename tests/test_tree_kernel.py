@@ -210,11 +210,13 @@ def launched_doubling_form():
     return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "true"
 
 
-@pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}])
+@pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}, {"tree_team_log2": 0}, {"tree_team_log2": 1},
+                                   {"tree_team_log2": 2, "tree_store": 0}, {"tree_team_log2": 4}])
 def test_recursive_doubling_in_the_tree_form(torch, knobs):
     """Recursive Doubling seen by block is a binomial tree as well (relative rank = rank xor origin, a rank forwards
     in every step after the one it received in); the same one-launch form walks it in step order.  Every power of
-    two up to 256, blocks on and off the grids, in place, explicit mode and AUTO."""
+    two up to 256, blocks on and off the grids, in place, explicit mode and AUTO; one wavefront per piece and teams of
+    2 .. 16 (the tree split by the low bits of the relative rank)."""
     for k, v in knobs.items():
         sb.sparbit_tune(k, v)
     for p in (1, 2, 4, 8, 16, 32, 64, 128, 256):
