@@ -304,6 +304,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  *   "tree_auto"            0/1: AUTO runs whole Sparbit calls as the tree kernel (default 1)
  *   "tree_auto_doubling"   0/1: ... and whole Recursive Doubling calls too (default 1; needs tree_auto)
+ *   "tree_team_log2"       small calls (at most tree_small_bytes): 2^this wavefronts per workgroup share the walk of a
+ *                          tree's piece (0..4; -1, the default: 4 wavefronts from 33 ranks on, 8 from 65 on)
  *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 5, 4,
  *                          3, 2 or 3 as the grid has fewer than 1024, 2048, 4096, 8192, or more wavefronts)
  *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)
