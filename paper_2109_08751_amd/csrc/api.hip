@@ -803,9 +803,10 @@ int tree_form(bool asked_for, int w, bool whole_lines, uint64_t row_bytes, size_
         const bool as_before = g_tree_any_align.load() == 0 && longest < size_t(g_line_align_min_bytes.load());
         return (asked_for || !longish || as_before) ? 16 : -1;
     }
-    // single-byte accesses only up to 128 ranks (a lane walks its tree byte by byte: p = 256, B = 1: 47 us against
-    // 39 us step by step)
-    if (!longish) return (asked_for || w == 4 || p <= 128) ? w : -1;
+    // single-byte accesses only up to 1024 ranks (a lane walks its tree byte by byte; in a team of wavefronts p = 256,
+    // B = 1..7: 12-13 us against 34-40 us step by step, p = 1000: 53-55 against 56-67 us, p = 4096: 660-1430 against
+    // 130-470 us)
+    if (!longish) return (asked_for || w == 4 || p <= 1024) ? w : -1;
     return asked_for ? w : -1;
 }
 
