@@ -113,7 +113,8 @@ extern "C" {
                                      Their waits are bounded all the same (see sparbit_barrier_timeouts).
                                      PER_STEP and TREE never wait on the device. */
 #define SPARBIT_MODE_TREE 4       /* Sparbit and Recursive Doubling, whole calls only: one launch in which every
-                                     wavefront carries one piece of one block through that block's binomial tree
+                                     wavefront (in small calls: every team of 4 or 8 wavefronts of one workgroup)
+                                     carries one piece of one block through that block's binomial tree
                                      (Section III-B: the p trees are independent; Recursive Doubling's messages,
                                      seen by block, form such trees too, with rank xor origin as the relative rank).  Same messages as Algorithm 1, each read from the
                                      forwarder's receive buffer; a forwarder's reads of one slot for different steps

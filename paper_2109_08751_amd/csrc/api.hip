@@ -661,6 +661,37 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     return SPARBIT_OK;
 }
 
+// The access form of one tree launch, chosen by launch_tree below.
+struct TreeLaunch {
+    dim3 grid;
+    bool any;       // the any-alignment form
+    int width;      // else: bytes per access, 16, 4 or 1
+    int U;          // 16-byte vectors per lane
+    int store_kind;
+    bool prefetch;
+    uint32_t lds;
+    uint64_t bytes;
+    hipStream_t stream;
+    uint32_t team;
+};
+
+template <bool VAR, bool DOUBLING>
+int launch_tree_as(const TreeArgs& a, const TreeLaunch& h)
+{
+    if (h.any)
+        return launch_tree_vu<u32x4, 1, 8, VAR, true, DOUBLING>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+    if (h.width == 16) {
+        if constexpr (!DOUBLING) {
+            if (h.U == 2) return launch_tree_vu<u32x4, 2, 8, VAR>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream);
+        }
+        return launch_tree_vu<u32x4, 1, 8, VAR, false, DOUBLING>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream,
+                                                                 h.team);
+    }
+    if (h.width == 4)
+        return launch_tree_vu<uint32_t, 1, 8, VAR, false, DOUBLING>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+    return launch_tree_vu<uint8_t, 1, 8, VAR, false, DOUBLING>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+}
+
 // Equal blocks of B bytes (counts == nullptr; slot k at k * B of a row) or blocks of different sizes (device arrays
 // counts / displs; `B` is then the longest block).  Rows are row_bytes apart.  `width` is the access width the
 // call's addresses and lengths allow; 0 asks for the any-alignment form (16-byte chunks cut relative to the
@@ -714,7 +745,8 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
                            : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
     // Calls that small are one wavefront's walk through the tree, ~100 ns of address arithmetic per rank: from 33
-    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: ? us against 27 us).
+    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: 10.6 us of kernel time
+    // against 27 us; what is left is the depth of the tree, ceil(log2 p) dependent hops of ~1.2 us).
     uint32_t team = 1;
     if (U == 1) {
         const long long team_knob = g_tree_team_log2.load();
@@ -740,34 +772,9 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     if (any && row_bytes % 128 != 0) st = 0;
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
-    if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING) {  // one vector per lane, step order
-        if (counts) {
-            if (any) return launch_tree_vu<u32x4, 1, 8, true, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-            if (width == 16) return launch_tree_vu<u32x4, 1, 8, true, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-            if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-            return launch_tree_vu<uint8_t, 1, 8, true, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-        }
-        if (any) return launch_tree_vu<u32x4, 1, 8, false, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-        if (width == 16) return launch_tree_vu<u32x4, 1, 8, false, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-        return launch_tree_vu<uint8_t, 1, 8, false, false, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-    }
-    if (counts) {
-        if (any) return launch_tree_vu<u32x4, 1, 8, true, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-        if (width == 16) {
-            if (U == 2) return launch_tree_vu<u32x4, 2, 8, true>(a, grid, st, pf, lds, total_bytes, stream);
-            return launch_tree_vu<u32x4, 1, 8, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-        }
-        if (width == 4) return launch_tree_vu<uint32_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-        return launch_tree_vu<uint8_t, 1, 8, true>(a, grid, 0, pf, lds, total_bytes, stream, team);
-    }
-    if (any) return launch_tree_vu<u32x4, 1, 8, false, true>(a, grid, st, pf, lds, total_bytes, stream, team);
-    if (width == 16) {
-        if (U == 2) return launch_tree_vu<u32x4, 2, 8, false>(a, grid, st, pf, lds, total_bytes, stream);
-        return launch_tree_vu<u32x4, 1, 8, false>(a, grid, st, pf, lds, total_bytes, stream, team);
-    }
-    if (width == 4) return launch_tree_vu<uint32_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream, team);
-    return launch_tree_vu<uint8_t, 1, 8, false>(a, grid, 0, pf, lds, total_bytes, stream, team);
+    const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team};
+    if (doubling) return counts ? launch_tree_as<true, true>(a, how) : launch_tree_as<false, true>(a, how);
+    return counts ? launch_tree_as<true, false>(a, how) : launch_tree_as<false, false>(a, how);
 }
 
 // AUTO runs whole calls of this schedule as the tree kernel where tree_form() finds a form for them.

@@ -34,7 +34,8 @@ def test_c_program_builds_against_the_header():
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("p,B,algo", [(6, 1024, 0), (96, 4096, 0), (33, 52, 0), (64, 65536, 0), (16, 4096, 2),
-                                      (21, 4096, 1), (21, 4096, 3), (21, 4096, 4)])
+                                      (21, 4096, 1), (21, 4096, 3), (21, 4096, 4), (128, 1028, 0), (257, 1040, 0),
+                                      (64, 4100, 2), (256, 128, 0)])
 def test_c_program_matches_oracle_on_gpu(p, B, algo):
     exe = EXE if os.path.exists(EXE) else build_exe()
     print("[case] abi_parity", p, B, algo, flush=True)
