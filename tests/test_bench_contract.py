@@ -19,3 +19,69 @@ def test_help_lists_the_contract_flags():
     assert out.returncode == 0
     for flag in ("--gpus", "--steps", "--warmup", "--sweep", "--calibrate-copy"):
         assert flag in out.stdout
+
+
+def _bench():
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+def test_algorithmic_bytes_per_form():
+    """One launch per step moves every delivered byte twice, the tree form once plus the send buffer, Recursive
+    Doubling's tree form additionally reads every forwarder below p/2 from memory."""
+    b = _bench()
+    p, B = 128, 1 << 20
+    assert b.algorithmic_bytes("per_step", p, B) == 2 * p * p * B
+    assert b.algorithmic_bytes("tree", p, B) == p * p * B + p * B
+    assert b.algorithmic_bytes("direct", p, B) == p * p * B + p * B
+    assert b.algorithmic_bytes("tree_doubling", p, B) == p * p * B + p * B + (p // 2 - 1) * p * B
+
+
+def test_forms_are_read_off_the_kernel_name():
+    b = _bench()
+    tree = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"
+    anyal = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false, false>"
+    doubling = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, false, false, false, true, true>"
+    assert b.form_of(tree) == "tree" and b.form_of(anyal) == "tree" and b.form_of(doubling) == "tree_doubling"
+    assert b.tree_kernel_flags(anyal) == {"any_alignment": True, "doubling": False, "team": False}
+    assert b.tree_kernel_flags(doubling) == {"any_alignment": False, "doubling": True, "team": True}
+    assert b.form_of("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 64, 1, true, false, true>") == "per_step"
+    assert b.form_of("anything", "direct") == "direct" and b.form_of("anything", "memcpy_d2d") == "copy"
+    for key in b.MEASURED_TRAFFIC:  # the table's kernel names parse, and name the tree kernel without teams
+        assert b.form_of(key[1]) == "tree" and not b.tree_kernel_flags(key[1])["team"]
+
+
+def test_sweep_summary_from_a_small_file(tmp_path):
+    import json
+    b = _bench()
+    rows = []
+    for p in (8, 5):
+        for B in (1024, 4096):
+            for algo, us in (("sparbit", 10.0), ("sparbit_per_step", 20.0), ("ring", 30.0), ("bruck", 15.0),
+                             ("recursive_doubling", 12.0), ("recursive_doubling_per_step", 16.0), ("direct", 9.0)):
+                if algo.startswith("recursive") and p & (p - 1):
+                    continue
+                rows.append({"p": p, "block_bytes": B, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
+                             "effective_GBps": p * p * B / us / 1e3})
+    name = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, true, false, true>"
+    for algo, us in (("sparbit", 11.0), ("sparbit_per_step", 22.0), ("bruck", 16.0)):
+        rows.append({"p": 5, "block_bytes": 1025, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
+                     "effective_GBps": 1.0, "off_grid": True, "kernel": name, "rows_on_lines": False})
+    path = tmp_path / "ladder.jsonl"
+    path.write_text("".join(json.dumps(r) + "\n" for r in rows))
+    text = b.sweep_summary(str(path))
+    assert f"Cases: {len(rows)}" in text
+    assert "Cells won: sparbit 4, ring 0, recursive_doubling 0, bruck 0 of 4." in text
+    assert "| 8 | 0.83 | 0.83 |" in text  # Sparbit / Recursive Doubling
+    assert "| 8 | 0.75 | 0.75 |" in text  # Recursive Doubling AUTO / per step
+    assert "| 5 | 1K+1 | no | tree* | 11 | 22 | 0.50 |  | 16 |" in text
+    rows[0]["ok"] = False
+    path.write_text("".join(json.dumps(r) + "\n" for r in rows))
+    try:
+        b.sweep_summary(str(path))
+        raise RuntimeError("a failed case must not be summarised")
+    except AssertionError:
+        pass
