@@ -404,10 +404,14 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         } else {
             load(slot(first), xt);
         }
+        // The first ranks of other runs first: their wavefronts are waiting.
         const uint32_t dmax = first ? ((first & (0u - first)) >> 1) : a.top;
-        for (uint32_t d = dmax; d >= 1; d >>= 1)
+        uint32_t d = dmax;
+        for (; d >= K; d >>= 1)
             if (d < p - first) send_to(first, d, xt);
         hand_over(first, dmax);
+        for (; d >= 1; d >>= 1)
+            if (d < p - first) send_to(first, d, xt);
         const uint32_t end = (p - first < K) ? p : first + K;
         for (uint32_t st = K >> 1; st >= 2; st >>= 1) {
             for (uint32_t n0 = first + st; n0 < end; n0 += 2 * st * NB) {
