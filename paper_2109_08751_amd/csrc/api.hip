@@ -745,7 +745,7 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
                            : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
     // Calls that small are one wavefront's walk through the tree, ~100 ns of address arithmetic per rank: from 33
-    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: 10.6 us of kernel time
+    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: 9.9 us of kernel time
     // against 27 us; what is left is the depth of the tree, ceil(log2 p) dependent hops of ~1.2 us).
     uint32_t team = 1;
     if (U == 1) {
