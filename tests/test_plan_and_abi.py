@@ -146,3 +146,18 @@ def test_plan_at_the_maximum_rank_count():
     plan.close()
     with pytest.raises(sb.SparbitError):
         sb.Plan(4097)
+
+
+def test_every_tuning_key_is_documented_in_the_header():
+    """The keys sparbit_tune accepts (read off the source) and the keys the header lists are the same set, and an
+    unknown key is an argument error."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    api = open(os.path.join(root, "paper_2109_08751_amd", "csrc", "api.hip")).read()
+    hdr = open(os.path.join(root, "include", "sparbit.h")).read()
+    accepted = set(re.findall(r'std::strcmp\(key, "([a-z0-9_]+)"\)', api))
+    documented = set(re.findall(r'^ \*   "([a-z0-9_]+)"', hdr, re.M))
+    assert accepted and accepted == documented, (sorted(accepted - documented), sorted(documented - accepted))
+    with pytest.raises(sb.SparbitError) as e:
+        sb.sparbit_tune("no_such_key", 1)
+    assert e.value.code == -1
