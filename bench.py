@@ -56,11 +56,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, 0, false>"):
         (20547378700, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, 0, false>"):
         (20385691481, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false, false>"):
+    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false>"):
         (20378730054, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
@@ -136,14 +136,15 @@ def form_of(kernel_name, algo_label="sparbit"):
     if algo_label == "memcpy_d2d":
         return "copy"
     if "tree_kernel" in kernel_name:
-        return "tree_doubling" if tree_kernel_flags(kernel_name)["doubling"] else "tree"
+        return "tree_doubling" if tree_kernel_flags(kernel_name)["walk"] == "doubling" else "tree"
     return "per_step"
 
 
 def tree_kernel_flags(kernel_name):
     """The last three template arguments of the tree kernel's name as the library reports it."""
     args = kernel_name.rstrip(">").split(", ")
-    return {"any_alignment": args[-3] == "true", "doubling": args[-2] == "true", "team": args[-1] == "true"}
+    return {"any_alignment": args[-3] == "true", "walk": ("sparbit", "doubling", "chain")[int(args[-2])],
+            "team": args[-1] == "true"}
 
 
 def rates(p, B, ms, form):
@@ -288,8 +289,6 @@ def sweep(torch, sb, workloads, stream, path):
                 for label, algo, md in algos:
                     if algo == sb.RECURSIVE_DOUBLING and p & (p - 1):
                         continue
-                    if algo == sb.RING and p * p * B > (1 << 30):
-                        continue  # p - 1 launches of tiny kernels each: skipped where it only burns time
                     fn = lambda: sb.sparbit_allgather_mode(send, recv, p, B, algo, md, stream)
                     t = time_calls(torch, fn, stream, 3, 10)
                     ok = bool(torch.equal(recv, send.unsqueeze(0).expand(p, p, B))) if p * p * B <= (1 << 28) \
@@ -330,7 +329,7 @@ def sweep(torch, sb, workloads, stream, path):
                     send = torch.randint(0, 256, (p, B), dtype=torch.uint8, device=dev)
                     recv = torch.full((p, p, B), workloads.POISON, dtype=torch.uint8, device=dev)
                     for label, algo, md in algos:
-                        if label in ("ring", "direct", "recursive_doubling_per_step") or (algo == sb.RECURSIVE_DOUBLING and p & (p - 1)):
+                        if label in ("direct", "recursive_doubling_per_step") or (algo == sb.RECURSIVE_DOUBLING and p & (p - 1)):
                             continue
                         fn = lambda: sb.sparbit_allgather_mode(send, recv, p, B, algo, md, stream)
                         t = time_calls(torch, fn, stream, 3, 10)
@@ -412,6 +411,15 @@ def sweep_summary(path):
             c = by.get((p, s))
             cells.append("" if not c or "recursive_doubling" not in c else f"{c['sparbit'] / c['recursive_doubling']:.2f}")
         out.append(f"| {p} | " + " | ".join(cells) + " |")
+    out.append("\n## Sparbit time / Ring time\n")
+    out.append("| p \\ bytes | " + " | ".join(_size_label(s) for s in sizes) + " |")
+    out.append("|---|" + "---|" * len(sizes))
+    for p in ps:
+        cells = []
+        for s in sizes:
+            c = by.get((p, s))
+            cells.append("" if not c or "ring" not in c else f"{c['sparbit'] / c['ring']:.2f}")
+        out.append(f"| {p} | " + " | ".join(cells) + " |")
     out.append("\n## Recursive Doubling as AUTO issues it (tree form) / one launch per step\n")
     out.append("| p \\ bytes | " + " | ".join(_size_label(s) for s in sizes) + " |")
     out.append("|---|" + "---|" * len(sizes))
@@ -441,8 +449,8 @@ def sweep_summary(path):
         out.append("Rows on lines: p * bytes is a multiple of 128, so every rank's receive buffer lies the same way "
                    "relative to the 128-byte lines.  Form: what AUTO launched (tree* = the tree kernel's any-alignment "
                    "form, tree = its other forms, steps = one launch per step, flow = dataflow launches).\n")
-        out.append("| p | bytes | rows on lines | form | Sparbit AUTO | Sparbit per step | AUTO / per step | Recursive Doubling | Bruck |")
-        out.append("|---|---|---|---|---|---|---|---|---|")
+        out.append("| p | bytes | rows on lines | form | Sparbit AUTO | Sparbit per step | AUTO / per step | Recursive Doubling | Ring | Bruck |")
+        out.append("|---|---|---|---|---|---|---|---|---|---|")
         for (p, s), c in sorted(off.items()):
             k = c["sparbit"]["kernel"]
             form = ("tree*" if tree_kernel_flags(k)["any_alignment"] else "tree") if "tree_kernel" in k else \
@@ -451,7 +459,7 @@ def sweep_summary(path):
             base = 1 << (s.bit_length() - 1)
             out.append(f"| {p} | {_size_label(base)}+{s - base} | {'yes' if c['sparbit']['rows_on_lines'] else 'no'} | {form} | "
                        f"{g('sparbit')} | {g('sparbit_per_step')} | "
-                       f"{c['sparbit']['avg_us'] / c['sparbit_per_step']['avg_us']:.2f} | {g('recursive_doubling')} | {g('bruck')} |")
+                       f"{c['sparbit']['avg_us'] / c['sparbit_per_step']['avg_us']:.2f} | {g('recursive_doubling')} | {g('ring')} | {g('bruck')} |")
     return "\n".join(out) + "\n"
 
 

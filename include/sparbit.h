@@ -92,10 +92,10 @@ extern "C" {
 #define SPARBIT_ALGO_DIRECT 4             /* no schedule: every slot copied straight from its owner (context only) */
 
 /* ---- how the steps of one call are issued -------------------------------- */
-#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit and Recursive Doubling: TREE, except for blocks of 512 bytes and more that are
-                                     off the 128-byte grid in rows (p * block_bytes) that are off it too, when the
-                                     call is larger than 512 MiB (and, below 64 KiB per block, off the 16-byte
-                                     grid).  Everything else: DATAFLOW for
+#define SPARBIT_MODE_AUTO 0       /* library picks.  Sparbit, Recursive Doubling and Ring: TREE, except for blocks of
+                                     512 bytes and more that are off the 128-byte grid in rows (p * block_bytes)
+                                     that are off it too, when the call is larger than 512 MiB (and, below 64 KiB
+                                     per block, off the 16-byte grid).  Everything else: DATAFLOW for
                                      calls of at most 256 work items (block copies x 16 KiB pieces) or at most 512
                                      with pieces of up to 64 KiB, PERSISTENT (one workgroup) for other calls of at most
                                      4 KiB, else PER_STEP with the leading small steps (at most 512 work items)
@@ -111,15 +111,18 @@ extern "C" {
                                      item only waits for items of lower-numbered workgroups, which the GPU starts
                                      first; a call with more than 2^24 - 1 items is refused (SPARBIT_ERR_UNSUPPORTED).
                                      Their waits are bounded all the same (see sparbit_barrier_timeouts).
-                                     PER_STEP and TREE never wait on the device. */
-#define SPARBIT_MODE_TREE 4       /* Sparbit and Recursive Doubling, whole calls only: one launch in which every
+                                     PER_STEP never waits on the device; in TREE only the wavefronts of one
+                                     workgroup wait for each other (small calls, bounded), which needs nothing
+                                     resident but that workgroup. */
+#define SPARBIT_MODE_TREE 4       /* Sparbit, Recursive Doubling and Ring, whole calls only: one launch in which every
                                      wavefront (in small calls: every team of 4 or 8 wavefronts of one workgroup)
                                      carries one piece of one block through that block's binomial tree
                                      (Section III-B: the p trees are independent; Recursive Doubling's messages,
-                                     seen by block, form such trees too, with rank xor origin as the relative rank).  Same messages as Algorithm 1, each read from the
+                                     seen by block, form such trees too, with rank xor origin as the relative rank;
+                                     Ring's form a chain per block).  Same messages as Algorithm 1, each read from the
                                      forwarder's receive buffer; a forwarder's reads of one slot for different steps
                                      are merged, and the order is any order in which a rank forwards after it
-                                     received.  No table, flag, barrier or device state: nothing waits.
+                                     received.  No table, no barrier and no state in device memory.
                                      Blocks of 512 bytes and more that do not start and end on 128-byte lines are
                                      cut into pieces relative to the lines of the owner's receive buffer (the
                                      same block offsets at every rank): 16-byte chunks, and single bytes at a
@@ -200,7 +203,7 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  *               buffer is defined for equal blocks).
  * Equal counts packed back to back (displs[k] = k * counts[0], row_bytes =
  * p * counts[0]) are the layout of sparbit_allgather and are handed to it.
- * Sparbit and Recursive Doubling go out as ONE launch of the tree form
+ * Sparbit, Recursive Doubling and Ring go out as ONE launch of the tree form
  * (SPARBIT_MODE_TREE), which
  * reads each block's length and offset from the geometry's device copy, under
  * the same rules as equal blocks: counts and displs of any granularity run at
@@ -305,6 +308,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "spin_limit_ms"        bound of one wait of the persistent and dataflow kernels
  *   "tree_auto"            0/1: AUTO runs whole Sparbit calls as the tree kernel (default 1)
  *   "tree_auto_doubling"   0/1: ... and whole Recursive Doubling calls too (default 1; needs tree_auto)
+ *   "tree_auto_ring"       0/1: ... and whole Ring calls (default 1; needs tree_auto)
  *   "tree_team_log2"       small calls (at most tree_small_bytes): 2^this wavefronts per workgroup share the walk of a
  *                          tree's piece (0..4; -1, the default: 4 wavefronts from 33 ranks on, 8 from 65 on)
  *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 5, 4,

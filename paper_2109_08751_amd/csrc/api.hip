@@ -113,6 +113,7 @@ std::atomic<long long> g_var_idle_max{131072};                // Allgatherv: idl
 std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
+std::atomic<long long> g_tree_auto_ring{1};                   // ... and whole Ring calls (a chain per block)
 std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
 std::atomic<long long> g_tree_small_bytes{96ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
@@ -616,19 +617,21 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
 }
 
 // The tree kernel: one wavefront, or with `team` > 1 that many, per (tree, piece of 64 * U vectors).
-template <typename V, int U, int NB, bool VAR, bool ANY = false, bool DOUBLING = false>
+template <typename V, int U, int NB, bool VAR, bool ANY = false, int WALK = kWalkSparbit>
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream,
                    uint32_t team = 1)
 {
+    constexpr bool kStepOrderOnly = WALK != kWalkSparbit;  // no runs: no look-ahead, and plain or write-through stores
     if (sizeof(V) != 16) store_kind = 0;
-    if (DOUBLING || team > 1) prefetch = false;
-    if (team > 1 && store_kind == 3) store_kind = 2;
-    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %s, %s>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR), bool_label(ANY), bool_label(DOUBLING), bool_label(team > 1));
-#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, DOUBLING>), grid, dim3(64), lds, stream, a)
+    if (kStepOrderOnly || team > 1) prefetch = false;
+    if ((kStepOrderOnly || team > 1) && store_kind == 3) store_kind = 2;
+    if (WALK == kWalkChain) team = 1;
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1));
+#define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, WALK>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
-    hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, DOUBLING, true>), grid, dim3(64 * team), lds, stream, a)
-    if constexpr (U == 1) {
+    hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, WALK, true>), grid, dim3(64 * team), lds, stream, a)
+    if constexpr (U == 1 && WALK != kWalkChain) {
         if (team > 1) {
             if (store_kind != 0) SB_TEAM(2);
             else SB_TEAM(0);
@@ -636,7 +639,7 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
             return SPARBIT_OK;
         }
     }
-    if constexpr (DOUBLING) {  // no look-ahead, and of the store forms plain and write-through
+    if constexpr (kStepOrderOnly) {
         if (store_kind != 0) SB_TREE(2, false);
         else SB_TREE(0, false);
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
@@ -675,21 +678,20 @@ struct TreeLaunch {
     uint32_t team;
 };
 
-template <bool VAR, bool DOUBLING>
+template <bool VAR, int WALK>
 int launch_tree_as(const TreeArgs& a, const TreeLaunch& h)
 {
     if (h.any)
-        return launch_tree_vu<u32x4, 1, 8, VAR, true, DOUBLING>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+        return launch_tree_vu<u32x4, 1, 8, VAR, true, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
     if (h.width == 16) {
-        if constexpr (!DOUBLING) {
+        if constexpr (WALK == kWalkSparbit) {
             if (h.U == 2) return launch_tree_vu<u32x4, 2, 8, VAR>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream);
         }
-        return launch_tree_vu<u32x4, 1, 8, VAR, false, DOUBLING>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream,
-                                                                 h.team);
+        return launch_tree_vu<u32x4, 1, 8, VAR, false, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
     }
     if (h.width == 4)
-        return launch_tree_vu<uint32_t, 1, 8, VAR, false, DOUBLING>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
-    return launch_tree_vu<uint8_t, 1, 8, VAR, false, DOUBLING>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+        return launch_tree_vu<uint32_t, 1, 8, VAR, false, WALK>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+    return launch_tree_vu<uint8_t, 1, 8, VAR, false, WALK>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
 }
 
 // Equal blocks of B bytes (counts == nullptr; slot k at k * B of a row) or blocks of different sizes (device arrays
@@ -748,7 +750,7 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: 9.9 us of kernel time
     // against 27 us; what is left is the depth of the tree, ceil(log2 p) dependent hops of ~1.2 us).
     uint32_t team = 1;
-    if (U == 1) {
+    if (U == 1 && algo != SPARBIT_ALGO_RING) {
         const long long team_knob = g_tree_team_log2.load();
         const int lg_p = ceil_log2(p);
         int lg_team = team_knob >= 0 ? int(team_knob) : (small && run_knob < 0 && p > 32) ? (p > 64 ? 3 : 2) : 0;
@@ -770,11 +772,15 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
     // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
     if (any && row_bytes % 128 != 0) st = 0;
+    // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
+    // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
+    if (algo == SPARBIT_ALGO_RING) st = 0;
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
     const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team};
-    if (doubling) return counts ? launch_tree_as<true, true>(a, how) : launch_tree_as<false, true>(a, how);
-    return counts ? launch_tree_as<true, false>(a, how) : launch_tree_as<false, false>(a, how);
+    if (algo == SPARBIT_ALGO_RING) return counts ? launch_tree_as<true, kWalkChain>(a, how) : launch_tree_as<false, kWalkChain>(a, how);
+    if (doubling) return counts ? launch_tree_as<true, kWalkDoubling>(a, how) : launch_tree_as<false, kWalkDoubling>(a, how);
+    return counts ? launch_tree_as<true, kWalkSparbit>(a, how) : launch_tree_as<false, kWalkSparbit>(a, how);
 }
 
 // AUTO runs whole calls of this schedule as the tree kernel where tree_form() finds a form for them.
@@ -782,6 +788,7 @@ bool auto_takes_tree_form(int algo)
 {
     if (algo == SPARBIT_ALGO_SPARBIT) return g_tree_auto.load() != 0;
     if (algo == SPARBIT_ALGO_RECURSIVE_DOUBLING) return g_tree_auto.load() != 0 && g_tree_auto_doubling.load() != 0;
+    if (algo == SPARBIT_ALGO_RING) return g_tree_auto.load() != 0 && g_tree_auto_ring.load() != 0;
     return false;
 }
 
@@ -1211,7 +1218,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
 
     // The tree kernel needs no table, no flag and no state, so it is decided before anything is looked up or built
     // (and a capturing stream can record it like any other launch).
-    const bool has_tree_form = algo == SPARBIT_ALGO_SPARBIT || algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
+    const bool has_tree_form = algo == SPARBIT_ALGO_SPARBIT || algo == SPARBIT_ALGO_RECURSIVE_DOUBLING || algo == SPARBIT_ALGO_RING;
     if (mode == SPARBIT_MODE_TREE && (!has_tree_form || !whole)) return SPARBIT_ERR_UNSUPPORTED;
     if (whole && has_tree_form && (mode == SPARBIT_MODE_TREE || (mode == SPARBIT_MODE_AUTO && auto_takes_tree_form(algo)))) {
         const int w = access_width(sendbufs, recvbufs, nullptr, B);
@@ -1627,6 +1634,8 @@ int sparbit_tune(const char* key, long long value)
         g_tree_auto = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_auto_doubling")) {
         g_tree_auto_doubling = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_auto_ring")) {
+        g_tree_auto_ring = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_team_log2")) {
         if (value < -1 || value > 4) return SPARBIT_ERR_ARG;
         g_tree_team_log2 = value;

@@ -207,7 +207,7 @@ struct Held {
 // target's buffer loads and stores accept.  A piece is a run of 16-byte chunks, one per lane, and, at the block's
 // first and last piece, up to 15 single bytes, one per lane.
 //
-// DOUBLING: the same form for Recursive Doubling (Section II-A; p a power of two).  Seen by block, that schedule is
+// WALK 1 (DOUBLING): the same form for Recursive Doubling (Section II-A; p a power of two).  Seen by block, that schedule is
 // a binomial tree as well, with the distances in the opposite order and the rank found by exclusive-or: with rho =
 // rank xor b, step s sends from every rho < 2^s to rho + 2^s.  So rho receives in the step of its highest set bit and
 // forwards in every later step, i.e. every rho below p/2 forwards and its destinations are far away.  The walk is
@@ -224,10 +224,17 @@ struct Held {
 // Recursive Doubling's tree is cut by the low bits of the relative rank instead (see the kernel).
 constexpr uint32_t kTeamSpinLimit = 1u << 22;  // polls of ~100 cycles each
 
-template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, bool DOUBLING = false,
+//
+// WALK 2, Ring (Section II-A) in the same form: per block a chain, relative rank rho forwards to rho + 1, so the
+// wavefront stores a rank and reads it back at once, p - 1 times.
+constexpr int kWalkSparbit = 0, kWalkDoubling = 1, kWalkChain = 2;
+
+template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, int WALK = kWalkSparbit,
           bool TEAM = false>
 __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a)
 {
+    constexpr bool DOUBLING = WALK == kWalkDoubling, CHAIN = WALK == kWalkChain;
+    static_assert(!CHAIN || (!PF && !TEAM), "a chain has nothing to look ahead of and nothing to share");
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
     static_assert(!DOUBLING || !PF, "the doubling walk has no run to look ahead of");
     static_assert(!TEAM || (!PF && U == 1), "a team's wavefronts walk one part of the tree each, one vector per lane");
@@ -439,6 +446,16 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         store(slot(0), xh, false);  // own-block placement; read again only in an in-place call
     } else {
         load(slot(0), xh);
+    }
+    if constexpr (CHAIN) {
+        for (uint32_t rho = 1; rho < p; ++rho) {
+            store(slot(rho), xh, true);
+            if (rho + 1 < p) {
+                load(slot(rho), xh);  // what rho forwards is what it received
+                wait_for_loads();
+            }
+        }
+        return;
     }
     if constexpr (DOUBLING) {
         for (uint32_t d = 1; d < p; d <<= 1) store(slot(d), xh, false);  // the origin sends in every step

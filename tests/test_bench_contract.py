@@ -42,12 +42,14 @@ def test_algorithmic_bytes_per_form():
 
 def test_forms_are_read_off_the_kernel_name():
     b = _bench()
-    tree = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, false, false>"
-    anyal = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, false, false>"
-    doubling = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, false, false, false, true, true>"
+    tree = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, 0, false>"
+    anyal = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false>"
+    doubling = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, false, false, false, 1, true>"
+    chain = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, false, 2, false>"
     assert b.form_of(tree) == "tree" and b.form_of(anyal) == "tree" and b.form_of(doubling) == "tree_doubling"
-    assert b.tree_kernel_flags(anyal) == {"any_alignment": True, "doubling": False, "team": False}
-    assert b.tree_kernel_flags(doubling) == {"any_alignment": False, "doubling": True, "team": True}
+    assert b.form_of(chain) == "tree"  # a chain's re-reads follow their writes at once: the tree form's byte count
+    assert b.tree_kernel_flags(anyal) == {"any_alignment": True, "walk": "sparbit", "team": False}
+    assert b.tree_kernel_flags(doubling) == {"any_alignment": False, "walk": "doubling", "team": True}
     assert b.form_of("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 64, 1, true, false, true>") == "per_step"
     assert b.form_of("anything", "direct") == "direct" and b.form_of("anything", "memcpy_d2d") == "copy"
     for key in b.MEASURED_TRAFFIC:  # the table's kernel names parse, and name the tree kernel without teams
@@ -66,7 +68,7 @@ def test_sweep_summary_from_a_small_file(tmp_path):
                     continue
                 rows.append({"p": p, "block_bytes": B, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
                              "effective_GBps": p * p * B / us / 1e3})
-    name = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, true, false, true>"
+    name = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, true, 0, true>"
     for algo, us in (("sparbit", 11.0), ("sparbit_per_step", 22.0), ("bruck", 16.0)):
         rows.append({"p": 5, "block_bytes": 1025, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
                      "effective_GBps": 1.0, "off_grid": True, "kernel": name, "rows_on_lines": False})
@@ -77,7 +79,8 @@ def test_sweep_summary_from_a_small_file(tmp_path):
     assert "Cells won: sparbit 4, ring 0, recursive_doubling 0, bruck 0 of 4." in text
     assert "| 8 | 0.83 | 0.83 |" in text  # Sparbit / Recursive Doubling
     assert "| 8 | 0.75 | 0.75 |" in text  # Recursive Doubling AUTO / per step
-    assert "| 5 | 1K+1 | no | tree* | 11 | 22 | 0.50 |  | 16 |" in text
+    assert "| 5 | 1K+1 | no | tree* | 11 | 22 | 0.50 |  |  | 16 |" in text
+    assert "| 8 | 0.33 | 0.33 |" in text  # Sparbit / Ring
     rows[0]["ok"] = False
     path.write_text("".join(json.dumps(r) + "\n" for r in rows))
     try:

@@ -708,7 +708,7 @@ def test_randomized_cases(torch):
         if p * p * B > (64 << 20):
             continue
         mode = modes[rng.integers(len(modes))]
-        if algo in (sb.SPARBIT, sb.RECURSIVE_DOUBLING) and rng.integers(0, 3) == 0:
+        if algo in (sb.SPARBIT, sb.RECURSIVE_DOUBLING, sb.RING) and rng.integers(0, 3) == 0:
             mode = "tree"
             sb.sparbit_tune("tree_run_log2", int(rng.integers(0, 8)))
             sb.sparbit_tune("tree_small_bytes", [0, 96 << 20][rng.integers(2)])

@@ -207,7 +207,7 @@ def test_auto_forms_teams_for_small_calls_of_many_ranks(torch):
 
 def launched_doubling_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "true"
+    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "1"
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}, {"tree_team_log2": 0}, {"tree_team_log2": 1},
@@ -259,11 +259,29 @@ def test_recursive_doubling_in_the_tree_form_at_full_size(torch):
         assert np.array_equal(d_recv[r, k].cpu().numpy(), send.reshape(p, B)[k])
 
 
+def test_ring_in_the_tree_form(torch):
+    """Ring seen by block is a chain (relative rank rho forwards to rho + 1): the same one-launch form stores a rank
+    and reads it back, p - 1 times, with plain stores whatever the store setting.  Explicit mode and AUTO, blocks on
+    and off the grids, in place."""
+    for p in (1, 2, 3, 5, 8, 21, 33, 64, 96, 257):
+        for B, mis in ((16, 0), (1040, 0), (100, 0), (333, 1), (4100, 0), (4096, 4)) if p <= 64 else ((1040, 0), (516, 0)):
+            for mode, in_place in ((sb.MODE_TREE, False), (sb.MODE_AUTO, False), (sb.MODE_TREE, True)):
+                announce("ring chain", p, B, mis, mode, in_place)
+                send = workloads.make_send_raw(p, B, seed=p + B)
+                want = oracle_result(sb.RING, p, B, send, in_place=in_place)
+                got = gpu_result(torch, sb.RING, p, B, send, mode, in_place=in_place, misalign=mis)
+                name = sb.sparbit_last_launch_info()[0]
+                if not (p == 1 and in_place):
+                    assert "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "2" and ", 8, 0, " in name, name
+                assert np.array_equal(got, want), (p, B, mis, mode, in_place)
+
+
 def test_refusals(torch):
-    """The tree form exists for the two schedules whose messages form binomial trees per block and end in the
-    block's own slot, Sparbit and Recursive Doubling; the others, and step ranges, are refused."""
+    """The tree form exists for the schedules whose messages, seen by block, form a tree that ends in the block's own
+    slot at every rank: Sparbit, Recursive Doubling and Ring.  Bruck (rotated working buffer), DIRECT, and step ranges
+    are refused."""
     d = torch.full((4096,), POISON, dtype=torch.uint8, device="cuda:0")
-    for algo in (sb.RING, sb.BRUCK, sb.DIRECT):
+    for algo in (sb.BRUCK, sb.DIRECT):
         with pytest.raises(sb.SparbitError) as e:
             sb.sparbit_allgather_mode(d[:64], d[1024:], 4, 16, algo, sb.MODE_TREE)
         assert e.value.code == -3
@@ -295,7 +313,7 @@ def test_capture_records_the_tree_launch_and_needs_no_tables(torch):
 
 
 def test_many_streams_at_once(torch):
-    """Nothing in the tree form waits, so any number of calls may run side by side."""
+    """Nothing in the tree form waits for another workgroup, so any number of calls may run side by side."""
     cases = [(96, 4096), (64, 16384), (125, 512), (32, 65536), (12, 1024), (257, 1040)]
     streams = [torch.cuda.Stream() for _ in cases]
     jobs = []
