@@ -312,7 +312,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_team_log2"       small calls (at most tree_small_bytes): 2^this wavefronts per workgroup share the walk of a
  *                          tree's piece (0..4; -1, the default: 4 wavefronts from 33 ranks on, 8 from 65 on)
  *   "tree_run_log2"        the tree kernel walks a tree in runs of 2^this relative ranks (0..12; -1, the default: 5, 4,
- *                          3, 2 or 3 as the grid has fewer than 1024, 2048, 4096, 8192, or more wavefronts)
+ *                          3, 2 or 3 as the grid has fewer than 1024, 2048, 4096, 8192, or more wavefronts; 2 instead
+ *                          of the last 3 up to 32 ranks)
  *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)
  *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1 or 2
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
@@ -324,7 +325,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          this many receive bytes (default 512 MiB)
  *   "tree_lds_bytes"       LDS each of its wavefronts reserves without using it, which caps the wavefronts per
  *                          compute unit (0..65536; 160 KiB per unit; -1, the default: 14336 for grids of 8192 and
- *                          more wavefronts, else 0)
+ *                          more wavefronts on more than 32 ranks, else 0)
  */
 int sparbit_tune(const char *key, long long value);
 

@@ -740,7 +740,9 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     //    3.12 ms; uncapped 3.45 ms; capped at 16 with runs of 4: 3.23 ms).
     const uint64_t waves = pieces * uint64_t(p);
     const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
-    const bool capped = waves >= 8192;
+    // ... from 33 ranks on: a shorter tree is walked too quickly for that to pay (p = 16, 1 MiB: 58.6 us uncapped with
+    // runs of 4, 66.6 us capped with runs of 8; p = 32, 4 MiB: 883 against 956 us; p = 64, 1 MiB: 891 against 789 us).
+    const bool capped = waves >= 8192 && p > 32;
     const long long run_knob = g_tree_run_log2.load();
     a.lg_k = run_knob >= 0 ? uint32_t(run_knob)
                            : small ? uint32_t(ceil_log2(p))
