@@ -114,6 +114,7 @@ std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
 std::atomic<long long> g_tree_auto_ring{1};                   // ... and whole Ring calls (a chain per block)
+std::atomic<long long> g_tree_hot{-1};                        // plain stores with forwarders read back at once: -1 = by size, 0 = never, 1 = always
 std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
 std::atomic<long long> g_tree_small_bytes{96ll << 20};        // p*p*B up to this: the tree kernel walks in step order instead
@@ -625,6 +626,8 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if (sizeof(V) != 16) store_kind = 0;
     if (kStepOrderOnly || team > 1) prefetch = false;
     if ((kStepOrderOnly || team > 1) && store_kind == 3) store_kind = 2;
+    if ((kStepOrderOnly || team > 1 || ANY) && store_kind == 1) store_kind = 0;
+    if (store_kind == 1) prefetch = true;
     if (WALK == kWalkChain) team = 1;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
                 bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1));
@@ -648,6 +651,14 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
         else if (prefetch) SB_TREE(0, true);
         else SB_TREE(0, false);
     } else if constexpr (sizeof(V) == 16) {
+        if constexpr (U == 1) {
+            if (store_kind == 1) {
+                SB_TREE(1, true);
+                SB_HIP(hipGetLastError());
+                return SPARBIT_OK;
+            }
+        }
+        if (store_kind == 1) store_kind = 0;
         if (store_kind == 3 && prefetch) SB_TREE(3, true);
         else if (store_kind == 3) SB_TREE(3, false);
         else if (store_kind == 2 && prefetch) SB_TREE(2, true);
@@ -767,9 +778,26 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // Recursive Doubling has no read that follows its write closely, so more resident wavefronts only help:
     // 20 per unit (p = 128, 1 MiB: 4.61 ms; 11 per unit 4.99 ms; uncapped 4.66 ms).
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
-    const uint32_t lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
+    const uint32_t lds_by_size = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
     int st = int(g_tree_store.load());
+    // Calls that the caches hold a good part of: plain stores, every forwarder read back right after it was stored
+    // (runs of 8, grid uncapped).  Measured against the write-through walk above (AUTO before): p = 16, 1 MiB: 48 against
+    // 57 us; p = 8, 64 MiB (4 GiB): 852 against 1068 us; p = 64, 64 KiB: 44.8 against 48.1 us; p = 61, 144 KiB (512
+    // MiB): 111 against 117 us; p = 128, 16 KiB (256 MiB): 46 against 52 us; level from 1 GiB on for 32 ranks and more
+    // (p = 64, 1 MiB: 833 against 793 us), behind at 4 GiB from 125 ranks on (895 against 833 us).
+    const long long hot_knob = g_tree_hot.load();
+    const uint64_t MiB = uint64_t(1) << 20;
+    const bool hot_size = p < 32    ? total_bytes > 48 * MiB
+                          : p <= 64 ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
+                                    : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
+    const bool untouched = run_knob < 0 && lds_knob < 0 && st == 2 && g_tree_team_log2.load() < 0;
+    if (algo == SPARBIT_ALGO_SPARBIT && width == 16 && U == 1 && (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched))) {
+        st = 1;
+        team = 1;
+        a.lg_k = 3;
+    }
+    const uint32_t lds = st == 1 && lds_knob < 0 ? 0u : lds_by_size;
     // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
     // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
     // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
@@ -1638,6 +1666,9 @@ int sparbit_tune(const char* key, long long value)
         g_tree_auto_doubling = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_auto_ring")) {
         g_tree_auto_ring = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_hot")) {
+        if (value < -1 || value > 1) return SPARBIT_ERR_ARG;
+        g_tree_hot = value;
     } else if (!std::strcmp(key, "tree_team_log2")) {
         if (value < -1 || value > 4) return SPARBIT_ERR_ARG;
         g_tree_team_log2 = value;

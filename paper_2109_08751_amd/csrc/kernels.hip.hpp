@@ -174,6 +174,9 @@ struct TreeArgs {
 // Store forms of the tree kernel (ST), for 16-byte vectors.  0: plain, the line is allocated in the XCD's L2 and
 // written back later.  2: write-through at system scope (sc0 sc1), the line goes straight to the memory side.
 // 3: by destination -- plain for a rank that forwards and is read again soon, write-through for the others.
+// 1: plain stores, and a run of 8 is walked so that every forwarder is read back right after it was stored, while
+// its lines are still in the caches, and held in registers until its turn to forward (the form for calls that the
+// caches hold a good part of: no read leaves the XCD, and the write-back of such a call is cheap).
 // The 16-byte accesses are raw buffer loads and stores: the base of a slot's piece is wave-uniform and sits in
 // scalar registers (no per-lane 64-bit address arithmetic), the piece's length is the buffer's size, so lanes past
 // a block's ragged end are dropped by the bounds check, and the cache-policy bits are an operand of the
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             for (int u = 0; u < U; ++u) {
                 const int at = int(lane * 16u + u * 1024u);
                 const raw4 v = __builtin_bit_cast(raw4, x.v[u]);
-                if (ST == 0 || (ST == 3 && read_again_soon))
+                if (ST == 0 || ST == 1 || (ST == 3 && read_again_soon))
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, kBufferSc0Sc1);
@@ -312,7 +315,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             if constexpr (ANY) {
                 if (tail_bytes)
                     __builtin_amdgcn_raw_buffer_store_b8(x.tail, piece_buffer(d + piece_vectors * 16u, tail_bytes), int(lane), 0,
-                                                         ST == 0 ? 0 : kBufferSc0Sc1);
+                                                         (ST == 0 || ST == 1) ? 0 : kBufferSc0Sc1);
             }
         } else {
             V* dv = reinterpret_cast<V*>(d) + lane;
@@ -476,6 +479,37 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     }
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;
+        if constexpr (ST == 1) {  // K = 8 (the host sees to it); PF: xh is this run's first rank, loaded by the run before
+            static_assert(PF && U == 1, "the read-back-at-once walk keeps the next run's first rank in registers");
+            auto to = [&](uint32_t n, uint32_t d, const H& x) {  // a forward, if both ranks exist
+                if (n < p && d < p - n) send_to(n, d, x);
+            };
+            auto back = [&](uint32_t n, H& x) {  // read a forwarder back
+                if (n < p && forwards(n)) load(slot(n), x);
+            };
+            const uint32_t dmax = h ? ((h & (0u - h)) >> 1) : a.top;
+            for (uint32_t d = dmax; d > 8; d >>= 1) to(h, d, xh);
+            H x4, x2, x6, xn;
+            if (dmax >= 8) {
+                to(h, 8, xh);
+                back(h + 8, xn);
+            }
+            to(h, 4, xh);
+            back(h + 4, x4);
+            to(h, 2, xh);
+            back(h + 2, x2);
+            to(h, 1, xh);
+            wait_for_loads();
+            to(h + 4, 2, x4);
+            back(h + 6, x6);
+            to(h + 4, 1, x4);
+            to(h + 2, 1, x2);
+            wait_for_loads();
+            to(h + 6, 1, x6);
+            if (dmax < 8) back(h + 8, xn);  // stored by an earlier run
+            xh = xn;
+            continue;
+        }
         if (!PF && h != 0 && forwards(h)) load(slot(h), xh);
         for (uint32_t d = h ? ((h & (0u - h)) >> 1) : a.top; d >= 1; d >>= 1)
             if (d < p - h) send_to(h, d, xh);

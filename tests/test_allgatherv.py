@@ -287,6 +287,34 @@ def test_gpu_allgatherv_blocks_off_the_16_byte_grid():
 
 
 @pytest.mark.gpu
+def test_gpu_allgatherv_forwarders_read_back_at_once():
+    """The tree kernel's form with plain stores and forwarders read back at once (what AUTO takes for calls the caches
+    hold a good part of), forced onto small geometries with per-slot sizes: blocks of 0 .. 4 KiB on whole lines, gaps,
+    shuffled displacements, in place."""
+    import torch
+    sb.sparbit_tune("tree_hot", 1)
+    try:
+        for p in (1, 2, 5, 8, 9, 12, 17, 33, 64, 96):
+            counts, displs, row = geometry(p, seed=p + 40, align=128, max_len=4096)
+            send = payload(row, p)
+            for in_place in (False, True):
+                print("[case] allgatherv read back at once", p, row, in_place, flush=True)
+                want = np.full((p, row), POISON, dtype=np.uint8)
+                if in_place:
+                    for r in range(p):
+                        d, c = int(displs[r]), int(counts[r])
+                        want[r, d:d + c] = send[d:d + c]
+                oracle.allgatherv(oracle.SPARBIT, p, counts, displs, row, None if in_place else send, want)
+                got = gpu_allgatherv(torch, sb.SPARBIT, p, counts, displs, row, send, in_place=in_place)
+                name = sb.sparbit_last_launch_info()[0]
+                if counts.any() and not (p == 1 and in_place):
+                    assert ", 8, 1, true, true, " in name, name
+                assert np.array_equal(got, want), (p, in_place)
+    finally:
+        sb.sparbit_tune("tree_hot", -1)
+
+
+@pytest.mark.gpu
 def test_gpu_allgatherv_block_with_more_tiles_than_the_grid_holds():
     """Eight copies of a block of 4 GiB + 48 B in one launch (DIRECT, p = 8, the other blocks tiny): the looping
     kernel takes over.  Expected state: every receive buffer equals the send layout inside the blocks (the

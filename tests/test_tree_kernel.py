@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 96 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
             "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
-            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1}
+            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1, "tree_hot": -1}
 
 
 @pytest.fixture(scope="module")
@@ -202,6 +202,34 @@ def test_auto_forms_teams_for_small_calls_of_many_ranks(torch):
         got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_AUTO)
         name = sb.sparbit_last_launch_info()[0]
         assert "tree_kernel" in name and name.endswith(", true>") == team, name
+        assert np.array_equal(got, want), (p, B)
+
+
+def test_forwarders_read_back_at_once(torch):
+    """The form for calls that the caches hold a good part of: plain stores, runs of 8, every forwarder read back
+    right after it was stored and kept in registers until its turn.  Forced onto every rank count around the run
+    length and the powers of two (last runs of 1 .. 8 ranks, trees shorter than a run), in place; and AUTO's own
+    choice of it.  (Per-slot sizes: test_allgatherv.py.)"""
+    sb.sparbit_tune("tree_hot", 1)
+    for p in (1, 2, 3, 5, 7, 8, 9, 10, 15, 16, 17, 21, 23, 24, 25, 31, 32, 33, 40, 63, 64, 65, 96, 127, 129, 257):
+        for B in (16, 1024, 4096 + 128) if p <= 65 else (1024,):  # whole vectors on whole lines, or short blocks
+            in_place = (p + B) % 3 == 0
+            announce("tree read back at once", p, B, in_place)
+            send = workloads.make_send_raw(p, B, seed=p * 5 + 1)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place)
+            name = sb.sparbit_last_launch_info()[0]
+            if not (p == 1 and in_place):
+                assert ", 8, 1, true, " in name, name
+            assert np.array_equal(got, want), (p, B, in_place)
+    sb.sparbit_tune("tree_hot", -1)
+    for p, B, hot in ((64, 16384, True), (16, 262144, True), (64, 4096, False), (128, 8192, True), (128, 4096, False)):
+        announce("tree read back at once, by itself", p, B)
+        send = workloads.make_send_raw(p, B, seed=p)
+        want = oracle_result(sb.SPARBIT, p, B, send)
+        got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_AUTO)
+        name = sb.sparbit_last_launch_info()[0]
+        assert "tree_kernel" in name and (", 8, 1, true, " in name) == hot, name
         assert np.array_equal(got, want), (p, B)
 
 
