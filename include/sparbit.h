@@ -318,7 +318,8 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1 or 2
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
  *                          and write-through to the others
- *   "tree_hot"             Sparbit, blocks on whole 16-byte vectors: plain stores, runs of 8, every forwarder read back
+ *   "tree_hot"             Sparbit, 16-byte vectors (aligned blocks or the any-alignment form): plain stores, runs of
+ *                          8, every forwarder read back
  *                          right after it was stored (-1, the default: for calls of 48 MiB .. 768 MiB up to 64 ranks,
  *                          of any size above 48 MiB below 32 ranks, of 96 .. 384 MiB beyond 64 ranks; 0 never; 1 always)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one

@@ -626,7 +626,7 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if (sizeof(V) != 16) store_kind = 0;
     if (kStepOrderOnly || team > 1) prefetch = false;
     if ((kStepOrderOnly || team > 1) && store_kind == 3) store_kind = 2;
-    if ((kStepOrderOnly || team > 1 || ANY) && store_kind == 1) store_kind = 0;
+    if ((kStepOrderOnly || team > 1) && store_kind == 1) store_kind = 0;
     if (store_kind == 1) prefetch = true;
     if (WALK == kWalkChain) team = 1;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
@@ -646,7 +646,8 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
         if (store_kind != 0) SB_TREE(2, false);
         else SB_TREE(0, false);
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
-        if (store_kind != 0 && prefetch) SB_TREE(2, true);
+        if (store_kind == 1) SB_TREE(1, true);
+        else if (store_kind != 0 && prefetch) SB_TREE(2, true);
         else if (store_kind != 0) SB_TREE(2, false);
         else if (prefetch) SB_TREE(0, true);
         else SB_TREE(0, false);
@@ -792,7 +793,8 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
                           : p <= 64 ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
                                     : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
     const bool untouched = run_knob < 0 && lds_knob < 0 && st == 2 && g_tree_team_log2.load() < 0;
-    if (algo == SPARBIT_ALGO_SPARBIT && width == 16 && U == 1 && (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched))) {
+    if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1 &&
+        (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched))) {
         st = 1;
         team = 1;
         a.lg_k = 3;
@@ -801,7 +803,7 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
     // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
     // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
-    if (any && row_bytes % 128 != 0) st = 0;
+    if (any && row_bytes % 128 != 0 && st != 1) st = 0;
     // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
     // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
     if (algo == SPARBIT_ALGO_RING) st = 0;
