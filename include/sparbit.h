@@ -317,7 +317,10 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)
  *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1 or 2
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
- *                          and write-through to the others
+ *                          and write-through to the others; 1 and 4 (Sparbit, 16-byte vectors; elsewhere they run as
+ *                          0 and 2): runs of 8 with every forwarder read back right after it was stored, all stores
+ *                          plain (1) or only those that are read back (4).  Left at 2, AUTO and MODE_TREE take 1 by
+ *                          the tree_hot rule and, for blocks on the 16-byte grid, 4 on the capped grids (see tree_lds_bytes)
  *   "tree_hot"             Sparbit, 16-byte vectors (aligned blocks or the any-alignment form): plain stores, runs of
  *                          8, every forwarder read back
  *                          right after it was stored (-1, the default: for calls of 48 MiB .. 768 MiB up to 64 ranks,

@@ -627,7 +627,8 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if (kStepOrderOnly || team > 1) prefetch = false;
     if ((kStepOrderOnly || team > 1) && store_kind == 3) store_kind = 2;
     if ((kStepOrderOnly || team > 1) && store_kind == 1) store_kind = 0;
-    if (store_kind == 1) prefetch = true;
+    if ((kStepOrderOnly || team > 1) && store_kind == 4) store_kind = 2;
+    if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
                 bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1));
@@ -647,19 +648,22 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
         else SB_TREE(0, false);
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
         if (store_kind == 1) SB_TREE(1, true);
+        else if (store_kind == 4) SB_TREE(4, true);
         else if (store_kind != 0 && prefetch) SB_TREE(2, true);
         else if (store_kind != 0) SB_TREE(2, false);
         else if (prefetch) SB_TREE(0, true);
         else SB_TREE(0, false);
     } else if constexpr (sizeof(V) == 16) {
         if constexpr (U == 1) {
-            if (store_kind == 1) {
-                SB_TREE(1, true);
+            if (store_kind == 1 || store_kind == 4) {
+                if (store_kind == 1) SB_TREE(1, true);
+                else SB_TREE(4, true);
                 SB_HIP(hipGetLastError());
                 return SPARBIT_OK;
             }
         }
         if (store_kind == 1) store_kind = 0;
+        if (store_kind == 4) store_kind = 2;
         if (store_kind == 3 && prefetch) SB_TREE(3, true);
         else if (store_kind == 3) SB_TREE(3, false);
         else if (store_kind == 2 && prefetch) SB_TREE(2, true);
@@ -782,28 +786,41 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const uint32_t lds_by_size = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
     int st = int(g_tree_store.load());
-    // Calls that the caches hold a good part of: plain stores, every forwarder read back right after it was stored
-    // (runs of 8, grid uncapped).  Measured against the write-through walk above (AUTO before): p = 16, 1 MiB: 48 against
-    // 57 us; p = 8, 64 MiB (4 GiB): 852 against 1068 us; p = 64, 64 KiB: 44.8 against 48.1 us; p = 61, 144 KiB (512
-    // MiB): 111 against 117 us; p = 128, 16 KiB (256 MiB): 46 against 52 us; level from 1 GiB on for 32 ranks and more
-    // (p = 64, 1 MiB: 833 against 793 us), behind at 4 GiB from 125 ranks on (895 against 833 us).
+    const bool part_lines = any && row_bytes % 128 != 0;
+    // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
+    // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
+    // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
+    if (part_lines && st != 1) st = 0;
+    // The walk of store forms 1 and 4: runs of 8, every forwarder read back right after it was stored.
+    //  - Form 1 (all stores plain, grid uncapped) for calls that the caches hold a good part of.  Against the
+    //    write-through walk above: p = 16, 1 MiB: 48 against 57 us; p = 8, 64 MiB (4 GiB): 852 against 1068 us; p = 64,
+    //    64 KiB: 44.8 against 48.1 us; p = 61, 144 KiB (512 MiB): 111 against 117 us; p = 128, 16 KiB (256 MiB): 46
+    //    against 52 us; level from 1 GiB on for 32 ranks and more, behind at 4 GiB from 125 ranks on (895 against
+    //    833 us).
+    //  - Form 4 (plain only for the stores that are read back, write-through for the others) on the capped grids of
+    //    the large calls: cfg4 3.075 against 3.114 ms, cfg5 3.21 against 3.25 ms, p = 96 with 1 MiB blocks 1.75
+    //    against 1.80 ms (form 1 there: 3.18 ms).  Not for the any-alignment form, which loses 4 % with it
+    //    (p = 128, B = 1 MiB + 4: 3.38 against 3.23 ms).
     const long long hot_knob = g_tree_hot.load();
     const uint64_t MiB = uint64_t(1) << 20;
     const bool hot_size = p < 32    ? total_bytes > 48 * MiB
                           : p <= 64 ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
                                     : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
-    const bool untouched = run_knob < 0 && lds_knob < 0 && st == 2 && g_tree_team_log2.load() < 0;
-    if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1 &&
-        (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched))) {
-        st = 1;
-        team = 1;
-        a.lg_k = 3;
+    const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && g_tree_team_log2.load() < 0;
+    bool uncap = false;
+    if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1) {
+        if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
+            st = 1;
+            uncap = lds_knob < 0;
+        } else if (hot_knob < 0 && untouched && capped && !any) {
+            st = 4;
+        }
+        if (st == 1 || st == 4) {
+            team = 1;
+            a.lg_k = 3;
+        }
     }
-    const uint32_t lds = st == 1 && lds_knob < 0 ? 0u : lds_by_size;
-    // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
-    // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
-    // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
-    if (any && row_bytes % 128 != 0 && st != 1) st = 0;
+    const uint32_t lds = uncap ? 0u : lds_by_size;
     // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
     // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
     if (algo == SPARBIT_ALGO_RING) st = 0;
@@ -1684,7 +1701,7 @@ int sparbit_tune(const char* key, long long value)
         if (value != 1 && value != 2) return SPARBIT_ERR_ARG;
         g_tree_unroll = value;
     } else if (!std::strcmp(key, "tree_store")) {
-        if (value != 0 && value != 2 && value != 3) return SPARBIT_ERR_ARG;
+        if (value < 0 || value > 4) return SPARBIT_ERR_ARG;
         g_tree_store = value;
     } else if (!std::strcmp(key, "tree_prefetch")) {
         g_tree_prefetch = value ? 1 : 0;

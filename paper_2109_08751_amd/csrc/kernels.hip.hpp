@@ -177,6 +177,8 @@ struct TreeArgs {
 // 1: plain stores, and a run of 8 is walked so that every forwarder is read back right after it was stored, while
 // its lines are still in the caches, and held in registers until its turn to forward (the form for calls that the
 // caches hold a good part of: no read leaves the XCD, and the write-back of such a call is cheap).
+// 4: the walk of 1 with the stores of 3 -- plain where the rank is read back at once, write-through for the ranks that
+// only receive and for the first ranks of far runs (the form for the largest calls).
 // The 16-byte accesses are raw buffer loads and stores: the base of a slot's piece is wave-uniform and sits in
 // scalar registers (no per-lane 64-bit address arithmetic), the piece's length is the buffer's size, so lanes past
 // a block's ragged end are dropped by the bounds check, and the cache-policy bits are an operand of the
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             for (int u = 0; u < U; ++u) {
                 const int at = int(lane * 16u + u * 1024u);
                 const raw4 v = __builtin_bit_cast(raw4, x.v[u]);
-                if (ST == 0 || ST == 1 || (ST == 3 && read_again_soon))
+                if (ST == 0 || ST == 1 || ((ST == 3 || ST == 4) && read_again_soon))
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, kBufferSc0Sc1);
@@ -479,7 +481,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     }
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;
-        if constexpr (ST == 1) {  // K = 8 (the host sees to it); PF: xh is this run's first rank, loaded by the run before
+        if constexpr (ST == 1 || ST == 4) {  // K = 8 (the host sees to it); PF: xh is this run's first rank, loaded by the run before
             static_assert(PF && U == 1, "the read-back-at-once walk keeps the next run's first rank in registers");
             auto to = [&](uint32_t n, uint32_t d, const H& x) {  // a forward, if both ranks exist
                 if (n < p && d < p - n) send_to(n, d, x);

@@ -50,7 +50,7 @@ def test_every_traversal_order(torch, run_log2, prefetch):
 
 
 @pytest.mark.parametrize("unroll", [1, 2])
-@pytest.mark.parametrize("store", [0, 2, 3])
+@pytest.mark.parametrize("store", [0, 1, 2, 3, 4])
 def test_piece_sizes_and_store_forms(torch, unroll, store):
     sb.sparbit_tune("tree_unroll", unroll)
     sb.sparbit_tune("tree_store", store)
