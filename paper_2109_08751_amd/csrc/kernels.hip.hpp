@@ -246,9 +246,19 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     const uint32_t lane = TEAM ? (threadIdx.x & 63u) : threadIdx.x;
     const uint32_t wave = TEAM ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
-    const uint32_t b = (group << a.lg_g) + (blockIdx.x & ((1u << a.lg_g) - 1u));  // the tree: origin rank = slot
-    if (b >= a.p) return;
+    // The tree (origin rank = slot) and the piece of it.  A last group of fewer than 2^lg_g trees interleaves just
+    // those, so that its pieces still go round all XCDs (p = 257: the last tree alone would run on one of them).
     const uint32_t p = a.p;
+    const uint32_t first = group << a.lg_g;
+    uint32_t b = first + (blockIdx.x & ((1u << a.lg_g) - 1u));
+    uint32_t piece_index = blockIdx.x >> a.lg_g;
+    if (first >= p) return;
+    if (p - first < (1u << a.lg_g)) {
+        const uint32_t t = p - first;
+        b = first + blockIdx.x % t;
+        piece_index = blockIdx.x / t;
+        if (piece_index >= (gridDim.x >> a.lg_g)) return;  // the grid holds 2^lg_g trees' pieces
+    }
     uint64_t offset = uint64_t(b) * a.block_bytes;  // this tree's block inside a row
     if constexpr (VAR) offset = a.displs[b];
     uint32_t piece_vectors;  // V's in this wavefront's piece
@@ -257,7 +267,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         const uint64_t bytes = VAR ? a.counts[b] : a.block_bytes;
         const uint64_t own = reinterpret_cast<uint64_t>(a.recv) + uint64_t(b) * a.row_bytes + offset;
         const uint64_t to_line = (0 - own) & 127u;  // block bytes ahead of the first line boundary
-        const uint64_t i = blockIdx.x >> a.lg_g;
+        const uint64_t i = piece_index;
         const uint64_t lo = i ? to_line + (i - 1) * 1024u : 0;
         uint64_t hi = to_line + i * 1024u;
         if (hi > bytes) hi = bytes;
@@ -267,7 +277,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         tail_bytes = uint32_t(hi - lo) & 15u;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
-        const uint64_t piece_at = uint64_t(blockIdx.x >> a.lg_g) * uint64_t(64 * U);  // first vector of the piece
+        const uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
         if (piece_at >= vectors) return;  // uniform: a shorter block has no such piece
         offset += piece_at * sizeof(V);
         const uint64_t left = vectors - piece_at;
