@@ -320,19 +320,22 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          and write-through to the others; 1 and 4 (Sparbit, 16-byte vectors; elsewhere they run as
  *                          0 and 2): runs of 8 with every forwarder read back right after it was stored, all stores
  *                          plain (1) or only those that are read back (4).  Left at 2, AUTO and MODE_TREE take 1 by
- *                          the tree_hot rule and, for blocks on the 16-byte grid, 4 on the capped grids (see tree_lds_bytes)
+ *                          the tree_hot rule and, for blocks on the 16-byte grid in calls of more than 336 MiB, 4
  *   "tree_hot"             Sparbit, 16-byte vectors (aligned blocks or the any-alignment form): plain stores, runs of
- *                          8, every forwarder read back
- *                          right after it was stored (-1, the default: for calls of 48 MiB .. 768 MiB up to 64 ranks,
- *                          of any size above 48 MiB below 32 ranks, of 96 .. 384 MiB beyond 64 ranks; 0 never; 1 always)
+ *                          8, every forwarder read back right after it was stored (-1, the default: for aligned
+ *                          blocks in calls of 48 MiB (from 65 ranks on: 96 MiB) .. 336 MiB; in the any-alignment form
+ *                          48 MiB .. 768 MiB up to 64 ranks, any size above 48 MiB below 32 ranks, 96 .. 384 MiB
+ *                          beyond 64 ranks; 0 never; 1 always).  Left at -1, with the other tree keys untouched,
+ *                          larger calls of aligned blocks take store form 4 on a capped grid (see tree_store)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
  *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the
  *                          tree kernel's any-alignment form (default 1; 0: one launch per step, realigning kernel)
  *   "tree_part_line_max_bytes"  ... in rows that are not a multiple of 128 bytes apart only for calls of at most
  *                          this many receive bytes (default 512 MiB)
  *   "tree_lds_bytes"       LDS each of its wavefronts reserves without using it, which caps the wavefronts per
- *                          compute unit (0..65536; 160 KiB per unit; -1, the default: 14336 for grids of 8192 and
- *                          more wavefronts on more than 32 ranks, else 0)
+ *                          compute unit (0..65536; 160 KiB per unit, handed out in granules of 1280 bytes; -1, the
+ *                          default: by form, size and rank count 0, 10240 (16 wavefronts per unit) or 14336 (10 per
+ *                          unit), the latter for grids of 8192 and more wavefronts on more than 32 ranks)
  */
 int sparbit_tune(const char *key, long long value);
 

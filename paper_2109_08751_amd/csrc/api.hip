@@ -750,10 +750,11 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     //    longer the runs, for more loads in flight per wavefront (p = 256, 2 KiB: 38 us with runs of 32, 43 us with
     //    runs of 16, 54 us with runs of 4; p = 256, 4 KiB: 55 us with runs of 16, 64 us with runs of 4; p = 64,
     //    64 KiB: 52 us with runs of 8, 47 us with runs of 4);
-    //  - when the grid has more wavefronts than the GPU holds, 11 resident ones per compute unit are enough to keep
+    //  - when the grid has more wavefronts than the GPU holds, 10 resident ones per compute unit are enough to keep
     //    the memory side busy, and fewer resident wavefronts mean fewer bytes between a write and its read-back:
-    //    each wavefront then reserves an eleventh of the unit's LDS, and the runs are 8 ranks (p = 128, 1 MiB:
-    //    3.12 ms; uncapped 3.45 ms; capped at 16 with runs of 4: 3.23 ms).
+    //    each wavefront then reserves 14336 bytes of the unit's 160 KiB of LDS (handed out in granules of 1280 bytes,
+    //    so 15360: a tenth), and the runs are 8 ranks (p = 128, 1 MiB: 3.12 ms; uncapped 3.45 ms; capped at 16 with
+    //    runs of 4: 3.23 ms).
     const uint64_t waves = pieces * uint64_t(p);
     const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
     // ... from 33 ranks on: a shorter tree is walked too quickly for that to pay (p = 16, 1 MiB: 58.6 us uncapped with
@@ -781,7 +782,7 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     }
     const long long lds_knob = g_tree_lds_bytes.load();
     // Recursive Doubling has no read that follows its write closely, so more resident wavefronts only help:
-    // 20 per unit (p = 128, 1 MiB: 4.61 ms; 11 per unit 4.99 ms; uncapped 4.66 ms).
+    // 18 per unit (8192 bytes each; p = 128, 1 MiB: 4.61 ms; 10 per unit 4.99 ms; uncapped 4.66 ms).
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
     const uint32_t lds_by_size = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
@@ -801,26 +802,46 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     //    the large calls: cfg4 3.075 against 3.114 ms, cfg5 3.21 against 3.25 ms, p = 96 with 1 MiB blocks 1.75
     //    against 1.80 ms (form 1 there: 3.18 ms).  Not for the any-alignment form, which loses 4 % with it
     //    (p = 128, B = 1 MiB + 4: 3.38 against 3.23 ms).
+    //  - From 336 MiB on, form 4 on a capped grid.  16 wavefronts per unit up to 48 ranks, up to 1.25 GiB on 49 .. 64
+    //    ranks and up to 480 MiB beyond, else 10 (p = 64, 128 KiB: 99 us with 16, 110 us with 10, uncapped 114 us; p = 48,
+    //    768 MiB: 156 / 161 / 166 us; p = 16, 4 MiB: 223 / 282 / 241 us; p = 33, 2 GiB: 415 / 433 / 419 us; p = 80,
+    //    762 MiB: 162 / 153 / 169 us; p = 125, 885 MiB: 185 / 178 / 194 us; p = 256, 24 KiB: 326 / 320 / 337 us).  The
+    //    other cap, or none, where the preferred one would leave a last round of few wavefronts among fewer than
+    //    three rounds (p = 125, 504 MiB, 4125 wavefronts on 4096 places: 118 us, uncapped 103 us; p = 253, 750 MiB,
+    //    3036 wavefronts on 2560 places: 186 us, uncapped 161 us; 875 MiB, 3542 wavefronts: 193 against 183 us).
     const long long hot_knob = g_tree_hot.load();
     const uint64_t MiB = uint64_t(1) << 20;
-    const bool hot_size = p < 32    ? total_bytes > 48 * MiB
+    const bool lines16 = width == 16 && !any;  // whole 16-byte vectors: what the figures above were measured on
+    const bool hot_size = lines16   ? total_bytes > (p <= 64 ? 48 : 96) * MiB && total_bytes <= 336 * MiB
+                          : p < 32  ? total_bytes > 48 * MiB
                           : p <= 64 ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
                                     : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
     const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && g_tree_team_log2.load() < 0;
-    bool uncap = false;
+    uint32_t lds = lds_by_size;
     if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1) {
         if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
             st = 1;
-            uncap = lds_knob < 0;
-        } else if (hot_knob < 0 && untouched && capped && !any) {
+            if (lds_knob < 0) lds = 0;
+        } else if (hot_knob < 0 && untouched && lines16 && total_bytes > 336 * MiB) {
             st = 4;
+            // LDS is handed out in granules of 1280 bytes: 10240 bytes each leave room for 16 wavefronts per unit,
+            // 14336 (12 granules) for 10.
+            struct Cap { uint32_t lds; uint64_t places; };
+            const Cap c16{10240u, 16 * 256}, c10{14336u, 10 * 256};
+            const bool prefer16 = p <= 48 || total_bytes < (p <= 64 ? 1280 : 480) * MiB;
+            const Cap first = prefer16 ? c16 : c10, second = prefer16 ? c10 : c16;
+            auto whole_rounds = [&](const Cap& c) {  // no last round that leaves most of the GPU idle
+                const uint64_t last = waves % c.places;
+                if (waves <= c.places || waves >= 3 * c.places || last == 0) return true;
+                return waves < 2 * c.places ? last * 5 >= c.places * 3 : last * 8 >= c.places * 3;
+            };
+            lds = whole_rounds(first) ? first.lds : (p > 32 && whole_rounds(second)) ? second.lds : 0u;
         }
         if (st == 1 || st == 4) {
             team = 1;
             a.lg_k = 3;
         }
     }
-    const uint32_t lds = uncap ? 0u : lds_by_size;
     // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
     // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
     if (algo == SPARBIT_ALGO_RING) st = 0;
