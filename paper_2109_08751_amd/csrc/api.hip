@@ -812,30 +812,40 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const long long hot_knob = g_tree_hot.load();
     const uint64_t MiB = uint64_t(1) << 20;
     const bool lines16 = width == 16 && !any;  // whole 16-byte vectors: what the figures above were measured on
-    const bool hot_size = lines16   ? total_bytes > (p <= 64 ? 48 : 96) * MiB && total_bytes <= 336 * MiB
-                          : p < 32  ? total_bytes > 48 * MiB
-                          : p <= 64 ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
-                                    : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
+    // The any-alignment form in rows on the lines: every store covers whole lines but for a block's first and last
+    // piece (plain stores, see the kernel), and the same forms win, with other caps (p = 32, 2 MiB + 4: 403 us with
+    // form 4 and 16 per unit, 453 us with the write-through walk; p = 256, 24 KiB + 4: 370 us uncapped, 413 / 478 us
+    // with 16 / 10 per unit; p = 128, 64 KiB + 4: 237 / 266 us with 16 / 10), from blocks of 10 KiB on (p = 256,
+    // 6 KiB + 4: 151 us against 132 us with the write-through walk) and below 8 GiB (beyond: level, or 1 % behind with
+    // per-slot sizes).
+    const bool lines_any = any && !part_lines;
+    const bool hot_size = lines16 || lines_any ? total_bytes > (p <= 64 ? 48 : 96) * MiB && total_bytes <= 336 * MiB
+                          : p < 32             ? total_bytes > 48 * MiB
+                          : p <= 64            ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
+                                               : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
     const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && g_tree_team_log2.load() < 0;
     uint32_t lds = lds_by_size;
     if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1) {
         if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
             st = 1;
             if (lds_knob < 0) lds = 0;
-        } else if (hot_knob < 0 && untouched && lines16 && total_bytes > 336 * MiB) {
+        } else if (hot_knob < 0 && untouched && total_bytes > 336 * MiB &&
+                   (lines16 || (lines_any && B >= 10240 && total_bytes < 8192 * MiB))) {
             st = 4;
             // LDS is handed out in granules of 1280 bytes: 10240 bytes each leave room for 16 wavefronts per unit,
             // 14336 (12 granules) for 10.
             struct Cap { uint32_t lds; uint64_t places; };
-            const Cap c16{10240u, 16 * 256}, c10{14336u, 10 * 256};
-            const bool prefer16 = p <= 48 || total_bytes < (p <= 64 ? 1280 : 480) * MiB;
-            const Cap first = prefer16 ? c16 : c10, second = prefer16 ? c10 : c16;
+            const Cap c16{10240u, 16 * 256}, c10{14336u, 10 * 256}, none{0u, 0};
+            const bool prefer16 = lines_any || p <= 48 || total_bytes < (p <= 64 ? 1280 : 480) * MiB;
+            const Cap first = prefer16 ? c16 : c10, second = lines_any || p <= 32 ? none : prefer16 ? c10 : c16;
             auto whole_rounds = [&](const Cap& c) {  // no last round that leaves most of the GPU idle
+                if (c.places == 0) return true;
                 const uint64_t last = waves % c.places;
                 if (waves <= c.places || waves >= 3 * c.places || last == 0) return true;
+                if (lines_any) return false;  // its first and last pieces are short: rounds are uneven anyway
                 return waves < 2 * c.places ? last * 5 >= c.places * 3 : last * 8 >= c.places * 3;
             };
-            lds = whole_rounds(first) ? first.lds : (p > 32 && whole_rounds(second)) ? second.lds : 0u;
+            lds = whole_rounds(first) ? first.lds : whole_rounds(second) ? second.lds : 0u;
         }
         if (st == 1 || st == 4) {
             team = 1;

@@ -263,6 +263,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     if constexpr (VAR) offset = a.displs[b];
     uint32_t piece_vectors;  // V's in this wavefront's piece
     uint32_t tail_bytes = 0;  // ANY: single bytes after them
+    bool part_of_a_line = false;  // ANY: the piece starts or ends inside a 128-byte line (a block's first and last piece)
     if constexpr (ANY) {
         const uint64_t bytes = VAR ? a.counts[b] : a.block_bytes;
         const uint64_t own = reinterpret_cast<uint64_t>(a.recv) + uint64_t(b) * a.row_bytes + offset;
@@ -275,6 +276,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         offset += lo;
         piece_vectors = uint32_t(hi - lo) >> 4;
         tail_bytes = uint32_t(hi - lo) & 15u;
+        part_of_a_line = i == 0 || hi - lo != 1024u;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
         const uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
@@ -319,7 +321,9 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             for (int u = 0; u < U; ++u) {
                 const int at = int(lane * 16u + u * 1024u);
                 const raw4 v = __builtin_bit_cast(raw4, x.v[u]);
-                if (ST == 0 || ST == 1 || ((ST == 3 || ST == 4) && read_again_soon))
+                // Write-through stores that cover part of a line are slow (the any-alignment form on 256 ranks with
+                // 4 KiB + 4 byte blocks, where two pieces in six are such: 328 us all write-through, 141 us this way).
+                if (ST == 0 || ST == 1 || ((ST == 3 || ST == 4) && read_again_soon) || (ANY && part_of_a_line))
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, 0);
                 else
                     __builtin_amdgcn_raw_buffer_store_b128(v, rd, at, 0, kBufferSc0Sc1);
@@ -327,7 +331,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             if constexpr (ANY) {
                 if (tail_bytes)
                     __builtin_amdgcn_raw_buffer_store_b8(x.tail, piece_buffer(d + piece_vectors * 16u, tail_bytes), int(lane), 0,
-                                                         (ST == 0 || ST == 1) ? 0 : kBufferSc0Sc1);
+                                                         0);
             }
         } else {
             V* dv = reinterpret_cast<V*>(d) + lane;
