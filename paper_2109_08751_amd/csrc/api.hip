@@ -855,6 +855,23 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
     // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
     if (algo == SPARBIT_ALGO_RING) st = 0;
+    // The two other schedules get the caps that the same sweeps found for them (336 MiB and more, no knob set), so
+    // that a comparison of the schedules compares tuned forms.  Ring: 16 per unit (p = 64, 128 KiB: 93 against 103 us;
+    // p = 128, 1 GiB: 195 against 206 us; 16 GiB: level with 10).  Recursive Doubling below 8 GiB: 10 per unit from 32
+    // ranks on (p = 128, 64 KiB: 239 against 290 us; p = 64, 1 MiB: 936 against 1116 us); on 16 GiB uncapped up to 64
+    // ranks (3.97 against 4.56 ms), 18 per unit beyond.
+    if (untouched && hot_knob < 0 && total_bytes > 336 * MiB && (algo == SPARBIT_ALGO_RING || doubling)) {
+        auto rounds_fit = [&](uint64_t places) {
+            const uint64_t last = waves % places;
+            return waves <= places || waves >= 3 * places || last == 0 || last * 5 >= places * 3;
+        };
+        if (algo == SPARBIT_ALGO_RING)
+            lds = rounds_fit(16 * 256) ? 10240u : (p > 32 && rounds_fit(10 * 256)) ? 14336u : 0u;
+        else if (total_bytes < 8192 * MiB)
+            lds = (p >= 32 && rounds_fit(10 * 256)) ? 14336u : 0u;
+        else
+            lds = p <= 64 ? 0u : 8192u;
+    }
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
     const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team};
