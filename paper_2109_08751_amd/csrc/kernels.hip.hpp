@@ -175,8 +175,9 @@ struct TreeArgs {
 // written back later.  2: write-through at system scope (sc0 sc1), the line goes straight to the memory side.
 // 3: by destination -- plain for a rank that forwards and is read again soon, write-through for the others.
 // 1: plain stores, and a run of 8 is walked so that every forwarder is read back right after it was stored, while
-// its lines are still in the caches, and held in registers until its turn to forward (the form for calls that the
-// caches hold a good part of: no read leaves the XCD, and the write-back of such a call is cheap).
+// its lines are still in the caches, and held in registers until its turn to forward; so are the first ranks of the
+// runs 8, 16 and 32 ranks ahead (the form for calls that the caches hold a good part of: no read leaves the XCD but
+// that of every eighth run's first rank, and the write-back of such a call is cheap).
 // 4: the walk of 1 with the stores of 3 -- plain where the rank is read back at once, write-through for the ranks that
 // only receive and for the first ranks of far runs (the form for the largest calls).
 // The 16-byte accesses are raw buffer loads and stores: the base of a slot's piece is wave-uniform and sits in
@@ -493,6 +494,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         }
         return;
     }
+    H y16, y32;  // store forms 1 and 4: the first ranks of the runs 16 and 32 ranks ahead, read back when they were stored
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;
         if constexpr (ST == 1 || ST == 4) {  // K = 8 (the host sees to it); PF: xh is this run's first rank, loaded by the run before
@@ -504,7 +506,17 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
                 if (n < p && forwards(n)) load(slot(n), x);
             };
             const uint32_t dmax = h ? ((h & (0u - h)) >> 1) : a.top;
-            for (uint32_t d = dmax; d > 8; d >>= 1) to(h, d, xh);
+            for (uint32_t d = dmax; d > 32; d >>= 1) to(h, d, xh);
+            // The first ranks of the runs at +32 and +16 are read back at once as well and kept until those runs
+            // begin, so that only every eighth run starts with a load of what an earlier run stored long ago.
+            if (dmax >= 32) {
+                if (h + 32 < p) store(slot(h + 32), xh, true);
+                back(h + 32, y32);
+            }
+            if (dmax >= 16) {
+                if (h + 16 < p) store(slot(h + 16), xh, true);
+                back(h + 16, y16);
+            }
             H x4, x2, x6, xn;
             if (dmax >= 8) {
                 to(h, 8, xh);
@@ -522,7 +534,12 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
             to(h + 2, 1, x2);
             wait_for_loads();
             to(h + 6, 1, x6);
-            if (dmax < 8) back(h + 8, xn);  // stored by an earlier run
+            if (dmax < 8) {  // the next run's first rank was stored by an earlier run
+                const uint32_t hn = h + 8;
+                if ((hn & 31u) == 16u) xn = y16;       // ... 16 ranks back, which kept it
+                else if ((hn & 63u) == 32u) xn = y32;  // ... 32 ranks back
+                else back(hn, xn);
+            }
             xh = xn;
             continue;
         }

@@ -209,10 +209,12 @@ def test_auto_forms_teams_for_small_calls_of_many_ranks(torch):
 def test_forwarders_read_back_at_once(torch):
     """The form for calls that the caches hold a good part of: plain stores, runs of 8, every forwarder read back
     right after it was stored and kept in registers until its turn.  Forced onto every rank count around the run
-    length and the powers of two (last runs of 1 .. 8 ranks, trees shorter than a run), in place; and AUTO's own
-    choice of it.  (Per-slot sizes: test_allgatherv.py.)"""
+    length, the powers of two and the multiples of 16, 32 and 64 (last runs of 1 .. 8 ranks, trees shorter than a run,
+    runs whose first rank was kept in registers since it was stored 8, 16 or 32 ranks earlier, or is loaded), in place;
+    and AUTO's own choice of it.  (Per-slot sizes: test_allgatherv.py.)"""
     sb.sparbit_tune("tree_hot", 1)
-    for p in (1, 2, 3, 5, 7, 8, 9, 10, 15, 16, 17, 21, 23, 24, 25, 31, 32, 33, 40, 63, 64, 65, 96, 127, 129, 257):
+    for p in (1, 2, 3, 5, 7, 8, 9, 10, 15, 16, 17, 21, 23, 24, 25, 31, 32, 33, 40, 41, 47, 48, 49, 56, 57, 63, 64, 65, 72, 73,
+              81, 96, 97, 113, 127, 129, 145, 193, 200, 257):
         for B in (16, 1024, 4096 + 128) if p <= 65 else (1024,):  # whole vectors on whole lines, or short blocks
             in_place = (p + B) % 3 == 0
             announce("tree read back at once", p, B, in_place)
