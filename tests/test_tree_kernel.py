@@ -236,6 +236,31 @@ def test_forwarders_read_back_at_once(torch):
         assert np.array_equal(got, want), (p, B)
 
 
+@pytest.mark.parametrize("algo,p,B", [
+    ("sparbit", 61, 131072),   # 465 MiB, 7808 wavefronts: 16 resident per unit
+    ("sparbit", 125, 33792),   # 504 MiB, 4125 wavefronts: a cap of 4096 would leave a round of 29, so another or none
+    ("sparbit", 33, 393216),   # 408 MiB on few ranks
+    ("sparbit", 16, 2 << 20),  # 512 MiB on fewer ranks than a capped grid used to need
+    ("sparbit", 64, 131072 + 4),   # the any-alignment form in rows on the lines
+    ("sparbit", 96, 57344),    # 504 MiB, 5376 wavefronts
+    ("ring", 64, 131072), ("recursive_doubling", 64, 131072)])
+def test_calls_of_some_hundred_mib(torch, algo, p, B):
+    """Between the calls the caches hold and the 16 GiB ones AUTO picks store form 4 on a grid capped by size, rank
+    count and the fill of its last round (Ring and Recursive Doubling: their own caps): every byte against the
+    oracle, and the form that ran."""
+    a = {"sparbit": sb.SPARBIT, "ring": sb.RING, "recursive_doubling": sb.RECURSIVE_DOUBLING}[algo]
+    announce("some hundred MiB", algo, p, B)
+    send = workloads.make_send_raw(p, B, seed=p + 3)
+    want = oracle_result(a, p, B, send)
+    got = gpu_result(torch, a, p, B, send, sb.MODE_AUTO)
+    name = sb.sparbit_last_launch_info()[0]
+    assert "tree_kernel" in name, name
+    if algo == "sparbit":
+        assert ", 8, 4, true, " in name, name
+        assert launched_any_alignment_form() == (B % 16 != 0)
+    assert np.array_equal(got, want), (algo, p, B)
+
+
 def launched_doubling_form():
     name = sb.sparbit_last_launch_info()[0]
     return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "1"
