@@ -120,7 +120,7 @@ def make_device_send(torch, w, dev):
 def algorithmic_bytes(form, p, B):
     """HBM bytes one call has to move, by the form it is issued in (see the module docstring).
     `form`: "per_step" (also persistent / dataflow: every forward reads what an earlier phase wrote), "tree"
-    (Sparbit: a forwarder is read back right after it was written), "tree_doubling" (Recursive Doubling in that form),
+    (a forwarder is read back right after it was written), "tree_doubling" (Recursive Doubling walked in step order),
     "direct" (every slot straight from the send buffer), "copy" (a device-to-device copy of p*p*B bytes)."""
     landed = p * p * B
     if form in ("tree", "direct"):
@@ -136,15 +136,18 @@ def form_of(kernel_name, algo_label="sparbit"):
     if algo_label == "memcpy_d2d":
         return "copy"
     if "tree_kernel" in kernel_name:
-        return "tree_doubling" if tree_kernel_flags(kernel_name)["walk"] == "doubling" else "tree"
+        flags = tree_kernel_flags(kernel_name)
+        # Recursive Doubling walked in step order reads a forwarder a whole step after it was written; with store
+        # forms 1 and 4 it is walked like Sparbit's tree (bits of the relative rank reversed) and read back at once
+        return "tree_doubling" if flags["walk"] == "doubling" and flags["store"] not in (1, 4) else "tree"
     return "per_step"
 
 
 def tree_kernel_flags(kernel_name):
-    """The last three template arguments of the tree kernel's name as the library reports it."""
+    """The store form and the last three template arguments of the tree kernel's name as the library reports it."""
     args = kernel_name.rstrip(">").split(", ")
-    return {"any_alignment": args[-3] == "true", "walk": ("sparbit", "doubling", "chain")[int(args[-2])],
-            "team": args[-1] == "true"}
+    return {"store": int(args[-6]), "any_alignment": args[-3] == "true",
+            "walk": ("sparbit", "doubling", "chain")[int(args[-2])], "team": args[-1] == "true"}
 
 
 def rates(p, B, ms, form):

@@ -622,12 +622,16 @@ template <typename V, int U, int NB, bool VAR, bool ANY = false, int WALK = kWal
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream,
                    uint32_t team = 1)
 {
-    constexpr bool kStepOrderOnly = WALK != kWalkSparbit;  // no runs: no look-ahead, and plain or write-through stores
     if (sizeof(V) != 16) store_kind = 0;
-    if (kStepOrderOnly || team > 1) prefetch = false;
-    if ((kStepOrderOnly || team > 1) && store_kind == 3) store_kind = 2;
-    if ((kStepOrderOnly || team > 1) && store_kind == 1) store_kind = 0;
-    if ((kStepOrderOnly || team > 1) && store_kind == 4) store_kind = 2;
+    // Ring's chain has no runs: no look-ahead, plain or write-through stores.  Recursive Doubling's tree has them
+    // only in store forms 1 and 4 (walked as Sparbit's tree with the bits of the relative rank reversed), on whole
+    // 16-byte vectors, one per lane, without teams.
+    const bool reversed = WALK == kWalkDoubling && (store_kind == 1 || store_kind == 4) && sizeof(V) == 16 && U == 1 && team == 1;
+    const bool step_order_only = WALK != kWalkSparbit && !reversed;
+    if (step_order_only || team > 1) prefetch = false;
+    if ((step_order_only || team > 1) && store_kind == 3) store_kind = 2;
+    if ((step_order_only || team > 1) && store_kind == 1) store_kind = 0;
+    if ((step_order_only || team > 1) && store_kind == 4) store_kind = 2;
     if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
@@ -643,7 +647,15 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
             return SPARBIT_OK;
         }
     }
-    if constexpr (kStepOrderOnly) {
+    if constexpr (WALK == kWalkDoubling && sizeof(V) == 16 && U == 1) {
+        if (reversed) {
+            if (store_kind == 1) SB_TREE(1, true);
+            else SB_TREE(4, true);
+            SB_HIP(hipGetLastError());
+            return SPARBIT_OK;
+        }
+    }
+    if constexpr (WALK != kWalkSparbit) {
         if (store_kind != 0) SB_TREE(2, false);
         else SB_TREE(0, false);
     } else if constexpr (ANY) {  // the store forms that lost on whole vectors are not built a second time
@@ -825,7 +837,9 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
                                                : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
     const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && g_tree_team_log2.load() < 0;
     uint32_t lds = lds_by_size;
-    if (algo == SPARBIT_ALGO_SPARBIT && (width == 16 || any) && U == 1) {
+    // Recursive Doubling's tree is Sparbit's with the bits of the relative rank reversed, so forms 1 and 4 walk it
+    // too and the same choices hold (p = 128, 1 MiB: 3.07 ms like Sparbit, 4.55 ms in step order).
+    if ((algo == SPARBIT_ALGO_SPARBIT || doubling) && (width == 16 || any) && U == 1) {
         if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
             st = 1;
             if (lds_knob < 0) lds = 0;
@@ -857,10 +871,11 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     if (algo == SPARBIT_ALGO_RING) st = 0;
     // The two other schedules get the caps that the same sweeps found for them (336 MiB and more, no knob set), so
     // that a comparison of the schedules compares tuned forms.  Ring: 16 per unit (p = 64, 128 KiB: 93 against 103 us;
-    // p = 128, 1 GiB: 195 against 206 us; 16 GiB: level with 10).  Recursive Doubling below 8 GiB: 10 per unit from 32
-    // ranks on (p = 128, 64 KiB: 239 against 290 us; p = 64, 1 MiB: 936 against 1116 us); on 16 GiB uncapped up to 64
-    // ranks (3.97 against 4.56 ms), 18 per unit beyond.
-    if (untouched && hot_knob < 0 && total_bytes > 336 * MiB && (algo == SPARBIT_ALGO_RING || doubling)) {
+    // p = 128, 1 GiB: 195 against 206 us; 16 GiB: level with 10).  Recursive Doubling where it still walks in step
+    // order (the forms above switched off, or rows off the lines), below 8 GiB: 10 per unit from 32 ranks on (p = 128,
+    // 64 KiB: 239 against 290 us; p = 64, 1 MiB: 936 against 1116 us); on 16 GiB uncapped up to 64 ranks (3.97 against
+    // 4.56 ms), 18 per unit beyond.
+    if (untouched && hot_knob < 0 && total_bytes > 336 * MiB && st != 1 && st != 4 && (algo == SPARBIT_ALGO_RING || doubling)) {
         auto rounds_fit = [&](uint64_t places) {
             const uint64_t last = waves % places;
             return waves <= places || waves >= 3 * places || last == 0 || last * 5 >= places * 3;

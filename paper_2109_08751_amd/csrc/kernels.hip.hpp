@@ -218,7 +218,10 @@ struct Held {
 // rank xor b, step s sends from every rho < 2^s to rho + 2^s.  So rho receives in the step of its highest set bit and
 // forwards in every later step, i.e. every rho below p/2 forwards and its destinations are far away.  The walk is
 // the step order: the ranks that received in one step are loaded in batches and each is stored to all its
-// destinations; the runs of the Sparbit walk have no counterpart (a rank's first forward is a whole step later).
+// destinations.  With store forms 1 and 4 it is walked like Sparbit's tree instead: under sigma = rho with its
+// log2(p) bits reversed the two trees are the same (rho < 2^s means sigma is a multiple of 2^(L - s), and rho + 2^s is
+// sigma + 2^(L - 1 - s), a distance below sigma's lowest set bit), so the runs and the read-back-at-once walk below
+// serve with the rank found as b xor the reversed bits of the walk's relative rank.
 //
 // TEAM: several wavefronts per workgroup share one piece of one tree, for calls so small that the time is one
 // wavefront's walk through all p ranks (its address arithmetic alone is ~100 ns per rank).  The tree is cut into
@@ -242,7 +245,9 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     constexpr bool DOUBLING = WALK == kWalkDoubling, CHAIN = WALK == kWalkChain;
     static_assert(!CHAIN || (!PF && !TEAM), "a chain has nothing to look ahead of and nothing to share");
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
-    static_assert(!DOUBLING || !PF, "the doubling walk has no run to look ahead of");
+    constexpr bool REVERSED = DOUBLING && (ST == 1 || ST == 4);  // the doubling tree walked as Sparbit's, bits reversed
+    static_assert(!DOUBLING || !PF || REVERSED, "the step-order doubling walk has no run to look ahead of");
+    static_assert(!REVERSED || !TEAM, "teams walk the doubling tree by the low bits of the relative rank");
     static_assert(!TEAM || (!PF && U == 1), "a team's wavefronts walk one part of the tree each, one vector per lane");
     const uint32_t lane = TEAM ? (threadIdx.x & 63u) : threadIdx.x;
     const uint32_t wave = TEAM ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
@@ -293,7 +298,9 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     // The piece of slot b held by the rank at relative rank rho (wave-uniform).  No __restrict__ anywhere: a slot
     // is written and later read.
     auto slot = [&](uint32_t rho) -> uint8_t* {
-        uint32_t r = DOUBLING ? (b ^ rho) : b + rho;
+        uint32_t r;
+        if constexpr (REVERSED) r = b ^ (__builtin_bitreverse32(rho) >> __builtin_clz(a.top | 1u));  // a.top = p / 2 (0: one rank)
+        else r = DOUBLING ? (b ^ rho) : b + rho;
         if (r >= p) r -= p;
         return a.recv + uint64_t(r) * a.row_bytes + offset;
     };
@@ -477,7 +484,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         }
         return;
     }
-    if constexpr (DOUBLING) {
+    if constexpr (DOUBLING && !REVERSED) {
         for (uint32_t d = 1; d < p; d <<= 1) store(slot(d), xh, false);  // the origin sends in every step
         for (uint32_t lvl = 1; 2 * lvl < p; lvl <<= 1) {  // rho in [lvl, 2 lvl) received in the step with distance lvl
             for (uint32_t n0 = lvl; n0 < 2 * lvl; n0 += NB) {

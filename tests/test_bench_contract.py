@@ -48,8 +48,11 @@ def test_forms_are_read_off_the_kernel_name():
     chain = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, false, 2, false>"
     assert b.form_of(tree) == "tree" and b.form_of(anyal) == "tree" and b.form_of(doubling) == "tree_doubling"
     assert b.form_of(chain) == "tree"  # a chain's re-reads follow their writes at once: the tree form's byte count
-    assert b.tree_kernel_flags(anyal) == {"any_alignment": True, "walk": "sparbit", "team": False}
-    assert b.tree_kernel_flags(doubling) == {"any_alignment": False, "walk": "doubling", "team": True}
+    assert b.tree_kernel_flags(anyal) == {"store": 2, "any_alignment": True, "walk": "sparbit", "team": False}
+    assert b.tree_kernel_flags(doubling) == {"store": 2, "any_alignment": False, "walk": "doubling", "team": True}
+    # Recursive Doubling in store forms 1 and 4 is walked like Sparbit's tree: read back at once
+    reversed_bits = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 1, false>"
+    assert b.form_of(reversed_bits) == "tree" and b.tree_kernel_flags(reversed_bits)["store"] == 4
     assert b.form_of("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 64, 1, true, false, true>") == "per_step"
     assert b.form_of("anything", "direct") == "direct" and b.form_of("anything", "memcpy_d2d") == "copy"
     for key in b.MEASURED_TRAFFIC:  # the table's kernel names parse, and name the tree kernel without teams

@@ -267,10 +267,12 @@ def launched_doubling_form():
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}, {"tree_team_log2": 0}, {"tree_team_log2": 1},
-                                   {"tree_team_log2": 2, "tree_store": 0}, {"tree_team_log2": 4}])
+                                   {"tree_team_log2": 2, "tree_store": 0}, {"tree_team_log2": 4}, {"tree_hot": 1},
+                                   {"tree_store": 4, "tree_small_bytes": 0}])
 def test_recursive_doubling_in_the_tree_form(torch, knobs):
     """Recursive Doubling seen by block is a binomial tree as well (relative rank = rank xor origin, a rank forwards
-    in every step after the one it received in); the same one-launch form walks it in step order.  Every power of
+    in every step after the one it received in); the same one-launch form walks it in step order, or, in store forms
+    1 and 4, like Sparbit's tree with the bits of the relative rank reversed.  Every power of
     two up to 256, blocks on and off the grids, in place, explicit mode and AUTO; one wavefront per piece and teams of
     2 .. 16 (the tree split by the low bits of the relative rank)."""
     for k, v in knobs.items():
@@ -305,6 +307,7 @@ def test_recursive_doubling_in_the_tree_form_at_full_size(torch):
     sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.RECURSIVE_DOUBLING, sb.MODE_AUTO)
     torch.cuda.synchronize()
     assert launched_doubling_form(), sb.sparbit_last_launch_info()
+    assert ", 8, 4, true, " in sb.sparbit_last_launch_info()[0]  # walked like Sparbit's tree, bits reversed
     for r in range(p):
         assert torch.equal(d_recv[r], d_send), r
     small = workloads.make_send_raw(p, 4, seed=3)
