@@ -118,7 +118,8 @@ extern "C" {
                                      wavefront (in small calls: every team of 4 or 8 wavefronts of one workgroup)
                                      carries one piece of one block through that block's binomial tree
                                      (Section III-B: the p trees are independent; Recursive Doubling's messages,
-                                     seen by block, form such trees too, with rank xor origin as the relative rank;
+                                     seen by block, form such trees too, with rank xor origin as the relative rank
+                                     (the same tree as Sparbit's once the bits of that relative rank are reversed);
                                      Ring's form a chain per block).  Same messages as Algorithm 1, each read from the
                                      forwarder's receive buffer; a forwarder's reads of one slot for different steps
                                      are merged, and the order is any order in which a rank forwards after it
@@ -317,17 +318,19 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_small_bytes"     calls of at most this many receive bytes walk it in step order instead (default 96 MiB)
  *   "tree_unroll"          16-byte vectors per lane of the tree kernel: 1 or 2
  *   "tree_store"           its stores: 0 plain, 2 write-through (default), 3 plain to ranks that are read again soon
- *                          and write-through to the others; 1 and 4 (Sparbit, 16-byte vectors; elsewhere they run as
- *                          0 and 2): runs of 8 with every forwarder read back right after it was stored, all stores
- *                          plain (1) or only those that are read back (4).  Left at 2, AUTO and MODE_TREE take 1 by
- *                          the tree_hot rule and, in calls of more than 336 MiB, 4 (see tree_hot)
- *   "tree_hot"             Sparbit, 16-byte vectors (aligned blocks or the any-alignment form): plain stores, runs of
- *                          8, every forwarder read back right after it was stored (-1, the default: in calls of 48 MiB
- *                          (from 65 ranks on: 96 MiB) .. 336 MiB; the any-alignment form in rows that are not a
- *                          multiple of 128 bytes in calls of 48 MiB .. 768 MiB up to 64 ranks, above 48 MiB below 32
- *                          ranks, 96 .. 384 MiB beyond 64 ranks; 0 never; 1 always).  Left at -1, with the other tree
- *                          keys untouched, larger calls take store form 4 on a capped grid (see tree_store; the
- *                          any-alignment form only in rows on the lines, blocks of 10 KiB and more, below 8 GiB)
+ *                          and write-through to the others; 1 and 4 (Sparbit and Recursive Doubling, 16-byte
+ *                          vectors; elsewhere they run as 0 and 2): runs of 8 with every forwarder read back right
+ *                          after it was stored, all stores plain (1) or only those that are read back (4).  Left at
+ *                          2, AUTO and MODE_TREE take 1 by the tree_hot rule and, in calls of more than 336 MiB, 4
+ *                          (see tree_hot)
+ *   "tree_hot"             Sparbit and Recursive Doubling, 16-byte vectors (aligned blocks or the any-alignment
+ *                          form): plain stores, runs of 8, every forwarder read back right after it was stored (-1,
+ *                          the default: in calls of 48 MiB (from 65 ranks on: 96 MiB) .. 336 MiB; the any-alignment
+ *                          form in rows that are not a multiple of 128 bytes in calls of 48 MiB .. 768 MiB up to 64
+ *                          ranks, above 48 MiB below 32 ranks, 96 .. 384 MiB beyond 64 ranks; 0 never; 1 always).
+ *                          Left at -1, with the other tree keys untouched, larger calls take store form 4 on a capped
+ *                          grid (see tree_store; the any-alignment form only in rows on the lines, blocks of 10 KiB
+ *                          and more, below 8 GiB)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
  *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the
  *                          tree kernel's any-alignment form (default 1; 0: one launch per step, realigning kernel)
