@@ -722,6 +722,141 @@ int launch_tree_as(const TreeArgs& a, const TreeLaunch& h)
     return launch_tree_vu<uint8_t, 1, 8, VAR, false, WALK>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
 }
 
+// How launch_tree's wavefronts walk their trees, and how many of them a compute unit holds at once.
+struct TreeWalk {
+    uint32_t lg_k;  // runs of 2^lg_k relative ranks (with teams: one run per wavefront; Recursive Doubling: 2^lg_k sub-trees)
+    uint32_t team;  // wavefronts per workgroup that share one piece of one tree
+    int store;      // the kernel's store form
+    uint32_t lds;   // bytes of LDS each wavefront reserves without using them: caps the resident wavefronts per unit
+};
+struct TreeCall {
+    int algo, p;
+    size_t B;         // the (longest) block
+    bool any;         // the any-alignment form ...
+    bool part_lines;  // ... in rows that are not a multiple of 128 bytes apart: stores cover parts of lines at most ranks
+    int width, U;     // bytes per access (any: 0) and 16-byte vectors per lane
+    uint64_t total_bytes, waves;  // receive bytes of the call; wavefronts (teams) of the grid
+};
+
+// Every figure below was measured on an MI355X; the kernel's comment explains the terms.  LDS is handed out in
+// granules of 1280 bytes (measured with a kernel that only sleeps): 10240 bytes per wavefront leave room for 16
+// wavefronts per compute unit, 14336 bytes (12 granules) for 10, 8192 bytes (7 granules) for 18.
+//
+// Without the knobs, by receive bytes of the call:
+//  - up to 96 MiB (tree_small_bytes): step order, the fewest dependent round trips of a latency-bound call; from 33
+//    ranks on a team of 4 wavefronts, from 65 on of 8, walks a piece's tree (p = 256, 128-byte blocks: 9.9 us of kernel
+//    time against 27 us; what is left is the depth of the tree, ceil(log2 p) dependent hops of ~1.2 us).  Otherwise:
+//  - grids of fewer than 4096 wavefronts: runs of 32, 16 or 8 ranks as the grid has fewer than 1024, 2048 or more
+//    wavefronts, for more loads in flight per wavefront (p = 256, 2 KiB: 38 us with runs of 32, 43 us with 16, 54 us
+//    with 4; p = 256, 4 KiB: 55 us with runs of 16, 64 us with 4); larger grids: runs of 4, write-through stores;
+//  - Sparbit and Recursive Doubling (the same tree, see the kernel), whole 16-byte vectors or the any-alignment form:
+//    from 48 MiB (96 MiB from 65 ranks on) to 336 MiB store form 1, uncapped: plain stores, runs of 8, every
+//    forwarder read back right after it was stored (against the write-through walk: p = 16, 1 MiB: 48 against 57 us;
+//    p = 64, 64 KiB: 42 against 48 us; p = 128, 16 KiB (256 MiB): 46 against 52 us);
+//  - beyond 336 MiB store form 4 (that walk, write-through for the stores that are not read back) on a capped grid.
+//    16 wavefronts per unit up to 48 ranks, up to 1.25 GiB on 49 .. 64 ranks and up to 480 MiB beyond, else 10 (p = 64,
+//    128 KiB: 99 us with 16, 110 us with 10, uncapped 114 us; p = 48, 768 MiB: 156 / 161 / 166 us; p = 16, 4 MiB: 223 /
+//    282 / 241 us; p = 33, 2 GiB: 415 / 433 / 419 us; p = 80, 762 MiB: 162 / 153 / 169 us; p = 125, 885 MiB: 185 / 178 /
+//    194 us; p = 256, 24 KiB: 326 / 320 / 337 us; cfg4 3.21 / 3.07 / 3.48 ms, 3.11-3.15 ms with the write-through walk
+//    on 10 per unit; cfg5 3.33 / 3.21 / 3.52 ms, 3.25 ms).  A cap turns the grid into rounds of 4096 or 2560
+//    wavefronts, and a last round of a few wavefronts costs a whole round: with fewer than three rounds the preferred
+//    cap is taken only if its last round is 3/8 full (3/5 with fewer than two rounds), else the other cap on the same
+//    condition, else none (p = 125, 504 MiB, 4125 wavefronts on 4096 places: 118 us, uncapped 103 us; p = 253, 750 MiB,
+//    3036 wavefronts on 2560 places: 186 against 161 us; 875 MiB, 3542 wavefronts: 193 against 183 us);
+//  - the any-alignment form in rows on the lines takes form 4 from blocks of 10 KiB on (p = 256, 6 KiB + 4: 151 us
+//    against 132 us with the write-through walk) and below 8 GiB (beyond: level, or 1 % behind with per-slot sizes),
+//    with 16 per unit or no cap, and a cap only from three rounds on: its first and last pieces are short, so its
+//    rounds are uneven anyway (p = 32, 2 MiB + 4: 403 us with 16 per unit, 453 us with the write-through walk; p = 256,
+//    24 KiB + 4: 370 us uncapped, 413 / 478 us with 16 / 10 per unit; p = 128, 64 KiB + 4: 237 / 266 us with 16 / 10);
+//  - the any-alignment form in other rows: plain stores, since a piece's stores cover part-lines at most ranks, which
+//    write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of several
+//    GiB 5.6-6.1 ms against 6.5-8.6 ms), and form 1 by the earlier rule (48 MiB .. 768 MiB up to 64 ranks, any size
+//    above 48 MiB below 32 ranks, 96 .. 384 MiB beyond 64 ranks);
+//  - what is left of the large calls (the knobs switch the forms above off, narrow accesses): the write-through walk
+//    in runs of 8 on 10 wavefronts per unit when the grid has 8192 wavefronts and more on more than 32 ranks (p = 128,
+//    1 MiB: 3.12 ms; uncapped 3.45 ms; capped at 16 with runs of 4: 3.23 ms; a shorter tree is walked too quickly for
+//    that to pay: p = 16, 1 MiB: 58.6 us uncapped with runs of 4, 66.6 us capped with runs of 8);
+//  - Ring: plain stores always (the chain reads a rank back right after storing it, and a plain store leaves the line
+//    in the L2 for that read: p = 128, 1 MiB: 3.23 ms; a write-through store makes every hop wait for the memory side:
+//    13.3 ms); beyond 336 MiB 16 wavefronts per unit (p = 64, 128 KiB: 93 against 103 us; p = 128, 1 GiB: 195 against
+//    206 us; 16 GiB: level with 10), so that a comparison of the schedules compares tuned forms;
+//  - Recursive Doubling where it still walks in step order beyond 336 MiB: below 8 GiB 10 per unit from 32 ranks on
+//    (p = 128, 64 KiB: 239 against 290 us; p = 64, 1 MiB: 936 against 1116 us); on 16 GiB uncapped up to 64 ranks (3.97
+//    against 4.56 ms), 18 per unit beyond (p = 128, 1 MiB: 4.61 ms; 10 per unit 4.99 ms; uncapped 4.66 ms).
+TreeWalk choose_tree_walk(const TreeCall& c)
+{
+    const int p = c.p;
+    const uint64_t MiB = uint64_t(1) << 20, total_bytes = c.total_bytes, waves = c.waves;
+    const bool doubling = c.algo == SPARBIT_ALGO_RECURSIVE_DOUBLING, ring = c.algo == SPARBIT_ALGO_RING;
+    const long long run_knob = g_tree_run_log2.load(), lds_knob = g_tree_lds_bytes.load(), hot_knob = g_tree_hot.load();
+    const long long team_knob = g_tree_team_log2.load();
+    const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && team_knob < 0;
+    const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
+    const bool capped = waves >= 8192 && p > 32;
+    TreeWalk w;
+    w.lg_k = run_knob >= 0 ? uint32_t(run_knob)
+                           : small ? uint32_t(ceil_log2(p))
+                           : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
+    w.team = 1;
+    if (c.U == 1 && !ring) {
+        const int lg_p = ceil_log2(p);
+        int lg_team = team_knob >= 0 ? int(team_knob) : (small && run_knob < 0 && p > 32) ? (p > 64 ? 3 : 2) : 0;
+        if (lg_team > lg_p - 1) lg_team = lg_p > 1 ? lg_p - 1 : 0;  // at least 2 ranks per wavefront
+        if (lg_team > 0) {
+            w.team = 1u << lg_team;
+            // Sparbit: runs of 2^lg_k ranks, one per wavefront; Recursive Doubling: 2^lg_k sub-trees, by low bits
+            w.lg_k = doubling ? uint32_t(lg_team) : uint32_t(lg_p - lg_team);
+        }
+    }
+    w.lds = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
+    w.store = int(g_tree_store.load());
+    if (c.part_lines && w.store != 1) w.store = 0;
+    struct Cap { uint32_t lds; uint64_t places; };
+    const Cap c16{10240u, 16 * 256}, c10{14336u, 10 * 256}, none{0u, 0};
+    const bool lines16 = c.width == 16 && !c.any, lines_any = c.any && !c.part_lines;
+    auto whole_rounds = [&](const Cap& cap, bool from_three_rounds_only) {  // no last round that leaves most of the GPU idle
+        if (cap.places == 0) return true;
+        const uint64_t last = waves % cap.places;
+        if (waves <= cap.places || waves >= 3 * cap.places || last == 0) return true;
+        if (from_three_rounds_only) return false;
+        return waves < 2 * cap.places ? last * 5 >= cap.places * 3 : last * 8 >= cap.places * 3;
+    };
+    if ((c.algo == SPARBIT_ALGO_SPARBIT || doubling) && (c.width == 16 || c.any) && c.U == 1) {
+        const bool hot_size = lines16 || lines_any ? total_bytes > (p <= 64 ? 48 : 96) * MiB && total_bytes <= 336 * MiB
+                              : p < 32             ? total_bytes > 48 * MiB
+                              : p <= 64            ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
+                                                   : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
+        if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
+            w.store = 1;
+            if (lds_knob < 0) w.lds = 0;
+        } else if (hot_knob < 0 && untouched && total_bytes > 336 * MiB &&
+                   (lines16 || (lines_any && c.B >= 10240 && total_bytes < 8192 * MiB))) {
+            w.store = 4;
+            const bool prefer16 = lines_any || p <= 48 || total_bytes < (p <= 64 ? 1280 : 480) * MiB;
+            const Cap first = prefer16 ? c16 : c10, second = lines_any || p <= 32 ? none : prefer16 ? c10 : c16;
+            w.lds = whole_rounds(first, lines_any) ? first.lds : whole_rounds(second, lines_any) ? second.lds : 0u;
+        }
+        if (w.store == 1 || w.store == 4) {  // those walks are runs of 8 by one wavefront
+            w.team = 1;
+            w.lg_k = 3;
+        }
+    }
+    if (ring) w.store = 0;
+    if (untouched && hot_knob < 0 && total_bytes > 336 * MiB && w.store != 1 && w.store != 4 && (ring || doubling)) {
+        auto rounds_fit = [&](const Cap& cap) {
+            const uint64_t last = waves % cap.places;
+            return waves <= cap.places || waves >= 3 * cap.places || last == 0 || last * 5 >= cap.places * 3;
+        };
+        if (ring)
+            w.lds = rounds_fit(c16) ? c16.lds : (p > 32 && rounds_fit(c10)) ? c10.lds : 0u;
+        else if (total_bytes < 8192 * MiB)
+            w.lds = (p >= 32 && rounds_fit(c10)) ? c10.lds : 0u;
+        else
+            w.lds = p <= 64 ? 0u : 8192u;
+    }
+    return w;
+}
+
 // Equal blocks of B bytes (counts == nullptr; slot k at k * B of a row) or blocks of different sizes (device arrays
 // counts / displs; `B` is then the longest block).  Rows are row_bytes apart.  `width` is the access width the
 // call's addresses and lengths allow; 0 asks for the any-alignment form (16-byte chunks cut relative to the
@@ -756,137 +891,14 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     a.displs = displs;
     a.p = uint32_t(p);
     a.top = p > 1 ? 1u << (ceil_log2(p) - 1) : 0u;
-    // How the tree is walked (all measured on MI355X, see the kernel's comment for the terms):
-    //  - jobs that fit the caches anyway are latency-bound: step order has the fewest dependent round trips;
-    //  - otherwise short runs, which keep a slot's read close to its write; the fewer wavefronts the grid has, the
-    //    longer the runs, for more loads in flight per wavefront (p = 256, 2 KiB: 38 us with runs of 32, 43 us with
-    //    runs of 16, 54 us with runs of 4; p = 256, 4 KiB: 55 us with runs of 16, 64 us with runs of 4; p = 64,
-    //    64 KiB: 52 us with runs of 8, 47 us with runs of 4);
-    //  - when the grid has more wavefronts than the GPU holds, 10 resident ones per compute unit are enough to keep
-    //    the memory side busy, and fewer resident wavefronts mean fewer bytes between a write and its read-back:
-    //    each wavefront then reserves 14336 bytes of the unit's 160 KiB of LDS (handed out in granules of 1280 bytes,
-    //    so 15360: a tenth), and the runs are 8 ranks (p = 128, 1 MiB: 3.12 ms; uncapped 3.45 ms; capped at 16 with
-    //    runs of 4: 3.23 ms).
-    const uint64_t waves = pieces * uint64_t(p);
-    const bool small = total_bytes <= uint64_t(g_tree_small_bytes.load());
-    // ... from 33 ranks on: a shorter tree is walked too quickly for that to pay (p = 16, 1 MiB: 58.6 us uncapped with
-    // runs of 4, 66.6 us capped with runs of 8; p = 32, 4 MiB: 883 against 956 us; p = 64, 1 MiB: 891 against 789 us).
-    const bool capped = waves >= 8192 && p > 32;
-    const long long run_knob = g_tree_run_log2.load();
-    a.lg_k = run_knob >= 0 ? uint32_t(run_knob)
-                           : small ? uint32_t(ceil_log2(p))
-                           : waves < 1024 ? 5u : waves < 2048 ? 4u : waves < 4096 ? 3u : capped ? 3u : 2u;
     a.lg_g = lg_g;
-    // Calls that small are one wavefront's walk through the tree, ~100 ns of address arithmetic per rank: from 33
-    // ranks on the walk is shared by a team of wavefronts, one run each (p = 256, 128-byte blocks: 9.9 us of kernel time
-    // against 27 us; what is left is the depth of the tree, ceil(log2 p) dependent hops of ~1.2 us).
-    uint32_t team = 1;
-    if (U == 1 && algo != SPARBIT_ALGO_RING) {
-        const long long team_knob = g_tree_team_log2.load();
-        const int lg_p = ceil_log2(p);
-        int lg_team = team_knob >= 0 ? int(team_knob) : (small && run_knob < 0 && p > 32) ? (p > 64 ? 3 : 2) : 0;
-        if (lg_team > lg_p - 1) lg_team = lg_p > 1 ? lg_p - 1 : 0;  // at least 2 ranks per wavefront
-        if (lg_team > 0) {
-            team = 1u << lg_team;
-            // Sparbit: runs of 2^lg_k ranks, one per wavefront; Recursive Doubling: 2^lg_k sub-trees, by low bits
-            a.lg_k = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING ? uint32_t(lg_team) : uint32_t(lg_p - lg_team);
-        }
-    }
-    const long long lds_knob = g_tree_lds_bytes.load();
-    // Recursive Doubling has no read that follows its write closely, so more resident wavefronts only help:
-    // 18 per unit (8192 bytes each; p = 128, 1 MiB: 4.61 ms; 10 per unit 4.99 ms; uncapped 4.66 ms).
+    const uint64_t waves = pieces * uint64_t(p);
+    const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, width, U, total_bytes, waves});
+    a.lg_k = walk.lg_k;
+    const uint32_t team = walk.team, lds = walk.lds;
+    const int st = walk.store;
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
-    const uint32_t lds_by_size = lds_knob >= 0 ? uint32_t(lds_knob) : capped ? (doubling ? 8192u : 14336u) : 0u;
     const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
-    int st = int(g_tree_store.load());
-    const bool part_lines = any && row_bytes % 128 != 0;
-    // Rows that lie differently relative to the lines: a piece's stores cover part-lines at most ranks, which
-    // write-through stores do badly (p = 61, B = 64 KiB + 16: 54 us plain, 57-60 us write-through; on jobs of
-    // several GiB 5.6-6.1 ms against 6.5-8.6 ms).
-    if (part_lines && st != 1) st = 0;
-    // The walk of store forms 1 and 4: runs of 8, every forwarder read back right after it was stored.
-    //  - Form 1 (all stores plain, grid uncapped) for calls that the caches hold a good part of.  Against the
-    //    write-through walk above: p = 16, 1 MiB: 48 against 57 us; p = 8, 64 MiB (4 GiB): 852 against 1068 us; p = 64,
-    //    64 KiB: 44.8 against 48.1 us; p = 61, 144 KiB (512 MiB): 111 against 117 us; p = 128, 16 KiB (256 MiB): 46
-    //    against 52 us; level from 1 GiB on for 32 ranks and more, behind at 4 GiB from 125 ranks on (895 against
-    //    833 us).
-    //  - Form 4 (plain only for the stores that are read back, write-through for the others) on the capped grids of
-    //    the large calls: cfg4 3.075 against 3.114 ms, cfg5 3.21 against 3.25 ms, p = 96 with 1 MiB blocks 1.75
-    //    against 1.80 ms (form 1 there: 3.18 ms).  Not for the any-alignment form, which loses 4 % with it
-    //    (p = 128, B = 1 MiB + 4: 3.38 against 3.23 ms).
-    //  - From 336 MiB on, form 4 on a capped grid.  16 wavefronts per unit up to 48 ranks, up to 1.25 GiB on 49 .. 64
-    //    ranks and up to 480 MiB beyond, else 10 (p = 64, 128 KiB: 99 us with 16, 110 us with 10, uncapped 114 us; p = 48,
-    //    768 MiB: 156 / 161 / 166 us; p = 16, 4 MiB: 223 / 282 / 241 us; p = 33, 2 GiB: 415 / 433 / 419 us; p = 80,
-    //    762 MiB: 162 / 153 / 169 us; p = 125, 885 MiB: 185 / 178 / 194 us; p = 256, 24 KiB: 326 / 320 / 337 us).  The
-    //    other cap, or none, where the preferred one would leave a last round of few wavefronts among fewer than
-    //    three rounds (p = 125, 504 MiB, 4125 wavefronts on 4096 places: 118 us, uncapped 103 us; p = 253, 750 MiB,
-    //    3036 wavefronts on 2560 places: 186 us, uncapped 161 us; 875 MiB, 3542 wavefronts: 193 against 183 us).
-    const long long hot_knob = g_tree_hot.load();
-    const uint64_t MiB = uint64_t(1) << 20;
-    const bool lines16 = width == 16 && !any;  // whole 16-byte vectors: what the figures above were measured on
-    // The any-alignment form in rows on the lines: every store covers whole lines but for a block's first and last
-    // piece (plain stores, see the kernel), and the same forms win, with other caps (p = 32, 2 MiB + 4: 403 us with
-    // form 4 and 16 per unit, 453 us with the write-through walk; p = 256, 24 KiB + 4: 370 us uncapped, 413 / 478 us
-    // with 16 / 10 per unit; p = 128, 64 KiB + 4: 237 / 266 us with 16 / 10), from blocks of 10 KiB on (p = 256,
-    // 6 KiB + 4: 151 us against 132 us with the write-through walk) and below 8 GiB (beyond: level, or 1 % behind with
-    // per-slot sizes).
-    const bool lines_any = any && !part_lines;
-    const bool hot_size = lines16 || lines_any ? total_bytes > (p <= 64 ? 48 : 96) * MiB && total_bytes <= 336 * MiB
-                          : p < 32             ? total_bytes > 48 * MiB
-                          : p <= 64            ? total_bytes > 48 * MiB && total_bytes <= 768 * MiB
-                                               : total_bytes > 96 * MiB && total_bytes <= 384 * MiB;
-    const bool untouched = run_knob < 0 && lds_knob < 0 && g_tree_store.load() == 2 && g_tree_team_log2.load() < 0;
-    uint32_t lds = lds_by_size;
-    // Recursive Doubling's tree is Sparbit's with the bits of the relative rank reversed, so forms 1 and 4 walk it
-    // too and the same choices hold (p = 128, 1 MiB: 3.07 ms like Sparbit, 4.55 ms in step order).
-    if ((algo == SPARBIT_ALGO_SPARBIT || doubling) && (width == 16 || any) && U == 1) {
-        if (hot_knob > 0 || (hot_knob < 0 && hot_size && untouched)) {
-            st = 1;
-            if (lds_knob < 0) lds = 0;
-        } else if (hot_knob < 0 && untouched && total_bytes > 336 * MiB &&
-                   (lines16 || (lines_any && B >= 10240 && total_bytes < 8192 * MiB))) {
-            st = 4;
-            // LDS is handed out in granules of 1280 bytes: 10240 bytes each leave room for 16 wavefronts per unit,
-            // 14336 (12 granules) for 10.
-            struct Cap { uint32_t lds; uint64_t places; };
-            const Cap c16{10240u, 16 * 256}, c10{14336u, 10 * 256}, none{0u, 0};
-            const bool prefer16 = lines_any || p <= 48 || total_bytes < (p <= 64 ? 1280 : 480) * MiB;
-            const Cap first = prefer16 ? c16 : c10, second = lines_any || p <= 32 ? none : prefer16 ? c10 : c16;
-            auto whole_rounds = [&](const Cap& c) {  // no last round that leaves most of the GPU idle
-                if (c.places == 0) return true;
-                const uint64_t last = waves % c.places;
-                if (waves <= c.places || waves >= 3 * c.places || last == 0) return true;
-                if (lines_any) return false;  // its first and last pieces are short: rounds are uneven anyway
-                return waves < 2 * c.places ? last * 5 >= c.places * 3 : last * 8 >= c.places * 3;
-            };
-            lds = whole_rounds(first) ? first.lds : whole_rounds(second) ? second.lds : 0u;
-        }
-        if (st == 1 || st == 4) {
-            team = 1;
-            a.lg_k = 3;
-        }
-    }
-    // Ring's chain reads a rank back right after storing it: a plain store leaves the line in the L2 for that read
-    // (p = 128, 1 MiB: 3.23 ms), a write-through store makes every hop wait for the memory side (13.3 ms).
-    if (algo == SPARBIT_ALGO_RING) st = 0;
-    // The two other schedules get the caps that the same sweeps found for them (336 MiB and more, no knob set), so
-    // that a comparison of the schedules compares tuned forms.  Ring: 16 per unit (p = 64, 128 KiB: 93 against 103 us;
-    // p = 128, 1 GiB: 195 against 206 us; 16 GiB: level with 10).  Recursive Doubling where it still walks in step
-    // order (the forms above switched off, or rows off the lines), below 8 GiB: 10 per unit from 32 ranks on (p = 128,
-    // 64 KiB: 239 against 290 us; p = 64, 1 MiB: 936 against 1116 us); on 16 GiB uncapped up to 64 ranks (3.97 against
-    // 4.56 ms), 18 per unit beyond.
-    if (untouched && hot_knob < 0 && total_bytes > 336 * MiB && st != 1 && st != 4 && (algo == SPARBIT_ALGO_RING || doubling)) {
-        auto rounds_fit = [&](uint64_t places) {
-            const uint64_t last = waves % places;
-            return waves <= places || waves >= 3 * places || last == 0 || last * 5 >= places * 3;
-        };
-        if (algo == SPARBIT_ALGO_RING)
-            lds = rounds_fit(16 * 256) ? 10240u : (p > 32 && rounds_fit(10 * 256)) ? 14336u : 0u;
-        else if (total_bytes < 8192 * MiB)
-            lds = (p >= 32 && rounds_fit(10 * 256)) ? 14336u : 0u;
-        else
-            lds = p <= 64 ? 0u : 8192u;
-    }
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
     const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team};
