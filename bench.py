@@ -56,11 +56,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 1>"):
         (17761467776, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 1>"):
         (17625713471, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false>"):
+    ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false, 1>"):
         (20484773698, "profiles/tree_kernel_cfg4_cfg5.md"),
 }
 
@@ -144,10 +144,12 @@ def form_of(kernel_name, algo_label="sparbit"):
 
 
 def tree_kernel_flags(kernel_name):
-    """The store form and the last three template arguments of the tree kernel's name as the library reports it."""
+    """Template arguments of the tree kernel's name as the library reports it: access type, vectors per lane, loads
+    per batch, store form, look-ahead load, per-slot sizes, any-alignment form, walk, teams, wavefronts per gang."""
     args = kernel_name.rstrip(">").split(", ")
-    return {"store": int(args[-6]), "any_alignment": args[-3] == "true",
-            "walk": ("sparbit", "doubling", "chain")[int(args[-2])], "team": args[-1] == "true"}
+    return {"store": int(args[3]), "any_alignment": args[6] == "true",
+            "walk": ("sparbit", "doubling", "chain")[int(args[7])], "team": args[8] == "true",
+            "gang": int(args[9]) if len(args) > 9 else 1}
 
 
 def rates(p, B, ms, form):

@@ -114,6 +114,7 @@ std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
 std::atomic<long long> g_tree_auto_ring{1};                   // ... and whole Ring calls (a chain per block)
+std::atomic<long long> g_tree_gang{-1};                       // gangs of 4 wavefronts with pieces 32 KiB apart: -1 = by size, 0 = never, 1 = wherever the form allows
 std::atomic<long long> g_tree_hot{-1};                        // plain stores with forwarders read back at once: -1 = by size, 0 = never, 1 = always
 std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
@@ -618,9 +619,11 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
 }
 
 // The tree kernel: one wavefront, or with `team` > 1 that many, per (tree, piece of 64 * U vectors).
+constexpr int kTreeGang = 4;  // wavefronts per workgroup in the gang form
+
 template <typename V, int U, int NB, bool VAR, bool ANY = false, int WALK = kWalkSparbit>
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream,
-                   uint32_t team = 1)
+                   uint32_t team = 1, bool gang = false)
 {
     if (sizeof(V) != 16) store_kind = 0;
     // Ring's chain has no runs: no look-ahead, plain or write-through stores.  Recursive Doubling's tree has them
@@ -634,11 +637,22 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if ((step_order_only || team > 1) && store_kind == 4) store_kind = 2;
     if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
-    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1));
+    if (sizeof(V) != 16 || U != 1 || ANY || team > 1 || WALK == kWalkChain || (store_kind != 1 && store_kind != 4)) gang = false;
+    note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s, %d>", type_label<V>(), U, NB, store_kind,
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1), gang ? kTreeGang : 1);
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, WALK>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
     hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, WALK, true>), grid, dim3(64 * team), lds, stream, a)
+    if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16 && !ANY) {
+        if (gang) {
+            if (store_kind == 1)
+                hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
+            else
+                hipLaunchKernelGGL((tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
+            SB_HIP(hipGetLastError());
+            return SPARBIT_OK;
+        }
+    }
     if constexpr (U == 1 && WALK != kWalkChain) {
         if (team > 1) {
             if (store_kind != 0) SB_TEAM(2);
@@ -704,6 +718,7 @@ struct TreeLaunch {
     uint64_t bytes;
     hipStream_t stream;
     uint32_t team;
+    bool gang;
 };
 
 template <bool VAR, int WALK>
@@ -715,7 +730,7 @@ int launch_tree_as(const TreeArgs& a, const TreeLaunch& h)
         if constexpr (WALK == kWalkSparbit) {
             if (h.U == 2) return launch_tree_vu<u32x4, 2, 8, VAR>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream);
         }
-        return launch_tree_vu<u32x4, 1, 8, VAR, false, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+        return launch_tree_vu<u32x4, 1, 8, VAR, false, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team, h.gang);
     }
     if (h.width == 4)
         return launch_tree_vu<uint32_t, 1, 8, VAR, false, WALK>(a, h.grid, 0, h.prefetch, h.lds, h.bytes, h.stream, h.team);
@@ -728,6 +743,7 @@ struct TreeWalk {
     uint32_t team;  // wavefronts per workgroup that share one piece of one tree
     int store;      // the kernel's store form
     uint32_t lds;   // bytes of LDS each wavefront reserves without using them: caps the resident wavefronts per unit
+    bool gang;      // workgroups of 4 wavefronts whose pieces lie 32 KiB apart
 };
 struct TreeCall {
     int algo, p;
@@ -854,6 +870,7 @@ TreeWalk choose_tree_walk(const TreeCall& c)
         else
             w.lds = p <= 64 ? 0u : 8192u;
     }
+    w.gang = g_tree_gang.load() == 1;
     return w;
 }
 
@@ -895,13 +912,19 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const uint64_t waves = pieces * uint64_t(p);
     const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, width, U, total_bytes, waves});
     a.lg_k = walk.lg_k;
-    const uint32_t team = walk.team, lds = walk.lds;
+    const uint32_t team = walk.team;
     const int st = walk.store;
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
-    const dim3 grid(uint32_t(pieces << lg_g), groups, 1);
+    // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie kGangStride pieces apart, i.e. per
+    // group of kTreeGang * kGangStride pieces kGangStride workgroups; a block's last group may be part empty.
+    const bool gang = walk.gang && width == 16 && !any && U == 1 && team == 1 && (st == 1 || st == 4) && algo != SPARBIT_ALGO_RING;
+    const uint64_t per_group = uint64_t(kTreeGang) * kGangStride;
+    const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * kGangStride : pieces;
+    const uint32_t lds = gang ? walk.lds * kTreeGang : walk.lds;  // per workgroup
+    const dim3 grid(uint32_t(x_items << lg_g), groups, 1);
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
-    const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team};
+    const TreeLaunch how{grid, any, width, U, st, pf, lds, total_bytes, stream, team, gang};
     if (algo == SPARBIT_ALGO_RING) return counts ? launch_tree_as<true, kWalkChain>(a, how) : launch_tree_as<false, kWalkChain>(a, how);
     if (doubling) return counts ? launch_tree_as<true, kWalkDoubling>(a, how) : launch_tree_as<false, kWalkDoubling>(a, how);
     return counts ? launch_tree_as<true, kWalkSparbit>(a, how) : launch_tree_as<false, kWalkSparbit>(a, how);
@@ -1760,6 +1783,9 @@ int sparbit_tune(const char* key, long long value)
         g_tree_auto_doubling = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_auto_ring")) {
         g_tree_auto_ring = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_gang")) {
+        if (value < -1 || value > 1) return SPARBIT_ERR_ARG;
+        g_tree_gang = value;
     } else if (!std::strcmp(key, "tree_hot")) {
         if (value < -1 || value > 1) return SPARBIT_ERR_ARG;
         g_tree_hot = value;

@@ -238,10 +238,20 @@ constexpr uint32_t kTeamSpinLimit = 1u << 22;  // polls of ~100 cycles each
 // wavefront stores a rank and reads it back at once, p - 1 times.
 constexpr int kWalkSparbit = 0, kWalkDoubling = 1, kWalkChain = 2;
 
+// GANG: the workgroup holds GANG wavefronts that each carry a piece of their own through the same tree, the pieces
+// kGangStride KiB apart, and meet at a barrier before every run.  What the memory side then sees at one time are
+// stores to one rank's slot that lie 32 KiB apart, which it takes at a higher rate than stores to unrelated places
+// (a stream of nothing but such stores, 16 GiB: 6.4-6.6 TB/s against 5.7 TB/s with adjacent or unrelated pieces; 16 KiB
+// apart 6.2-6.4, 64 KiB 6.2-6.3, 8 KiB and less or 256 KiB and more: no gain).  A piece index past the block's end leaves
+// its wavefront with an empty buffer: its accesses are dropped by the bounds check and it still meets every barrier.
+constexpr uint32_t kGangStride = 32;
+
 template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, int WALK = kWalkSparbit,
-          bool TEAM = false>
-__global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a)
+          bool TEAM = false, int GANG = 1>
+__global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const TreeArgs a)
 {
+    static_assert(GANG == 1 || (!TEAM && !ANY && (ST == 1 || ST == 4) && sizeof(V) == 16),
+                  "gangs walk whole 16-byte vectors in the read-back-at-once forms");
     constexpr bool DOUBLING = WALK == kWalkDoubling, CHAIN = WALK == kWalkChain;
     static_assert(!CHAIN || (!PF && !TEAM), "a chain has nothing to look ahead of and nothing to share");
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
@@ -249,8 +259,8 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     static_assert(!DOUBLING || !PF || REVERSED, "the step-order doubling walk has no run to look ahead of");
     static_assert(!REVERSED || !TEAM, "teams walk the doubling tree by the low bits of the relative rank");
     static_assert(!TEAM || (!PF && U == 1), "a team's wavefronts walk one part of the tree each, one vector per lane");
-    const uint32_t lane = TEAM ? (threadIdx.x & 63u) : threadIdx.x;
-    const uint32_t wave = TEAM ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
+    const uint32_t lane = TEAM || GANG > 1 ? (threadIdx.x & 63u) : threadIdx.x;
+    const uint32_t wave = TEAM || GANG > 1 ? uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6))) : 0u;
     const uint32_t group = blockIdx.z * gridDim.y + blockIdx.y;
     // The tree (origin rank = slot) and the piece of it.  A last group of fewer than 2^lg_g trees interleaves just
     // those, so that its pieces still go round all XCDs (p = 257: the last tree alone would run on one of them).
@@ -285,11 +295,17 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
         part_of_a_line = i == 0 || hi - lo != 1024u;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
-        const uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
-        if (piece_at >= vectors) return;  // uniform: a shorter block has no such piece
+        if constexpr (GANG > 1)  // the workgroup's number counts groups of GANG * kGangStride pieces and a place in one
+            piece_index = (piece_index / kGangStride) * (kGangStride * GANG) + piece_index % kGangStride + kGangStride * wave;
+        uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
+        bool no_piece = piece_at >= vectors;  // uniform: a shorter block has no such piece
+        if (no_piece) {
+            if constexpr (GANG == 1) return;
+            piece_at = 0;  // stays for the barriers, with an empty buffer
+        }
         offset += piece_at * sizeof(V);
         const uint64_t left = vectors - piece_at;
-        piece_vectors = left < uint64_t(64 * U) ? uint32_t(left) : uint32_t(64 * U);
+        piece_vectors = no_piece ? 0u : left < uint64_t(64 * U) ? uint32_t(left) : uint32_t(64 * U);
     }
     bool ok[U];
 #pragma unroll
@@ -504,6 +520,7 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64) void tree_kernel(const TreeArgs a
     H y16, y32;  // store forms 1 and 4: the first ranks of the runs 16 and 32 ranks ahead, read back when they were stored
     for (uint32_t h = 0; h < p; h += K) {  // h: first relative rank of the run; its lowest set bit is >= K
         const uint32_t end = (p - h < K) ? p : h + K;
+        if constexpr (GANG > 1) __syncthreads();  // every wavefront of the gang takes every turn of this loop
         if constexpr (ST == 1 || ST == 4) {  // K = 8 (the host sees to it); PF: xh is this run's first rank, loaded by the run before
             static_assert(PF && U == 1, "the read-back-at-once walk keeps the next run's first rank in registers");
             auto to = [&](uint32_t n, uint32_t d, const H& x) {  // a forward, if both ranks exist

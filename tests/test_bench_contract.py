@@ -42,16 +42,16 @@ def test_algorithmic_bytes_per_form():
 
 def test_forms_are_read_off_the_kernel_name():
     b = _bench()
-    tree = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, 0, false>"
-    anyal = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false>"
-    doubling = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, false, false, false, 1, true>"
-    chain = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, false, 2, false>"
+    tree = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, false, 0, false, 1>"
+    anyal = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false, 1>"
+    doubling = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, false, false, false, 1, true, 1>"
+    chain = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, false, 2, false, 1>"
     assert b.form_of(tree) == "tree" and b.form_of(anyal) == "tree" and b.form_of(doubling) == "tree_doubling"
     assert b.form_of(chain) == "tree"  # a chain's re-reads follow their writes at once: the tree form's byte count
-    assert b.tree_kernel_flags(anyal) == {"store": 2, "any_alignment": True, "walk": "sparbit", "team": False}
-    assert b.tree_kernel_flags(doubling) == {"store": 2, "any_alignment": False, "walk": "doubling", "team": True}
+    assert b.tree_kernel_flags(anyal) == {"store": 2, "any_alignment": True, "walk": "sparbit", "team": False, "gang": 1}
+    assert b.tree_kernel_flags(doubling) == {"store": 2, "any_alignment": False, "walk": "doubling", "team": True, "gang": 1}
     # Recursive Doubling in store forms 1 and 4 is walked like Sparbit's tree: read back at once
-    reversed_bits = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 1, false>"
+    reversed_bits = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 1, false, 1>"
     assert b.form_of(reversed_bits) == "tree" and b.tree_kernel_flags(reversed_bits)["store"] == 4
     assert b.form_of("sparbit::copy_tiles_kernel<unsigned int __vector(4), unsigned int, 64, 1, true, false, true>") == "per_step"
     assert b.form_of("anything", "direct") == "direct" and b.form_of("anything", "memcpy_d2d") == "copy"
@@ -71,7 +71,7 @@ def test_sweep_summary_from_a_small_file(tmp_path):
                     continue
                 rows.append({"p": p, "block_bytes": B, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
                              "effective_GBps": p * p * B / us / 1e3})
-    name = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, true, 0, true>"
+    name = "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 0, false, false, true, 0, true, 1>"
     for algo, us in (("sparbit", 11.0), ("sparbit_per_step", 22.0), ("bruck", 16.0)):
         rows.append({"p": 5, "block_bytes": 1025, "algo": algo, "ok": True, "avg_us": us, "min_us": us, "max_us": us,
                      "effective_GBps": 1.0, "off_grid": True, "kernel": name, "rows_on_lines": False})

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 96 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
             "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
-            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1, "tree_hot": -1}
+            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1, "tree_hot": -1, "tree_gang": -1}
 
 
 @pytest.fixture(scope="module")
@@ -79,7 +79,7 @@ def test_narrow_accesses(torch):
 
 def launched_any_alignment_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.rstrip(">").split(", ")[-3] == "true"
+    return "tree_kernel" in name and name.rstrip(">").split(", ")[6] == "true"
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_small_bytes": 0, "tree_run_log2": 0, "tree_prefetch": 0},
@@ -190,7 +190,7 @@ def test_teams_of_wavefronts(torch, team_log2):
             got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place, misalign=mis)
             name = sb.sparbit_last_launch_info()[0]
             if p > 2 and not (p == 1 and in_place):
-                assert name.endswith(", true>"), name  # a team
+                assert name.endswith(", true, 1>"), name  # a team
             assert np.array_equal(got, want), (team_log2, p, B, mis, in_place)
 
 
@@ -202,7 +202,7 @@ def test_auto_forms_teams_for_small_calls_of_many_ranks(torch):
         want = oracle_result(sb.SPARBIT, p, B, send)
         got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_AUTO)
         name = sb.sparbit_last_launch_info()[0]
-        assert "tree_kernel" in name and name.endswith(", true>") == team, name
+        assert "tree_kernel" in name and name.endswith(", true, 1>") == team, name
         assert np.array_equal(got, want), (p, B)
 
 
@@ -261,9 +261,54 @@ def test_calls_of_some_hundred_mib(torch, algo, p, B):
     assert np.array_equal(got, want), (algo, p, B)
 
 
+def launched_gangs():
+    name = sb.sparbit_last_launch_info()[0]
+    return "tree_kernel" in name and name.endswith(", false, 4>")
+
+
+@pytest.mark.parametrize("store", [1, 4])
+def test_gangs_of_wavefronts(torch, store):
+    """Workgroups of 4 wavefronts whose pieces lie 32 KiB apart and that meet at a barrier before every run: forced
+    onto blocks of less than one group of 128 pieces (wavefronts without a piece), of whole groups, of groups and a
+    ragged rest, with a last piece of a few bytes; rank counts around the run length, in place, Recursive Doubling,
+    and where the form does not allow gangs (teams, narrow accesses, the any-alignment form, Ring)."""
+    sb.sparbit_tune("tree_gang", 1)
+    sb.sparbit_tune("tree_store", store)
+    sb.sparbit_tune("tree_small_bytes", 0)
+    for p, B in ((1, 4096), (2, 16), (3, 1024 + 128), (5, 33 * 1024), (7, 128 * 1024), (8, 160 * 1024 + 384), (9, 64 * 1024),
+                 (16, 256 * 1024), (17, 100 * 1024 + 128), (21, 31 * 1024 + 256), (33, 130 * 1024), (64, 96 * 1024),
+                 (65, 32 * 1024 + 128), (96, 1024), (129, 4096), (257, 2048 + 128)):  # whole lines, or under 512 bytes
+        for in_place in (False, True):
+            announce("gangs", store, p, B, in_place)
+            send = workloads.make_send_raw(p, B, seed=p + B % 97)
+            want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place)
+            if not (p == 1 and in_place):
+                assert launched_gangs(), sb.sparbit_last_launch_info()
+            assert np.array_equal(got, want), (p, B, in_place)
+    for p, B in ((4, 64 * 1024), (32, 40 * 1024 + 128), (128, 1024)):
+        announce("gangs, doubling", store, p, B)
+        send = workloads.make_send_raw(p, B, seed=p)
+        want = oracle_result(sb.RECURSIVE_DOUBLING, p, B, send)
+        got = gpu_result(torch, sb.RECURSIVE_DOUBLING, p, B, send, sb.MODE_TREE)
+        assert launched_gangs() and launched_doubling_form(), sb.sparbit_last_launch_info()
+        assert np.array_equal(got, want), (p, B)
+    for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 4100, {}), (sb.SPARBIT, 3, 1040, {}), (sb.RING, 9, 4096, {}),
+                              (sb.SPARBIT, 64, 1024, {"tree_team_log2": 2, "tree_store": 2})):
+        for k, v in knobs.items():
+            sb.sparbit_tune(k, v)
+        announce("no gangs here", algo, p, B)
+        send = workloads.make_send_raw(p, B, seed=p)
+        want = oracle_result(algo, p, B, send)
+        got = gpu_result(torch, algo, p, B, send, sb.MODE_TREE)
+        assert not launched_gangs(), sb.sparbit_last_launch_info()
+        assert np.array_equal(got, want), (algo, p, B)
+
+
 def launched_doubling_form():
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "1"
+    args = name.rstrip(">").split(", ")
+    return "tree_kernel" in name and args[7] == "1"  # access type, U, NB, store, look-ahead, sizes, any, walk, team, gang
 
 
 @pytest.mark.parametrize("knobs", [{}, {"tree_store": 0, "tree_lds_bytes": 0}, {"tree_team_log2": 0}, {"tree_team_log2": 1},
@@ -331,7 +376,7 @@ def test_ring_in_the_tree_form(torch):
                 got = gpu_result(torch, sb.RING, p, B, send, mode, in_place=in_place, misalign=mis)
                 name = sb.sparbit_last_launch_info()[0]
                 if not (p == 1 and in_place):
-                    assert "tree_kernel" in name and name.rstrip(">").split(", ")[-2] == "2" and ", 8, 0, " in name, name
+                    assert "tree_kernel" in name and name.rstrip(">").split(", ")[7] == "2" and ", 8, 0, " in name, name
                 assert np.array_equal(got, want), (p, B, mis, mode, in_place)
 
 
