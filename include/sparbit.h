@@ -334,6 +334,7 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *   "tree_gang"            store forms 1 and 4 on whole 16-byte vectors: workgroups of 4 wavefronts whose pieces lie 32
  *                          KiB apart and that meet at a barrier before every run (-1, the default: by size; 0 never; 1
  *                          wherever the form allows); tree_lds_bytes then counts per wavefront all the same
+ *   "tree_gang_apart_log2" ... 2^this KiB apart instead (0..10; -1, the default: by the call)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
  *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the
  *                          tree kernel's any-alignment form (default 1; 0: one launch per step, realigning kernel)

@@ -114,6 +114,7 @@ std::atomic<long long> g_realign_min_bytes{512};
 std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparbit as the tree kernel where it applies
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
 std::atomic<long long> g_tree_auto_ring{1};                   // ... and whole Ring calls (a chain per block)
+std::atomic<long long> g_tree_gang_apart_log2{-1};            // ... 2^this KiB apart (-1: by the call)
 std::atomic<long long> g_tree_gang{-1};                       // gangs of 4 wavefronts with pieces 32 KiB apart: -1 = by size, 0 = never, 1 = wherever the form allows
 std::atomic<long long> g_tree_hot{-1};                        // plain stores with forwarders read back at once: -1 = by size, 0 = never, 1 = always
 std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
@@ -743,7 +744,8 @@ struct TreeWalk {
     uint32_t team;  // wavefronts per workgroup that share one piece of one tree
     int store;      // the kernel's store form
     uint32_t lds;   // bytes of LDS each wavefront reserves without using them: caps the resident wavefronts per unit
-    bool gang;      // workgroups of 4 wavefronts whose pieces lie 32 KiB apart
+    bool gang;      // workgroups of 4 wavefronts whose pieces lie 2^lg_s KiB apart
+    uint32_t lg_s;
 };
 struct TreeCall {
     int algo, p;
@@ -870,7 +872,44 @@ TreeWalk choose_tree_walk(const TreeCall& c)
         else
             w.lds = p <= 64 ? 0u : 8192u;
     }
-    w.gang = g_tree_gang.load() == 1;
+    // Gangs (the kernel's GANG): where form 4 was chosen above for whole 16-byte vectors and the blocks are a multiple
+    // of 64 KiB, so that the 64 or 128 KiB that a gang's four pieces span start on such a boundary at every rank, or
+    // are 48 KiB and more (then the gain is smaller: 3-10 %).  Against the choice above: cfg5 2.70 against 3.21 ms, cfg4 2.66
+    // against 3.07 ms, p = 64 with 1 MiB blocks 683 against 777 us, p = 16 with 4 MiB blocks 192 against 222 us, p = 128
+    // with 64 KiB blocks 183 against 214 us; blocks off those boundaries: p = 125 with 1073 KiB blocks 2.55 against
+    // 2.75 ms, p = 33 with 1925 KiB blocks 394 against 417 us, p = 257 with 254 KiB blocks 3.11 against 3.13 ms.  Few
+    // pieces per block leave most of a gang idle (p = 125, 6 KiB blocks: 56 against 22 us).  Pieces 32 KiB apart, 16 KiB
+    // from 64 ranks on for blocks of 1 MiB and more or off the 128 KiB boundaries (cfg4 2.66 against 2.77 ms, cfg5 2.75
+    // against 2.70 ms).  Resident wavefronts per unit: 16 up to 16 ranks, 12 up to 48 and up to 768 MiB, else 8 (two
+    // gangs), again only where the grid's last round is at least half full or there are six rounds and more.
+    const long long gang_knob = g_tree_gang.load(), apart_knob = g_tree_gang_apart_log2.load();
+    const bool on_boundaries = c.B % 65536 == 0;
+    w.gang = gang_knob == 1;
+    w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
+    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && w.store == 4 && c.algo != SPARBIT_ALGO_RING &&
+        (on_boundaries || c.B >= 48 * 1024)) {
+        w.gang = true;
+        if (c.B % 131072 != 0 && on_boundaries && c.B < MiB) w.lg_s = 4;  // 64 KiB on its boundaries: two pieces of 32 KiB do not fit
+        if (!on_boundaries && c.B < 400 * 1024) {  // few pieces: the spacing that leaves fewer wavefronts without one
+            const uint64_t pieces = (c.B + 1023) / 1024;
+            const uint64_t room4 = (pieces + 63) / 64 * 64, room5 = (pieces + 127) / 128 * 128;
+            w.lg_s = room4 < room5 ? 4u : room5 < room4 ? 5u : w.lg_s;
+            // ... and none where two in five would be (p = 253, 65 KiB blocks: 908 against 820 us)
+            if (pieces * 5 < (room4 < room5 ? room4 : room5) * 3) w.gang = false;
+        }
+        const Cap g16{10240u, 16 * 256}, g12{12800u, 12 * 256}, g8{14336u, 8 * 256};  // per wavefront; a gang reserves four times that
+        auto rounds_fit = [&](const Cap& cap) {
+            const uint64_t last = waves % cap.places;
+            return waves <= cap.places || waves >= 6 * cap.places || last == 0 || last * 2 >= cap.places;
+        };
+        const Cap order[3] = {p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB) ? g12 : g8,
+                              p <= 16 ? g12 : g16, p <= 48 ? g8 : g12};
+        if (w.gang) {
+            w.lds = g16.lds;
+            for (int i = 2; i >= 0; --i)
+                if (rounds_fit(order[i])) w.lds = order[i].lds;
+        }
+    }
     return w;
 }
 
@@ -915,11 +954,12 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const uint32_t team = walk.team;
     const int st = walk.store;
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
-    // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie kGangStride pieces apart, i.e. per
-    // group of kTreeGang * kGangStride pieces kGangStride workgroups; a block's last group may be part empty.
+    // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie `apart` pieces apart, i.e. per
+    // group of kTreeGang * apart pieces `apart` workgroups; a block's last group may be part empty.
     const bool gang = walk.gang && width == 16 && !any && U == 1 && team == 1 && (st == 1 || st == 4) && algo != SPARBIT_ALGO_RING;
-    const uint64_t per_group = uint64_t(kTreeGang) * kGangStride;
-    const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * kGangStride : pieces;
+    a.lg_s = walk.lg_s;
+    const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(kTreeGang) * apart;
+    const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * apart : pieces;
     const uint32_t lds = gang ? walk.lds * kTreeGang : walk.lds;  // per workgroup
     const dim3 grid(uint32_t(x_items << lg_g), groups, 1);
     const bool pf = g_tree_prefetch.load() != 0;
@@ -1783,6 +1823,9 @@ int sparbit_tune(const char* key, long long value)
         g_tree_auto_doubling = value ? 1 : 0;
     } else if (!std::strcmp(key, "tree_auto_ring")) {
         g_tree_auto_ring = value ? 1 : 0;
+    } else if (!std::strcmp(key, "tree_gang_apart_log2")) {
+        if (value < -1 || value > 10) return SPARBIT_ERR_ARG;
+        g_tree_gang_apart_log2 = value;
     } else if (!std::strcmp(key, "tree_gang")) {
         if (value < -1 || value > 1) return SPARBIT_ERR_ARG;
         g_tree_gang = value;

@@ -169,6 +169,7 @@ struct TreeArgs {
     uint32_t top;   // distance of the first step: 2^(ceil(log2 p) - 1), 0 for p = 1
     uint32_t lg_k;
     uint32_t lg_g;
+    uint32_t lg_s;  // gangs: the pieces of a workgroup's wavefronts lie 2^lg_s pieces apart
 };
 
 // Store forms of the tree kernel (ST), for 16-byte vectors.  0: plain, the line is allocated in the XCD's L2 and
@@ -239,12 +240,12 @@ constexpr uint32_t kTeamSpinLimit = 1u << 22;  // polls of ~100 cycles each
 constexpr int kWalkSparbit = 0, kWalkDoubling = 1, kWalkChain = 2;
 
 // GANG: the workgroup holds GANG wavefronts that each carry a piece of their own through the same tree, the pieces
-// kGangStride KiB apart, and meet at a barrier before every run.  What the memory side then sees at one time are
-// stores to one rank's slot that lie 32 KiB apart, which it takes at a higher rate than stores to unrelated places
-// (a stream of nothing but such stores, 16 GiB: 6.4-6.6 TB/s against 5.7 TB/s with adjacent or unrelated pieces; 16 KiB
-// apart 6.2-6.4, 64 KiB 6.2-6.3, 8 KiB and less or 256 KiB and more: no gain).  A piece index past the block's end leaves
-// its wavefront with an empty buffer: its accesses are dropped by the bounds check and it still meets every barrier.
-constexpr uint32_t kGangStride = 32;
+// 2^lg_s KiB apart (16 or 32), and meet at a barrier before every run.  What the memory side then sees at one time are
+// stores to one rank's slot that lie 16 or 32 KiB apart, which it takes at a higher rate than stores to unrelated
+// places (a stream of nothing but such stores, 16 GiB: 6.4-6.6 TB/s with 32 KiB against 5.7 TB/s with adjacent or
+// unrelated pieces; 16 KiB apart 6.2-6.4, 64 KiB 6.2-6.3, 8 KiB and less or 256 KiB and more: no gain).  A piece index
+// past the block's end leaves its wavefront with an empty buffer: its accesses are dropped by the bounds check and
+// it still meets every barrier.
 
 template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, int WALK = kWalkSparbit,
           bool TEAM = false, int GANG = 1>
@@ -295,8 +296,9 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
         part_of_a_line = i == 0 || hi - lo != 1024u;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
-        if constexpr (GANG > 1)  // the workgroup's number counts groups of GANG * kGangStride pieces and a place in one
-            piece_index = (piece_index / kGangStride) * (kGangStride * GANG) + piece_index % kGangStride + kGangStride * wave;
+        if constexpr (GANG > 1)  // the workgroup's number counts groups of GANG << lg_s pieces and a place in one
+            piece_index = (piece_index >> a.lg_s) * (uint32_t(GANG) << a.lg_s) + (piece_index & ((1u << a.lg_s) - 1u)) +
+                          (wave << a.lg_s);
         uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
         bool no_piece = piece_at >= vectors;  // uniform: a shorter block has no such piece
         if (no_piece) {
