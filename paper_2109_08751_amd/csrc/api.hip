@@ -638,13 +638,13 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if ((step_order_only || team > 1) && store_kind == 4) store_kind = 2;
     if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
-    if (sizeof(V) != 16 || U != 1 || ANY || team > 1 || WALK == kWalkChain || (store_kind != 1 && store_kind != 4)) gang = false;
+    if (sizeof(V) != 16 || U != 1 || team > 1 || WALK == kWalkChain || (store_kind != 1 && store_kind != 4)) gang = false;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s, %d>", type_label<V>(), U, NB, store_kind,
                 bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1), gang ? kTreeGang : 1);
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, WALK>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
     hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, WALK, true>), grid, dim3(64 * team), lds, stream, a)
-    if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16 && !ANY) {
+    if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16) {
         if (gang) {
             if (store_kind == 1)
                 hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
@@ -726,7 +726,7 @@ template <bool VAR, int WALK>
 int launch_tree_as(const TreeArgs& a, const TreeLaunch& h)
 {
     if (h.any)
-        return launch_tree_vu<u32x4, 1, 8, VAR, true, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team);
+        return launch_tree_vu<u32x4, 1, 8, VAR, true, WALK>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream, h.team, h.gang);
     if (h.width == 16) {
         if constexpr (WALK == kWalkSparbit) {
             if (h.U == 2) return launch_tree_vu<u32x4, 2, 8, VAR>(a, h.grid, h.store_kind, h.prefetch, h.lds, h.bytes, h.stream);
@@ -752,6 +752,7 @@ struct TreeCall {
     size_t B;         // the (longest) block
     bool any;         // the any-alignment form ...
     bool part_lines;  // ... in rows that are not a multiple of 128 bytes apart: stores cover parts of lines at most ranks
+    bool var;         // per-slot sizes
     int width, U;     // bytes per access (any: 0) and 16-byte vectors per lane
     uint64_t total_bytes, waves;  // receive bytes of the call; wavefronts (teams) of the grid
 };
@@ -886,6 +887,8 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     const bool on_boundaries = c.B % 65536 == 0;
     w.gang = gang_knob == 1;
     w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
+    // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
+    // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
     if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && w.store == 4 && c.algo != SPARBIT_ALGO_RING &&
         (on_boundaries || c.B >= 48 * 1024)) {
         w.gang = true;
@@ -902,7 +905,8 @@ TreeWalk choose_tree_walk(const TreeCall& c)
             const uint64_t last = waves % cap.places;
             return waves <= cap.places || waves >= 6 * cap.places || last == 0 || last * 2 >= cap.places;
         };
-        const Cap order[3] = {p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB) ? g12 : g8,
+        // (per-slot sizes: 12, the blocks' lengths differ; p = 128 with blocks of 0.5-1.5 MiB: 3.17 against 3.38 ms with 8)
+        const Cap order[3] = {p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB || c.var) ? g12 : g8,
                               p <= 16 ? g12 : g16, p <= 48 ? g8 : g12};
         if (w.gang) {
             w.lds = g16.lds;
@@ -949,14 +953,14 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     a.top = p > 1 ? 1u << (ceil_log2(p) - 1) : 0u;
     a.lg_g = lg_g;
     const uint64_t waves = pieces * uint64_t(p);
-    const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, width, U, total_bytes, waves});
+    const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, counts != nullptr, width, U, total_bytes, waves});
     a.lg_k = walk.lg_k;
     const uint32_t team = walk.team;
     const int st = walk.store;
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
     // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie `apart` pieces apart, i.e. per
     // group of kTreeGang * apart pieces `apart` workgroups; a block's last group may be part empty.
-    const bool gang = walk.gang && width == 16 && !any && U == 1 && team == 1 && (st == 1 || st == 4) && algo != SPARBIT_ALGO_RING;
+    const bool gang = walk.gang && (width == 16 || any) && U == 1 && team == 1 && (st == 1 || st == 4) && algo != SPARBIT_ALGO_RING;
     a.lg_s = walk.lg_s;
     const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(kTreeGang) * apart;
     const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * apart : pieces;

@@ -251,8 +251,8 @@ template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY
           bool TEAM = false, int GANG = 1>
 __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const TreeArgs a)
 {
-    static_assert(GANG == 1 || (!TEAM && !ANY && (ST == 1 || ST == 4) && sizeof(V) == 16),
-                  "gangs walk whole 16-byte vectors in the read-back-at-once forms");
+    static_assert(GANG == 1 || (!TEAM && (ST == 1 || ST == 4) && sizeof(V) == 16 && U == 1),
+                  "gangs walk 16-byte vectors, one per lane, in the read-back-at-once forms");
     constexpr bool DOUBLING = WALK == kWalkDoubling, CHAIN = WALK == kWalkChain;
     static_assert(!CHAIN || (!PF && !TEAM), "a chain has nothing to look ahead of and nothing to share");
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
@@ -278,6 +278,8 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
     }
     uint64_t offset = uint64_t(b) * a.block_bytes;  // this tree's block inside a row
     if constexpr (VAR) offset = a.displs[b];
+    if constexpr (GANG > 1)  // the workgroup's number counts groups of GANG << lg_s pieces and a place in one
+        piece_index = (piece_index >> a.lg_s) * (uint32_t(GANG) << a.lg_s) + (piece_index & ((1u << a.lg_s) - 1u)) + (wave << a.lg_s);
     uint32_t piece_vectors;  // V's in this wavefront's piece
     uint32_t tail_bytes = 0;  // ANY: single bytes after them
     bool part_of_a_line = false;  // ANY: the piece starts or ends inside a 128-byte line (a block's first and last piece)
@@ -289,16 +291,17 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
         const uint64_t lo = i ? to_line + (i - 1) * 1024u : 0;
         uint64_t hi = to_line + i * 1024u;
         if (hi > bytes) hi = bytes;
-        if (lo >= hi) return;  // uniform: no bytes ahead of the line, or past the block's end
-        offset += lo;
-        piece_vectors = uint32_t(hi - lo) >> 4;
-        tail_bytes = uint32_t(hi - lo) & 15u;
-        part_of_a_line = i == 0 || hi - lo != 1024u;
+        uint64_t at = lo;
+        if (lo >= hi) {  // uniform: no bytes ahead of the line, or past the block's end
+            if constexpr (GANG == 1) return;
+            at = hi = 0;  // stays for the barriers, with an empty buffer
+        }
+        offset += at;
+        piece_vectors = uint32_t(hi - at) >> 4;
+        tail_bytes = uint32_t(hi - at) & 15u;
+        part_of_a_line = i == 0 || hi - at != 1024u;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
-        if constexpr (GANG > 1)  // the workgroup's number counts groups of GANG << lg_s pieces and a place in one
-            piece_index = (piece_index >> a.lg_s) * (uint32_t(GANG) << a.lg_s) + (piece_index & ((1u << a.lg_s) - 1u)) +
-                          (wave << a.lg_s);
         uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece
         bool no_piece = piece_at >= vectors;  // uniform: a shorter block has no such piece
         if (no_piece) {

@@ -271,7 +271,7 @@ def test_gangs_of_wavefronts(torch, store):
     """Workgroups of 4 wavefronts whose pieces lie 32 KiB apart and that meet at a barrier before every run: forced
     onto blocks of less than one group of 128 pieces (wavefronts without a piece), of whole groups, of groups and a
     ragged rest, with a last piece of a few bytes; rank counts around the run length, in place, Recursive Doubling,
-    and where the form does not allow gangs (teams, narrow accesses, the any-alignment form, Ring)."""
+    the any-alignment form, and where the form does not allow gangs (teams, narrow accesses, Ring)."""
     sb.sparbit_tune("tree_gang", 1)
     sb.sparbit_tune("tree_store", store)
     sb.sparbit_tune("tree_small_bytes", 0)
@@ -293,7 +293,16 @@ def test_gangs_of_wavefronts(torch, store):
         got = gpu_result(torch, sb.RECURSIVE_DOUBLING, p, B, send, sb.MODE_TREE)
         assert launched_gangs() and launched_doubling_form(), sb.sparbit_last_launch_info()
         assert np.array_equal(got, want), (p, B)
-    for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 4100, {}), (sb.SPARBIT, 3, 1040, {}), (sb.RING, 9, 4096, {}),
+    for p, B, mis in ((9, 4100, 0), (3, 1040, 0), (7, 33 * 1024 + 1, 0), (32, 70 * 1024 + 4, 0), (33, 40 * 1024 + 16, 3), (64, 512, 1),
+                      (128, 3 * 1024 + 1, 0), (16, 200 * 1024 + 8, 0)):
+        announce("gangs, any alignment", store, p, B, mis)
+        send = workloads.make_send_raw(p, B, seed=p + 1)
+        want = oracle_result(sb.SPARBIT, p, B, send)
+        got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, misalign=mis)
+        # rows off the lines store plain, which form 4 does not do: form 0 then, one wavefront per workgroup
+        assert launched_gangs() == (store == 1 or p * B % 128 == 0) and launched_any_alignment_form(), sb.sparbit_last_launch_info()
+        assert np.array_equal(got, want), (p, B, mis)
+    for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 500, {}), (sb.RING, 9, 4096, {}),
                               (sb.SPARBIT, 64, 1024, {"tree_team_log2": 2, "tree_store": 2})):
         for k, v in knobs.items():
             sb.sparbit_tune(k, v)
