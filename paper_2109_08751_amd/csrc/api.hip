@@ -638,12 +638,19 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if ((step_order_only || team > 1) && store_kind == 4) store_kind = 2;
     if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
-    if (sizeof(V) != 16 || U != 1 || team > 1 || WALK == kWalkChain || (store_kind != 1 && store_kind != 4)) gang = false;
+    if (sizeof(V) != 16 || U != 1 || team > 1 || (WALK != kWalkChain && store_kind != 1 && store_kind != 4)) gang = false;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s, %d>", type_label<V>(), U, NB, store_kind,
                 bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1), gang ? kTreeGang : 1);
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, WALK>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
     hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, WALK, true>), grid, dim3(64 * team), lds, stream, a)
+    if constexpr (U == 1 && WALK == kWalkChain && sizeof(V) == 16 && !ANY) {
+        if (gang) {  // Ring's chain stores plain (see choose_tree_walk)
+            hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
+            SB_HIP(hipGetLastError());
+            return SPARBIT_OK;
+        }
+    }
     if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16) {
         if (gang) {
             if (store_kind == 1)
@@ -889,7 +896,7 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
     // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
     // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
-    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && w.store == 4 && c.algo != SPARBIT_ALGO_RING &&
+    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && (ring ? total_bytes > 336 * MiB : w.store == 4) &&
         (on_boundaries || c.B >= 48 * 1024)) {
         w.gang = true;
         if (c.B % 131072 != 0 && on_boundaries && c.B < MiB) w.lg_s = 4;  // 64 KiB on its boundaries: two pieces of 32 KiB do not fit
@@ -960,7 +967,8 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const bool doubling = algo == SPARBIT_ALGO_RECURSIVE_DOUBLING;
     // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie `apart` pieces apart, i.e. per
     // group of kTreeGang * apart pieces `apart` workgroups; a block's last group may be part empty.
-    const bool gang = walk.gang && (width == 16 || any) && U == 1 && team == 1 && (st == 1 || st == 4) && algo != SPARBIT_ALGO_RING;
+    const bool ring = algo == SPARBIT_ALGO_RING;
+    const bool gang = walk.gang && U == 1 && team == 1 && (ring ? width == 16 && !any : (width == 16 || any) && (st == 1 || st == 4));
     a.lg_s = walk.lg_s;
     const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(kTreeGang) * apart;
     const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * apart : pieces;

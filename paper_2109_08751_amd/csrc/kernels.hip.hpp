@@ -251,8 +251,8 @@ template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY
           bool TEAM = false, int GANG = 1>
 __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const TreeArgs a)
 {
-    static_assert(GANG == 1 || (!TEAM && (ST == 1 || ST == 4) && sizeof(V) == 16 && U == 1),
-                  "gangs walk 16-byte vectors, one per lane, in the read-back-at-once forms");
+    static_assert(GANG == 1 || (!TEAM && (ST == 1 || ST == 4 || WALK == kWalkChain) && sizeof(V) == 16 && U == 1),
+                  "gangs walk 16-byte vectors, one per lane, in the read-back-at-once forms or along Ring's chain");
     constexpr bool DOUBLING = WALK == kWalkDoubling, CHAIN = WALK == kWalkChain;
     static_assert(!CHAIN || (!PF && !TEAM), "a chain has nothing to look ahead of and nothing to share");
     static_assert(!ANY || (U == 1 && sizeof(V) == 16), "the any-alignment form moves one 16-byte chunk per lane");
@@ -497,6 +497,9 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
     }
     if constexpr (CHAIN) {
         for (uint32_t rho = 1; rho < p; ++rho) {
+            if constexpr (GANG > 1) {
+                if ((rho & 3u) == 1u) __syncthreads();  // every wavefront of the gang takes every turn of this loop
+            }
             store(slot(rho), xh, true);
             if (rho + 1 < p) {
                 load(slot(rho), xh);  // what rho forwards is what it received

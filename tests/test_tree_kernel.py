@@ -271,7 +271,8 @@ def test_gangs_of_wavefronts(torch, store):
     """Workgroups of 4 wavefronts whose pieces lie 32 KiB apart and that meet at a barrier before every run: forced
     onto blocks of less than one group of 128 pieces (wavefronts without a piece), of whole groups, of groups and a
     ragged rest, with a last piece of a few bytes; rank counts around the run length, in place, Recursive Doubling,
-    the any-alignment form, and where the form does not allow gangs (teams, narrow accesses, Ring)."""
+    the any-alignment form, Ring's chain, and where the form does not allow gangs (teams, narrow accesses, Ring off
+    the lines)."""
     sb.sparbit_tune("tree_gang", 1)
     sb.sparbit_tune("tree_store", store)
     sb.sparbit_tune("tree_small_bytes", 0)
@@ -302,7 +303,15 @@ def test_gangs_of_wavefronts(torch, store):
         # rows off the lines store plain, which form 4 does not do: form 0 then, one wavefront per workgroup
         assert launched_gangs() == (store == 1 or p * B % 128 == 0) and launched_any_alignment_form(), sb.sparbit_last_launch_info()
         assert np.array_equal(got, want), (p, B, mis)
-    for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 500, {}), (sb.RING, 9, 4096, {}),
+    for p, B, in_place in ((2, 1024, False), (9, 4096, False), (17, 33 * 1024, True), (40, 130 * 1024 + 128, False), (131, 2048, False)):
+        announce("gangs, ring", store, p, B, in_place)
+        send = workloads.make_send_raw(p, B, seed=p + 2)
+        want = oracle_result(sb.RING, p, B, send, in_place=in_place)
+        got = gpu_result(torch, sb.RING, p, B, send, sb.MODE_TREE, in_place=in_place)
+        name = sb.sparbit_last_launch_info()[0]
+        assert launched_gangs() and name.rstrip(">").split(", ")[7] == "2", name
+        assert np.array_equal(got, want), (p, B, in_place)
+    for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 500, {}), (sb.RING, 9, 4100, {}),
                               (sb.SPARBIT, 64, 1024, {"tree_team_log2": 2, "tree_store": 2})):
         for k, v in knobs.items():
             sb.sparbit_tune(k, v)
