@@ -331,9 +331,10 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          Left at -1, with the other tree keys untouched, larger calls take store form 4 on a capped
  *                          grid (see tree_store; the any-alignment form only in rows on the lines, blocks of 10 KiB
  *                          and more, below 8 GiB)
- *   "tree_gang"            store forms 1 and 4 on whole 16-byte vectors: workgroups of 4 wavefronts whose pieces lie 32
- *                          KiB apart and that meet at a barrier before every run (-1, the default: by size; 0 never; 1
- *                          wherever the form allows); tree_lds_bytes then counts per wavefront all the same
+ *   "tree_gang"            store forms 1 and 4 on 16-byte vectors, and Ring: workgroups of 4 wavefronts whose pieces lie 32
+ *                          KiB apart and that meet at barriers (-1, the default: by size and block length; 0 never; 1
+ *                          wherever the form allows); tree_lds_bytes then counts per wavefront all the same, up to
+ *                          the 64 KiB a workgroup may reserve (16384 per wavefront: 2 gangs per unit)
  *   "tree_gang_apart_log2" ... 2^this KiB apart instead (0..10; -1, the default: by the call)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
  *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the

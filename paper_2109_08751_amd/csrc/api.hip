@@ -972,7 +972,8 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     a.lg_s = walk.lg_s;
     const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(kTreeGang) * apart;
     const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * apart : pieces;
-    const uint32_t lds = gang ? walk.lds * kTreeGang : walk.lds;  // per workgroup
+    // per workgroup; a workgroup may reserve 64 KiB at most (a gang: 16384 bytes per wavefront, 2 gangs per unit)
+    const uint32_t lds = gang ? (walk.lds * kTreeGang > 65536u ? 65536u : walk.lds * kTreeGang) : walk.lds;
     const dim3 grid(uint32_t(x_items << lg_g), groups, 1);
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
