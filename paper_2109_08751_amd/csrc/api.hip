@@ -882,7 +882,7 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     }
     // Gangs (the kernel's GANG): where form 4 was chosen above for whole 16-byte vectors and the blocks are a multiple
     // of 64 KiB, so that the 64 or 128 KiB that a gang's four pieces span start on such a boundary at every rank, or
-    // are 48 KiB and more (then the gain is smaller: 3-10 %).  Against the choice above: cfg5 2.70 against 3.21 ms, cfg4 2.66
+    // are 16 KiB and more (then the gain is smaller: 3-10 %).  Against the choice above: cfg5 2.70 against 3.21 ms, cfg4 2.66
     // against 3.07 ms, p = 64 with 1 MiB blocks 683 against 777 us, p = 16 with 4 MiB blocks 192 against 222 us, p = 128
     // with 64 KiB blocks 183 against 214 us; blocks off those boundaries: p = 125 with 1073 KiB blocks 2.55 against
     // 2.75 ms, p = 33 with 1925 KiB blocks 394 against 417 us, p = 257 with 254 KiB blocks 3.11 against 3.13 ms.  Few
@@ -897,15 +897,27 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
     // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
     if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && (ring ? total_bytes > 336 * MiB : w.store == 4) &&
-        (on_boundaries || c.B >= 48 * 1024)) {
+        (on_boundaries || c.B >= 16 * 1024)) {
         w.gang = true;
+        const bool short_blocks = c.B < 48 * 1024;
         if (c.B % 131072 != 0 && on_boundaries && c.B < MiB) w.lg_s = 4;  // 64 KiB on its boundaries: two pieces of 32 KiB do not fit
         if (!on_boundaries && c.B < 400 * 1024) {  // few pieces: the spacing that leaves fewer wavefronts without one
             const uint64_t pieces = (c.B + 1023) / 1024;
             const uint64_t room4 = (pieces + 63) / 64 * 64, room5 = (pieces + 127) / 128 * 128;
             w.lg_s = room4 < room5 ? 4u : room5 < room4 ? 5u : w.lg_s;
+            uint64_t room = room4 < room5 ? room4 : room5;
+            if (short_blocks) {  // 16 or 32 KiB: closer together, so that a gang's four all lie inside a block
+                // (p = 256, 32 KiB: 393 us with 8 KiB between them, 401 us with 16, 429 us without gangs; p = 256, 16 KiB:
+                // 200 / 311 / 213 us with 4 / 16 KiB / none; p = 128, 32 KiB: 100 against 105 us; 8 KiB blocks: no gain;
+                // blocks that are not a multiple of the 16 or 32 KiB a gang spans lose: p = 200, 20 KiB: 196 against
+                // 162 us; p = 96, 40 KiB: 94 against 73 us)
+                w.lg_s = pieces >= 32 ? 3u : 2u;
+                const uint64_t group = uint64_t(4) << w.lg_s;
+                room = (pieces + group - 1) / group * group;
+                if (room != pieces) w.gang = false;
+            }
             // ... and none where two in five would be (p = 253, 65 KiB blocks: 908 against 820 us)
-            if (pieces * 5 < (room4 < room5 ? room4 : room5) * 3) w.gang = false;
+            if (pieces * 5 < room * 3) w.gang = false;
         }
         const Cap g16{10240u, 16 * 256}, g12{12800u, 12 * 256}, g8{14336u, 8 * 256};  // per wavefront; a gang reserves four times that
         auto rounds_fit = [&](const Cap& cap) {
@@ -913,12 +925,15 @@ TreeWalk choose_tree_walk(const TreeCall& c)
             return waves <= cap.places || waves >= 6 * cap.places || last == 0 || last * 2 >= cap.places;
         };
         // (per-slot sizes: 12, the blocks' lengths differ; p = 128 with blocks of 0.5-1.5 MiB: 3.17 against 3.38 ms with 8)
-        const Cap order[3] = {p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB || c.var) ? g12 : g8,
-                              p <= 16 ? g12 : g16, p <= 48 ? g8 : g12};
-        if (w.gang) {
-            w.lds = g16.lds;
+        const Cap order[3] = {short_blocks ? g8 : p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB || c.var) ? g12 : g8,
+                              short_blocks ? g12 : p <= 16 ? g12 : g16, short_blocks ? g16 : p <= 48 ? g8 : g12};
+        if (w.gang) {  // ... and no gangs where no cap fits (p = 257, 16 KiB, 4112 wavefronts: 255 against 220 us)
+            const uint32_t none = ~0u;
+            uint32_t fit = none;
             for (int i = 2; i >= 0; --i)
-                if (rounds_fit(order[i])) w.lds = order[i].lds;
+                if (rounds_fit(order[i])) fit = order[i].lds;
+            if (fit == none) w.gang = false;
+            else w.lds = fit;
         }
     }
     return w;
