@@ -16,14 +16,17 @@
  *             MPI_Allgather post-condition of Section II of the paper.
  *   Blocks are opaque bytes; the MPI (count, datatype) pair collapses into
  *   block_bytes.  Any block_bytes and any base alignment is accepted.  What
- *   the full rate of a Sparbit call needs is that p * block_bytes, the distance
- *   between two ranks' receive buffers, is a multiple of 128: blocks of 512
- *   bytes and more then move in 16-byte vectors that cover whole 128-byte
- *   lines wherever the blocks start and end (single bytes at their two ends).
- *   With other row lengths such blocks still move in 16-byte vectors, on
- *   calls of several GiB at about 60 % of that rate (one launch per step);
- *   blocks shorter than 512 bytes move with 16-, 4- or single-byte accesses as
- *   their alignment allows.
+ *   a Sparbit call needs to run as one launch at any size is that p *
+ *   block_bytes, the distance between two ranks' receive buffers, is a
+ *   multiple of 128: blocks of 512 bytes and more then move in 16-byte vectors
+ *   that cover whole 128-byte lines wherever the blocks start and end (single
+ *   bytes at their two ends).  With other row lengths such blocks still move
+ *   in 16-byte vectors, on calls of several GiB at about 60 % of that rate
+ *   (one launch per step); blocks shorter than 512 bytes move with 16-, 4- or
+ *   single-byte accesses as their alignment allows.  The highest rate (about
+ *   a fifth more on calls of 0.4 GiB and more) is that of blocks on the
+ *   128-byte grid whose length is a multiple of 64 KiB, with base addresses
+ *   on that grid too (see "tree_gang" below).
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
@@ -207,8 +210,8 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  * Sparbit, Recursive Doubling and Ring go out as ONE launch of the tree form
  * (SPARBIT_MODE_TREE), which
  * reads each block's length and offset from the geometry's device copy, under
- * the same rules as equal blocks: counts and displs of any granularity run at
- * the full rate when row_bytes is a multiple of 128 (round the rows up where
+ * the same rules as equal blocks: counts and displs of any granularity run as
+ * one launch when row_bytes is a multiple of 128 (round the rows up where
  * the layout is yours to choose); with other row lengths the tree form serves
  * calls of up to 512 MiB, and larger ones only when everything is on the
  * 128-byte grid (or, for blocks below 64 KiB, on the 16-byte grid).
