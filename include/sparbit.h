@@ -24,9 +24,10 @@
  *   in 16-byte vectors, on calls of several GiB at about 60 % of that rate
  *   (one launch per step); blocks shorter than 512 bytes move with 16-, 4- or
  *   single-byte accesses as their alignment allows.  The highest rate (about
- *   a fifth more on calls of 0.4 GiB and more) is that of blocks on the
- *   128-byte grid whose length is a multiple of 64 KiB, with base addresses
- *   on that grid too (see "tree_gang" below).
+ *   a fifth more on calls of 0.4 GiB and more) is that of blocks whose length
+ *   is a multiple of 64 KiB in a receive buffer that starts on a 64 KiB
+ *   boundary (see "tree_gang" below); other bases on the 128-byte grid keep
+ *   0-8 % of it.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
