@@ -152,8 +152,9 @@ __global__ __launch_bounds__(WG) void static_tables_kernel(Copy* __restrict__ ou
 // holds the write); K >= p is the step order of Algorithm 1 (all forwards of a
 // step before the next step), which has the fewest dependent round trips.
 //
-// Workgroups are single wavefronts; blockIdx.x interleaves 2^lg_g trees so that
-// each XCD streams through the pieces of one tree at a time.
+// Workgroups are single wavefronts (teams and gangs, below, hold several);
+// blockIdx.x interleaves 2^lg_g trees so that each XCD streams through the
+// pieces of one tree at a time.
 // ---------------------------------------------------------------------------
 struct TreeArgs {
     const uint8_t* send;  // nullptr: in place, slot r of rank r already holds rank r's block
