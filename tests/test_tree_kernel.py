@@ -88,13 +88,14 @@ def launched_any_alignment_form():
 def test_any_alignment_form(torch, knobs):
     """Blocks of 512 bytes and more that do not start and end on 128-byte lines, in rows that are a multiple of 128
     bytes apart: pieces cut relative to the lines, 16-byte chunks plus single bytes at a block's two ends.  Block
-    lengths and base addresses at 1-, 4- and 16-byte granularity, a first piece of 0 .. 127 bytes, in place, and
-    what AUTO does with such a call."""
+    lengths and base addresses at 1-, 4- and 16-byte granularity, a first piece of 0 .. 127 bytes (0 .. 1023 in rows
+    that are a multiple of 1 KiB apart), in place, and what AUTO does with such a call."""
     for k, v in knobs.items():
         sb.sparbit_tune(k, v)
     cases = ((128, 513, 0, 0), (128, 1028, 0, 0), (64, 4100, 0, 0), (32, 1000, 0, 0), (8, 65552, 0, 0), (16, 2072, 3, 5),
              (64, 4096, 1, 0), (64, 4096, 127, 13), (256, 600, 0, 0), (96, 4100, 0, 8), (257, 1280, 4, 0), (24, 70000, 0, 0),
-             (8, 3 * 1024 + 16, 112, 0), (8, 2048, 16, 0), (40, 16 * 77, 15, 1))
+             (8, 3 * 1024 + 16, 112, 0), (8, 2048, 16, 0), (40, 16 * 77, 15, 1),
+             (64, 4112, 0, 0), (256, 1028, 0, 3), (128, 5 * 1024 + 8, 250, 0))  # rows a multiple of 1 KiB: pieces cut on 1 KiB boundaries
     for p, B, mis, smis in cases:
         assert p * B % 128 == 0
         for mode, in_place in ((sb.MODE_TREE, False), (sb.MODE_AUTO, False), (sb.MODE_TREE, True)):
