@@ -56,9 +56,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
 # tuning.  (The counters sit between the L2 and the memory side: reads that the Infinity Cache serves are in it.)
 MEASURED_TRAFFIC = {
     # (workload, kernel name as the library reports it): (bytes per launch, profile it comes from)
-    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 4>"):
+    ("cfg5", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 8>"):
         (17797121364, "profiles/tree_kernel_cfg4_cfg5.md"),
-    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 4>"):
+    ("cfg4", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 4, true, false, false, 0, false, 8>"):
         (17628656531, "profiles/tree_kernel_cfg4_cfg5.md"),
     ("p128_b1048580", "sparbit::tree_kernel<unsigned int __vector(4), 1, 8, 2, true, false, true, 0, false, 1>"):
         (20476002400, "profiles/tree_kernel_cfg4_cfg5.md"),

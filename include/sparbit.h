@@ -25,9 +25,9 @@
  *   (one launch per step); blocks shorter than 512 bytes move with 16-, 4- or
  *   single-byte accesses as their alignment allows.  The highest rate (about
  *   a fifth more on calls of 0.4 GiB and more) is that of blocks whose length
- *   is a multiple of 64 KiB in a receive buffer that starts on a 64 KiB
- *   boundary (see "tree_gang" below); other bases on the 128-byte grid keep
- *   0-8 % of it.
+ *   is a multiple of 64 KiB, better of 128 KiB, in a receive buffer that
+ *   starts on such a boundary (see "tree_gang" below); other bases on the
+ *   128-byte grid keep 0-8 % of it.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns
@@ -337,9 +337,12 @@ int sparbit_barrier_timeouts(void *stream, uint64_t *count);
  *                          grid (see tree_store; the any-alignment form only in rows on the lines, blocks of 10 KiB
  *                          and more, below 8 GiB)
  *   "tree_gang"            store forms 1 and 4 on 16-byte vectors, and Ring: workgroups of 4 wavefronts whose pieces lie 32
- *                          KiB apart and that meet at barriers (-1, the default: by size and block length; 0 never; 1
- *                          wherever the form allows); tree_lds_bytes then counts per wavefront all the same, up to
- *                          the 64 KiB a workgroup may reserve (16384 per wavefront: 2 gangs per unit)
+ *                          KiB apart and that meet at barriers (-1, the default: by size and block length, and one
+ *                          workgroup of 8 per compute unit, pieces 16 KiB apart, from 48 ranks on where the blocks
+ *                          are a multiple of 128 KiB; 0 never; 1 or 4 wherever the form allows; 8: workgroups of 8
+ *                          for equal blocks of whole vectors in store form 4 and for Ring, of 4 elsewhere);
+ *                          tree_lds_bytes then counts per wavefront all the same, up to the 64 KiB a workgroup of 4
+ *                          may reserve (16384 per wavefront: 2 gangs per unit) and the 160 KiB a workgroup of 8 may
  *   "tree_gang_apart_log2" ... 2^this KiB apart instead (0..10; -1, the default: by the call)
  *   "tree_prefetch"        0/1: it loads the first rank of the next run while it serves the current one
  *   "tree_any_align"       0/1: blocks of realign_min_bytes and more that are off the 128-byte grid run through the

@@ -620,11 +620,33 @@ int launch_dataflow_v(const FlowArgs& a, hipStream_t stream)
 }
 
 // The tree kernel: one wavefront, or with `team` > 1 that many, per (tree, piece of 64 * U vectors).
-constexpr int kTreeGang = 4;  // wavefronts per workgroup in the gang form
+constexpr uint32_t kTreeGang = 4;     // wavefronts per workgroup in the gang form ...
+constexpr uint32_t kTreeBigGang = 8;  // ... and in its second size: one such workgroup per compute unit (see choose_tree_walk)
+constexpr uint32_t kLdsPerUnit = 160 * 1024;
+
+// One gang launch.  A workgroup that is to have a compute unit to itself reserves more than half of the unit's LDS,
+// which is more than a kernel may ask for unless the function's limit has been raised: once per function and device.
+template <typename K>
+int launch_gang(K kernel, dim3 grid, uint32_t wavefronts, uint32_t lds, hipStream_t stream, const TreeArgs& a)
+{
+    if (lds > 65536u) {
+        static std::atomic<uint64_t> raised{0};  // one per kernel instantiation; bit d = done on device d
+        int device = 0;
+        SB_HIP(hipGetDevice(&device));
+        const uint64_t bit = uint64_t(1) << (device & 63);
+        if (device >= 64 || !(raised.load() & bit)) {
+            SB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, int(kLdsPerUnit)));
+            raised.fetch_or(bit);
+        }
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(64 * wavefronts), lds, stream, a);
+    SB_HIP(hipGetLastError());
+    return SPARBIT_OK;
+}
 
 template <typename V, int U, int NB, bool VAR, bool ANY = false, int WALK = kWalkSparbit>
 int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, uint32_t lds, uint64_t bytes, hipStream_t stream,
-                   uint32_t team = 1, bool gang = false)
+                   uint32_t team = 1, uint32_t gang = 1)
 {
     if (sizeof(V) != 16) store_kind = 0;
     // Ring's chain has no runs: no look-ahead, plain or write-through stores.  Recursive Doubling's tree has them
@@ -638,27 +660,29 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if ((step_order_only || team > 1) && store_kind == 4) store_kind = 2;
     if (store_kind == 1 || store_kind == 4) prefetch = true;
     if (WALK == kWalkChain) team = 1;
-    if (sizeof(V) != 16 || U != 1 || team > 1 || (WALK != kWalkChain && store_kind != 1 && store_kind != 4)) gang = false;
+    if (sizeof(V) != 16 || U != 1 || team > 1 || (WALK != kWalkChain && store_kind != 1 && store_kind != 4)) gang = 1;
+    // the larger gang: equal blocks of whole vectors, store form 4 or the chain (the caller sized the grid for it)
+    if (gang == kTreeBigGang && (VAR || ANY || (WALK != kWalkChain && store_kind != 4))) return SPARBIT_ERR_ARG;
     note_launch(bytes, "sparbit::tree_kernel<%s, %d, %d, %d, %s, %s, %s, %d, %s, %d>", type_label<V>(), U, NB, store_kind,
-                bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1), gang ? kTreeGang : 1);
+                bool_label(prefetch), bool_label(VAR), bool_label(ANY), WALK, bool_label(team > 1), int(gang));
 #define SB_TREE(ST, PF) hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, PF, VAR, ANY, WALK>), grid, dim3(64), lds, stream, a)
 #define SB_TEAM(ST) \
     hipLaunchKernelGGL((tree_kernel<V, U, NB, ST, false, VAR, ANY, WALK, true>), grid, dim3(64 * team), lds, stream, a)
     if constexpr (U == 1 && WALK == kWalkChain && sizeof(V) == 16 && !ANY) {
-        if (gang) {  // Ring's chain stores plain (see choose_tree_walk)
-            hipLaunchKernelGGL((tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
-            SB_HIP(hipGetLastError());
-            return SPARBIT_OK;
-        }
+        if constexpr (!VAR)
+            if (gang == kTreeBigGang)
+                return launch_gang(tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeBigGang>, grid, gang, lds, stream, a);
+        if (gang > 1)  // Ring's chain stores plain (see choose_tree_walk)
+            return launch_gang(tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
     }
     if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16) {
-        if (gang) {
+        if constexpr (!VAR && !ANY)
+            if (gang == kTreeBigGang)
+                return launch_gang(tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeBigGang>, grid, gang, lds, stream, a);
+        if (gang > 1) {
             if (store_kind == 1)
-                hipLaunchKernelGGL((tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
-            else
-                hipLaunchKernelGGL((tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeGang>), grid, dim3(64 * kTreeGang), lds, stream, a);
-            SB_HIP(hipGetLastError());
-            return SPARBIT_OK;
+                return launch_gang(tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
+            return launch_gang(tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
         }
     }
     if constexpr (U == 1 && WALK != kWalkChain) {
@@ -726,7 +750,7 @@ struct TreeLaunch {
     uint64_t bytes;
     hipStream_t stream;
     uint32_t team;
-    bool gang;
+    uint32_t gang;  // wavefronts per workgroup in the gang form, else 1
 };
 
 template <bool VAR, int WALK>
@@ -751,7 +775,7 @@ struct TreeWalk {
     uint32_t team;  // wavefronts per workgroup that share one piece of one tree
     int store;      // the kernel's store form
     uint32_t lds;   // bytes of LDS each wavefront reserves without using them: caps the resident wavefronts per unit
-    bool gang;      // workgroups of 4 wavefronts whose pieces lie 2^lg_s KiB apart
+    uint32_t gang;  // 4 or 8: workgroups of that many wavefronts whose pieces lie 2^lg_s KiB apart; 0: none
     uint32_t lg_s;
 };
 struct TreeCall {
@@ -892,13 +916,13 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     // gangs), again only where the grid's last round is at least half full or there are six rounds and more.
     const long long gang_knob = g_tree_gang.load(), apart_knob = g_tree_gang_apart_log2.load();
     const bool on_boundaries = c.B % 65536 == 0;
-    w.gang = gang_knob == 1;
+    w.gang = gang_knob == 1 ? kTreeGang : gang_knob > 1 ? uint32_t(gang_knob) : 0u;
     w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
     // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
     // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
     if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && (ring ? total_bytes > 336 * MiB : w.store == 4) &&
         (on_boundaries || c.B >= 16 * 1024)) {
-        w.gang = true;
+        w.gang = kTreeGang;
         const bool short_blocks = c.B < 48 * 1024;
         if (c.B % 131072 != 0 && on_boundaries && c.B < MiB) w.lg_s = 4;  // 64 KiB on its boundaries: two pieces of 32 KiB do not fit
         if (!on_boundaries && c.B < 400 * 1024) {  // few pieces: the spacing that leaves fewer wavefronts without one
@@ -914,10 +938,10 @@ TreeWalk choose_tree_walk(const TreeCall& c)
                 w.lg_s = pieces >= 32 ? 3u : 2u;
                 const uint64_t group = uint64_t(4) << w.lg_s;
                 room = (pieces + group - 1) / group * group;
-                if (room != pieces) w.gang = false;
+                if (room != pieces) w.gang = 0;
             }
             // ... and none where two in five would be (p = 253, 65 KiB blocks: 908 against 820 us)
-            if (pieces * 5 < room * 3) w.gang = false;
+            if (pieces * 5 < room * 3) w.gang = 0;
         }
         const Cap g16{10240u, 16 * 256}, g12{12800u, 12 * 256}, g8{14336u, 8 * 256};  // per wavefront; a gang reserves four times that
         auto rounds_fit = [&](const Cap& cap) {
@@ -932,8 +956,21 @@ TreeWalk choose_tree_walk(const TreeCall& c)
             uint32_t fit = none;
             for (int i = 2; i >= 0; --i)
                 if (rounds_fit(order[i])) fit = order[i].lds;
-            if (fit == none) w.gang = false;
+            if (fit == none) w.gang = 0;
             else w.lds = fit;
+            // One gang of 8 per unit instead of two of 4, pieces 16 KiB apart, where the blocks are a multiple of the 128 KiB
+            // that such a gang spans and there are 48 ranks and more: one address translation serves eight stores instead
+            // of four (cfg5 2.61 against 2.69 ms, cfg4 2.68 against 2.71 ms; p = 64 with 1 MiB blocks 650 against 684 us,
+            // with 128 KiB blocks 87 against 90 us; p = 128 with 512 KiB blocks 1.30 against 1.35 ms; p = 200 with 384 KiB
+            // blocks 2.42 against 2.49 ms; p = 32 with 1 MiB 181 against 176 us, p = 16 with 4 MiB 202 against 185 us;
+            // 8 KiB apart in blocks of 64 KiB: 2.75 ms on cfg4's size).  Two gangs of 8 per unit, or a gang of 16: slower
+            // than the gangs of 4 (cfg4 2.84, 2.78 ms).  Ring's chain by the same rule (cfg4's size 2.63 against 2.68 ms,
+            // p = 64 with 1 MiB blocks 659 against 673 us, cfg5's size level).
+            if (w.gang && rounds_fit(g8) && !c.var && c.B % 131072 == 0 && p >= 48) {
+                w.gang = kTreeBigGang;
+                w.lg_s = 4;
+                w.lds = kLdsPerUnit / 2 / kTreeBigGang + 256;  // more than half of the unit's LDS per gang
+            }
         }
     }
     return w;
@@ -983,12 +1020,17 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     // Gangs: a workgroup of kTreeGang wavefronts per kTreeGang pieces that lie `apart` pieces apart, i.e. per
     // group of kTreeGang * apart pieces `apart` workgroups; a block's last group may be part empty.
     const bool ring = algo == SPARBIT_ALGO_RING;
-    const bool gang = walk.gang && U == 1 && team == 1 && (ring ? width == 16 && !any : (width == 16 || any) && (st == 1 || st == 4));
+    const bool in_gangs = walk.gang && U == 1 && team == 1 && (ring ? width == 16 && !any : (width == 16 || any) && (st == 1 || st == 4));
+    // the larger gang exists for equal blocks of whole vectors in store form 4 and for the chain
+    const bool big = walk.gang == kTreeBigGang && !any && !counts && (ring || st == 4);
+    const uint32_t gang = !in_gangs ? 1u : big ? kTreeBigGang : kTreeGang;
     a.lg_s = walk.lg_s;
-    const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(kTreeGang) * apart;
-    const uint64_t x_items = gang ? (pieces + per_group - 1) / per_group * apart : pieces;
-    // per workgroup; a workgroup may reserve 64 KiB at most (a gang: 16384 bytes per wavefront, 2 gangs per unit)
-    const uint32_t lds = gang ? (walk.lds * kTreeGang > 65536u ? 65536u : walk.lds * kTreeGang) : walk.lds;
+    const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(gang) * apart;
+    const uint64_t x_items = in_gangs ? (pieces + per_group - 1) / per_group * apart : pieces;
+    // per workgroup: a gang of 4 may reserve 64 KiB at most (16384 bytes per wavefront: 2 gangs per unit), a gang of 8
+    // the unit's whole LDS
+    const uint32_t most = big ? kLdsPerUnit : 65536u;
+    const uint32_t lds = in_gangs ? (walk.lds * gang > most ? most : walk.lds * gang) : walk.lds;
     const dim3 grid(uint32_t(x_items << lg_g), groups, 1);
     const bool pf = g_tree_prefetch.load() != 0;
     *eligible = true;
@@ -1855,7 +1897,7 @@ int sparbit_tune(const char* key, long long value)
         if (value < -1 || value > 10) return SPARBIT_ERR_ARG;
         g_tree_gang_apart_log2 = value;
     } else if (!std::strcmp(key, "tree_gang")) {
-        if (value < -1 || value > 1) return SPARBIT_ERR_ARG;
+        if (value < -1 || (value > 1 && value != kTreeGang && value != kTreeBigGang)) return SPARBIT_ERR_ARG;
         g_tree_gang = value;
     } else if (!std::strcmp(key, "tree_hot")) {
         if (value < -1 || value > 1) return SPARBIT_ERR_ARG;

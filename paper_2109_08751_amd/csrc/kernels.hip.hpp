@@ -244,9 +244,13 @@ constexpr int kWalkSparbit = 0, kWalkDoubling = 1, kWalkChain = 2;
 // 2^lg_s KiB apart (16 or 32), and meet at a barrier before every run.  What the memory side then sees at one time are
 // stores to one rank's slot that lie 16 or 32 KiB apart, which it takes at a higher rate than stores to unrelated
 // places (a stream of nothing but such stores, 16 GiB: 6.4-6.6 TB/s with 32 KiB against 5.7 TB/s with adjacent or
-// unrelated pieces; 16 KiB apart 6.2-6.4, 64 KiB 6.2-6.3, 8 KiB and less or 256 KiB and more: no gain).  A piece index
-// past the block's end leaves its wavefront with an empty buffer: its accesses are dropped by the bounds check and
-// it still meets every barrier.
+// unrelated pieces; 16 KiB apart 6.2-6.4, 64 KiB 6.2-6.3, 8 KiB and less or 256 KiB and more: no gain).  The counters
+// say why: every store of a wavefront goes to another rank's receive buffer, megabytes from the one before, so a
+// compute unit's first-level address translation cache misses on nearly every store of independent wavefronts (cfg4:
+// 13.4 M misses per call, 0.8 per store); the wavefronts of a gang store into the same 64 or 128 KiB at the same time
+// and share one miss (gangs of 4: 4.0 M; cfg5 8.7 M against 2.1 M).  GANG is 4 (two gangs per compute unit) or 8 (one).
+// A piece index past the block's end leaves its wavefront with an empty buffer: its accesses are dropped by the
+// bounds check and it still meets every barrier.
 
 template <typename V, int U, int NB, int ST, bool PF, bool VAR = false, bool ANY = false, int WALK = kWalkSparbit,
           bool TEAM = false, int GANG = 1>

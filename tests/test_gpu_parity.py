@@ -272,7 +272,7 @@ def test_full_size_configs(torch, cfg, mode):
         sb.sparbit_allgather(d_send, d_recv, p, B)
         name = sb.sparbit_last_launch_info()[0]
         # the largest calls: runs of 8 with every forwarder read back at once, write-through for the other stores
-        assert "tree_kernel" in name and ", 8, 4, true, " in name and name.endswith(", false, 4>"), name  # ... in gangs of 4
+        assert "tree_kernel" in name and ", 8, 4, true, " in name and name.endswith(", false, 8>"), name  # ... in gangs of 8
     else:
         sb.sparbit_allgather_mode(d_send, d_recv, p, B, sb.SPARBIT, MODES[mode])
     torch.cuda.synchronize()

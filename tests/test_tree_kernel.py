@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 
 DEFAULTS = {"tree_run_log2": -1, "tree_small_bytes": 96 << 20, "tree_unroll": 1, "tree_store": 2, "tree_prefetch": 1,
             "tree_lds_bytes": -1, "tree_any_align": 1, "realign_min_bytes": 512,
-            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1, "tree_hot": -1, "tree_gang": -1}
+            "tree_part_line_max_bytes": 512 << 20, "tree_team_log2": -1, "tree_hot": -1, "tree_gang": -1,
+            "tree_gang_apart_log2": -1}
 
 
 @pytest.fixture(scope="module")
@@ -263,20 +264,37 @@ def test_calls_of_some_hundred_mib(torch, algo, p, B):
 
 
 def launched_gangs():
+    """Wavefronts per gang in the last launch (4 or 8); 0 if it was not the tree kernel in gangs."""
     name = sb.sparbit_last_launch_info()[0]
-    return "tree_kernel" in name and name.endswith(", false, 4>")
+    for size in (4, 8):
+        if "tree_kernel" in name and name.endswith(", false, %d>" % size):
+            return size
+    return 0
 
 
+@pytest.mark.parametrize("gang", [1, 8])
 @pytest.mark.parametrize("store", [1, 4])
-def test_gangs_of_wavefronts(torch, store):
+def test_gangs_of_wavefronts(torch, store, gang):
     """Workgroups of 4 wavefronts whose pieces lie 32 KiB apart and that meet at a barrier before every run: forced
     onto blocks of less than one group of 128 pieces (wavefronts without a piece), of whole groups, of groups and a
     ragged rest, with a last piece of a few bytes; rank counts around the run length, in place, Recursive Doubling,
     the any-alignment form, Ring's chain, and where the form does not allow gangs (teams, narrow accesses, Ring off
-    the lines)."""
-    sb.sparbit_tune("tree_gang", 1)
+    the lines).  The same with gangs of 8 asked for, which exist for equal blocks of whole vectors in store form 4
+    and for the chain (elsewhere gangs of 4 run), with the pieces 4, 16 and 32 KiB apart."""
+    sb.sparbit_tune("tree_gang", gang)
     sb.sparbit_tune("tree_store", store)
     sb.sparbit_tune("tree_small_bytes", 0)
+    size = 8 if gang == 8 and store == 4 else 4
+    if gang == 8:
+        for apart_log2, p, B in ((2, 5, 32 * 1024), (2, 19, 33 * 1024 + 128), (4, 10, 128 * 1024), (4, 65, 129 * 1024), (5, 3, 256 * 1024)):
+            sb.sparbit_tune("tree_gang_apart_log2", apart_log2)
+            announce("gangs of 8, apart", store, apart_log2, p, B)
+            send = workloads.make_send_raw(p, B, seed=p + apart_log2)
+            want = oracle_result(sb.SPARBIT, p, B, send)
+            got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE)
+            assert launched_gangs() == size, sb.sparbit_last_launch_info()
+            assert np.array_equal(got, want), (apart_log2, p, B)
+        sb.sparbit_tune("tree_gang_apart_log2", -1)
     for p, B in ((1, 4096), (2, 16), (3, 1024 + 128), (5, 33 * 1024), (7, 128 * 1024), (8, 160 * 1024 + 384), (9, 64 * 1024),
                  (16, 256 * 1024), (17, 100 * 1024 + 128), (21, 31 * 1024 + 256), (33, 130 * 1024), (64, 96 * 1024),
                  (65, 32 * 1024 + 128), (96, 1024), (129, 4096), (257, 2048 + 128)):  # whole lines, or under 512 bytes
@@ -286,14 +304,14 @@ def test_gangs_of_wavefronts(torch, store):
             want = oracle_result(sb.SPARBIT, p, B, send, in_place=in_place)
             got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, in_place=in_place)
             if not (p == 1 and in_place):
-                assert launched_gangs(), sb.sparbit_last_launch_info()
+                assert launched_gangs() == size, sb.sparbit_last_launch_info()
             assert np.array_equal(got, want), (p, B, in_place)
     for p, B in ((4, 64 * 1024), (32, 40 * 1024 + 128), (128, 1024)):
         announce("gangs, doubling", store, p, B)
         send = workloads.make_send_raw(p, B, seed=p)
         want = oracle_result(sb.RECURSIVE_DOUBLING, p, B, send)
         got = gpu_result(torch, sb.RECURSIVE_DOUBLING, p, B, send, sb.MODE_TREE)
-        assert launched_gangs() and launched_doubling_form(), sb.sparbit_last_launch_info()
+        assert launched_gangs() == size and launched_doubling_form(), sb.sparbit_last_launch_info()
         assert np.array_equal(got, want), (p, B)
     for p, B, mis in ((9, 4100, 0), (3, 1040, 0), (7, 33 * 1024 + 1, 0), (32, 70 * 1024 + 4, 0), (33, 40 * 1024 + 16, 3), (64, 512, 1),
                       (128, 3 * 1024 + 1, 0), (16, 200 * 1024 + 8, 0)):
@@ -302,7 +320,7 @@ def test_gangs_of_wavefronts(torch, store):
         want = oracle_result(sb.SPARBIT, p, B, send)
         got = gpu_result(torch, sb.SPARBIT, p, B, send, sb.MODE_TREE, misalign=mis)
         # rows off the lines store plain, which form 4 does not do: form 0 then, one wavefront per workgroup
-        assert launched_gangs() == (store == 1 or p * B % 128 == 0) and launched_any_alignment_form(), sb.sparbit_last_launch_info()
+        assert launched_gangs() == (4 if store == 1 or p * B % 128 == 0 else 0) and launched_any_alignment_form(), sb.sparbit_last_launch_info()
         assert np.array_equal(got, want), (p, B, mis)
     for p, B, in_place in ((2, 1024, False), (9, 4096, False), (17, 33 * 1024, True), (40, 130 * 1024 + 128, False), (131, 2048, False)):
         announce("gangs, ring", store, p, B, in_place)
@@ -310,7 +328,7 @@ def test_gangs_of_wavefronts(torch, store):
         want = oracle_result(sb.RING, p, B, send, in_place=in_place)
         got = gpu_result(torch, sb.RING, p, B, send, sb.MODE_TREE, in_place=in_place)
         name = sb.sparbit_last_launch_info()[0]
-        assert launched_gangs() and name.rstrip(">").split(", ")[7] == "2", name
+        assert launched_gangs() == (8 if gang == 8 else 4) and name.rstrip(">").split(", ")[7] == "2", name
         assert np.array_equal(got, want), (p, B, in_place)
     for algo, p, B, knobs in ((sb.SPARBIT, 9, 20, {}), (sb.SPARBIT, 9, 500, {}), (sb.RING, 9, 4100, {}),
                               (sb.SPARBIT, 64, 1024, {"tree_team_log2": 2, "tree_store": 2})):
