@@ -214,7 +214,7 @@ int sparbit_allgather_static(const void *sendbufs, void *recvbufs, int p, size_t
  * the same rules as equal blocks: counts and displs of any granularity run as
  * one launch when row_bytes is a multiple of 128 (round the rows up where
  * the layout is yours to choose, best to a multiple of 1024: the pieces
- * then start on 1 KiB boundaries at every rank, 10 % faster on 16 GiB); with other row lengths the tree form serves
+ * then start on 1 KiB boundaries at every rank, 1-4 % faster on 16 GiB); with other row lengths the tree form serves
  * calls of up to 512 MiB, and larger ones only when everything is on the
  * 128-byte grid (or, for blocks below 64 KiB, on the 16-byte grid).
  * Equal blocks at their packed offsets in rows that are longer than p blocks

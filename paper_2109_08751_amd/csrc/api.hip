@@ -115,7 +115,7 @@ std::atomic<long long> g_tree_auto{1};                        // AUTO runs Sparb
 std::atomic<long long> g_tree_auto_doubling{1};               // ... and whole Recursive Doubling calls too
 std::atomic<long long> g_tree_auto_ring{1};                   // ... and whole Ring calls (a chain per block)
 std::atomic<long long> g_tree_gang_apart_log2{-1};            // ... 2^this KiB apart (-1: by the call)
-std::atomic<long long> g_tree_gang{-1};                       // gangs of 4 wavefronts with pieces 32 KiB apart: -1 = by size, 0 = never, 1 = wherever the form allows
+std::atomic<long long> g_tree_gang{-1};                       // gangs of wavefronts: -1 = by size, 0 = never, 1 or 4 = gangs of 4 wherever the form allows, 8 = of 8 where they exist
 std::atomic<long long> g_tree_hot{-1};                        // plain stores with forwarders read back at once: -1 = by size, 0 = never, 1 = always
 std::atomic<long long> g_tree_team_log2{-1};                  // small calls: 2^this wavefronts share a tree's piece; -1 = by size
 std::atomic<long long> g_tree_run_log2{-1};                   // tree kernel: relative ranks are walked in runs of 2^this; -1 = by size
@@ -913,15 +913,25 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     // pieces per block leave most of a gang idle (p = 125, 6 KiB blocks: 56 against 22 us).  Pieces 32 KiB apart, 16 KiB
     // from 64 ranks on for blocks of 1 MiB and more or off the 128 KiB boundaries (cfg4 2.66 against 2.77 ms, cfg5 2.75
     // against 2.70 ms).  Resident wavefronts per unit: 16 up to 16 ranks, 12 up to 48 and up to 768 MiB, else 8 (two
-    // gangs), again only where the grid's last round is at least half full or there are six rounds and more.
+    // gangs), again only where the grid's last round is at least half full or there are six rounds and more; and one
+    // gang of 8 per unit from 48 ranks on where the blocks are a multiple of 128 KiB (below).
     const long long gang_knob = g_tree_gang.load(), apart_knob = g_tree_gang_apart_log2.load();
     const bool on_boundaries = c.B % 65536 == 0;
     w.gang = gang_knob == 1 ? kTreeGang : gang_knob > 1 ? uint32_t(gang_knob) : 0u;
     w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
     // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
     // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
-    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 && (ring ? total_bytes > 336 * MiB : w.store == 4) &&
-        (on_boundaries || c.B >= 16 * 1024)) {
+    // Form 1's calls gain where they no longer fit the last-level cache and the blocks are long: from 240 MiB on with
+    // blocks of 128 KiB and more, no cap (p = 16 with 1 MiB blocks 43.7 against 47.5 us, p = 8 with 4 MiB 52 against
+    // 61-65 us, p = 20 with 768 KiB 58 against 63 us, p = 24 with 512 KiB 48.9 against 52 us, p = 48 with 128 KiB 49.2
+    // against 50.3 us, p = 5 with 12 MiB 64 against 74 us; below 240 MiB or with shorter blocks 0 +- 1 %: p = 29 with
+    // 256 KiB 34.8 us either way, p = 96 with 32 KiB 46.7-47.4 against 46.5 us; blocks under 512 KiB off the 64 KiB
+    // boundaries lose: p = 40 with 160 KiB 43.6 against 42.4 us).  Ring's chain by the same rule (p = 16 with 1 MiB 43.5
+    // against 45.8 us, p = 8 with 4 MiB 48.5 against 53 us, p = 20 with 768 KiB 54.5 against 58 us).
+    const bool hot_gangs = (ring ? total_bytes <= 336 * MiB : w.store == 1) && total_bytes >= 240 * MiB && c.B >= 128 * 1024 &&
+                           (on_boundaries || c.B >= 512 * 1024);
+    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines16 &&
+        (ring ? (total_bytes > 336 * MiB || hot_gangs) : (w.store == 4 || hot_gangs)) && (on_boundaries || c.B >= 16 * 1024)) {
         w.gang = kTreeGang;
         const bool short_blocks = c.B < 48 * 1024;
         if (c.B % 131072 != 0 && on_boundaries && c.B < MiB) w.lg_s = 4;  // 64 KiB on its boundaries: two pieces of 32 KiB do not fit
@@ -951,7 +961,9 @@ TreeWalk choose_tree_walk(const TreeCall& c)
         // (per-slot sizes: 12, the blocks' lengths differ; p = 128 with blocks of 0.5-1.5 MiB: 3.17 against 3.38 ms with 8)
         const Cap order[3] = {short_blocks ? g8 : p <= 16 ? g16 : (p <= 48 || total_bytes <= 768 * MiB || c.var) ? g12 : g8,
                               short_blocks ? g12 : p <= 16 ? g12 : g16, short_blocks ? g16 : p <= 48 ? g8 : g12};
-        if (w.gang) {  // ... and no gangs where no cap fits (p = 257, 16 KiB, 4112 wavefronts: 255 against 220 us)
+        if (w.gang && hot_gangs) {
+            w.lds = 0;
+        } else if (w.gang) {  // ... and no gangs where no cap fits (p = 257, 16 KiB, 4112 wavefronts: 255 against 220 us)
             const uint32_t none = ~0u;
             uint32_t fit = none;
             for (int i = 2; i >= 0; --i)

@@ -293,7 +293,8 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
         const uint64_t own = reinterpret_cast<uint64_t>(a.recv) + uint64_t(b) * a.row_bytes + offset;
         // block bytes ahead of the first line boundary -- of the first 1 KiB boundary where the rows are a multiple of
         // 1 KiB apart, so that the pieces start on such boundaries at every rank (per-slot sizes of 0.5-1.5 MiB on 128
-        // ranks, rows rounded up to 1 KiB: 3.07 against 3.43 ms; in other rows the same cut costs 0-3 %)
+        // ranks, rows rounded up to 1 KiB, both cuts in turn on the same buffers: 3.00 against 3.13 ms, 3.40 against 3.43
+        // ms; in other rows the same cut costs 0-3 %)
         const uint64_t to_line = (0 - own) & ((a.row_bytes & 1023u) == 0 ? 1023u : 127u);
         const uint64_t i = piece_index;
         const uint64_t lo = i ? to_line + (i - 1) * 1024u : 0;

@@ -272,6 +272,35 @@ def launched_gangs():
     return 0
 
 
+@pytest.mark.parametrize("algo,p,B,store,gang", [
+    ("sparbit", 16, 1 << 20, 1, 4),            # 256 MiB, forwarders read back at once: gangs from 240 MiB on
+    ("sparbit", 48, 128 << 10, 1, 4),          # 288 MiB
+    ("sparbit", 29, 256 << 10, 1, 0),          # 210 MiB: none
+    ("sparbit", 40, 160 << 10, 1, 0),          # 250 MiB, blocks under 512 KiB off the 64 KiB boundaries: none
+    ("recursive_doubling", 16, 1 << 20, 1, 4),
+    ("ring", 16, 1 << 20, 0, 4),
+    ("ring", 29, 256 << 10, 0, 0),
+    ("sparbit", 64, 128 << 10, 4, 8),          # 512 MiB, blocks a multiple of 128 KiB, 48 ranks and more: one gang of 8 per unit
+    ("sparbit", 64, 192 << 10, 4, 4),          # blocks a multiple of 64 KiB only
+    ("sparbit", 32, 512 << 10, 4, 4),          # fewer than 48 ranks
+    ("recursive_doubling", 64, 128 << 10, 4, 8),
+    ("ring", 64, 128 << 10, 0, 8),
+])
+def test_where_auto_forms_gangs(torch, algo, p, B, store, gang):
+    """AUTO's choice of the gang form by call size, block length and rank count (store form 1 from 240 MiB on with
+    blocks of 128 KiB and more, store form 4 beyond 336 MiB, Ring's chain by the same sizes; gangs of 8 from 48 ranks
+    on for blocks that are a multiple of 128 KiB), every byte against the oracle."""
+    a = {"sparbit": sb.SPARBIT, "ring": sb.RING, "recursive_doubling": sb.RECURSIVE_DOUBLING}[algo]
+    announce("where AUTO forms gangs", algo, p, B)
+    send = workloads.make_send_raw(p, B, seed=p + 5)
+    want = oracle_result(a, p, B, send)
+    got = gpu_result(torch, a, p, B, send, sb.MODE_AUTO)
+    name = sb.sparbit_last_launch_info()[0]
+    assert "tree_kernel" in name and name.rstrip(">").split(", ")[3] == str(store), name
+    assert launched_gangs() == gang, name
+    assert np.array_equal(got, want), (algo, p, B)
+
+
 @pytest.mark.parametrize("gang", [1, 8])
 @pytest.mark.parametrize("store", [1, 4])
 def test_gangs_of_wavefronts(torch, store, gang):
