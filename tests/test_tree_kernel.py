@@ -482,6 +482,27 @@ def test_capture_records_the_tree_launch_and_needs_no_tables(torch):
         assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
 
 
+def test_capture_of_a_call_in_gangs_of_8(torch):
+    """A gang of 8 reserves more LDS than a kernel may ask for by default; the limit is raised outside the stream, so
+    such a launch can be recorded too, and every replay reproduces the oracle's result."""
+    p, B = 64, 128 << 10
+    send = workloads.make_send_raw(p, B, seed=8)
+    want = oracle_result(sb.SPARBIT, p, B, send)
+    d_send, d_recv, _ = gpu_buffers(torch, p, B, send)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            sb.sparbit_allgather(d_send, d_recv, p, B, torch.cuda.current_stream())
+    assert launched_gangs() == 8, sb.sparbit_last_launch_info()
+    for rep in range(3):
+        d_recv.fill_(POISON)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(d_recv.cpu().numpy().reshape(p, p, B), want), rep
+
+
 def test_many_streams_at_once(torch):
     """Nothing in the tree form waits for another workgroup, so any number of calls may run side by side."""
     cases = [(96, 4096), (64, 16384), (125, 512), (32, 65536), (12, 1024), (257, 1040)]
