@@ -626,11 +626,11 @@ constexpr uint32_t kLdsPerUnit = 160 * 1024;
 
 // One gang launch.  A workgroup that is to have a compute unit to itself reserves more than half of the unit's LDS,
 // which is more than a kernel may ask for unless the function's limit has been raised: once per function and device.
-template <typename K>
-int launch_gang(K kernel, dim3 grid, uint32_t wavefronts, uint32_t lds, hipStream_t stream, const TreeArgs& a)
+template <auto kernel>
+int launch_gang(dim3 grid, uint32_t wavefronts, uint32_t lds, hipStream_t stream, const TreeArgs& a)
 {
     if (lds > 65536u) {
-        static std::atomic<uint64_t> raised{0};  // one per kernel instantiation; bit d = done on device d
+        static std::atomic<uint64_t> raised{0};  // one per kernel (the kernel is a template argument); bit d = done on device d
         int device = 0;
         SB_HIP(hipGetDevice(&device));
         const uint64_t bit = uint64_t(1) << (device & 63);
@@ -671,18 +671,18 @@ int launch_tree_vu(const TreeArgs& a, dim3 grid, int store_kind, bool prefetch, 
     if constexpr (U == 1 && WALK == kWalkChain && sizeof(V) == 16 && !ANY) {
         if constexpr (!VAR)
             if (gang == kTreeBigGang)
-                return launch_gang(tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeBigGang>, grid, gang, lds, stream, a);
+                return launch_gang<&tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeBigGang>>(grid, gang, lds, stream, a);
         if (gang > 1)  // Ring's chain stores plain (see choose_tree_walk)
-            return launch_gang(tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
+            return launch_gang<&tree_kernel<V, U, NB, 0, false, VAR, ANY, WALK, false, kTreeGang>>(grid, gang, lds, stream, a);
     }
     if constexpr (U == 1 && WALK != kWalkChain && sizeof(V) == 16) {
         if constexpr (!VAR && !ANY)
             if (gang == kTreeBigGang)
-                return launch_gang(tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeBigGang>, grid, gang, lds, stream, a);
+                return launch_gang<&tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeBigGang>>(grid, gang, lds, stream, a);
         if (gang > 1) {
             if (store_kind == 1)
-                return launch_gang(tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
-            return launch_gang(tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeGang>, grid, gang, lds, stream, a);
+                return launch_gang<&tree_kernel<V, U, NB, 1, true, VAR, ANY, WALK, false, kTreeGang>>(grid, gang, lds, stream, a);
+            return launch_gang<&tree_kernel<V, U, NB, 4, true, VAR, ANY, WALK, false, kTreeGang>>(grid, gang, lds, stream, a);
         }
     }
     if constexpr (U == 1 && WALK != kWalkChain) {
