@@ -721,7 +721,7 @@ def main():
         # Allgatherv on a cfg4-shaped job: 128 ranks, block sizes spread over 0.5 .. 1.5 MiB (mean 1 MiB), at three
         # granularities: 4 KiB (every block on whole 128-byte lines), 4 bytes and 1 byte.  The last two with rows as
         # long as the blocks need (the rows then lie differently relative to the lines: realigning kernel, one launch
-        # per step) and with rows rounded up to whole lines or to 1 KiB (any-alignment tree form, one launch).
+        # per step) and with rows rounded up to whole lines to 1 KiB or to 64 KiB (any-alignment tree form, one launch; in rows a multiple of 64 KiB in gangs).
         import numpy as np
         pv = 128
         for label, grain, row_grain in (("allgatherv_p128_0.5-1.5MiB", 4096, 1),
@@ -729,7 +729,8 @@ def main():
                                         ("allgatherv_p128_0.5-1.5MiB_grain1B", 1, 1),
                                         ("allgatherv_p128_0.5-1.5MiB_grain4B_rows128", 4, 128),
                                         ("allgatherv_p128_0.5-1.5MiB_grain1B_rows128", 1, 128),
-                                        ("allgatherv_p128_0.5-1.5MiB_grain1B_rows1024", 1, 1024)):
+                                        ("allgatherv_p128_0.5-1.5MiB_grain1B_rows1024", 1, 1024),
+                                        ("allgatherv_p128_0.5-1.5MiB_grain1B_rows65536", 1, 65536)):
             rng = np.random.default_rng(workloads.DEFAULT_SEED)
             counts = (rng.integers(512 << 10, (1536 << 10) + 1, pv) // grain * grain).astype(np.uint64)
             displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)

@@ -784,6 +784,7 @@ struct TreeCall {
     bool any;         // the any-alignment form ...
     bool part_lines;  // ... in rows that are not a multiple of 128 bytes apart: stores cover parts of lines at most ranks
     bool var;         // per-slot sizes
+    bool rows_64k;    // rows a multiple of 64 KiB apart
     int width, U;     // bytes per access (any: 0) and 16-byte vectors per lane
     uint64_t total_bytes, waves;  // receive bytes of the call; wavefronts (teams) of the grid
 };
@@ -985,6 +986,25 @@ TreeWalk choose_tree_walk(const TreeCall& c)
             }
         }
     }
+    // The any-alignment form in rows a multiple of 64 KiB apart: its pieces are the cells of the 1 KiB grid of addresses
+    // and a gang's four lie in one 64 KiB group of that grid at every rank, whatever the blocks' lengths and places
+    // (the kernel's ANY), so long blocks gain as aligned ones do, less the part-filled groups at a block's two ends
+    // (per-slot sizes of 0.5-1.5 MiB at 1-byte granularity on 128 ranks, rows rounded up to 64 KiB: 3.08 against 3.43 ms
+    // with 16 wavefronts per unit, 3.17 ms with 12; 128 ranks with blocks of 1 MiB + 512 bytes from a base 16 bytes off
+    // the lines: 3.02 ms with 12 per unit, 3.11 ms with 8, 3.31 ms without gangs).
+    if (gang_knob < 0 && untouched && hot_knob < 0 && apart_knob < 0 && lines_any && c.rows_64k && !ring && total_bytes > 336 * MiB &&
+        c.B >= 512 * 1024) {
+        const Cap cap = c.var ? Cap{10240u, 16 * 256} : Cap{12800u, 12 * 256};
+        const uint64_t last = waves % cap.places;
+        if (waves >= 6 * cap.places || last == 0 || last * 2 >= cap.places) {
+            w.store = 4;
+            w.lg_k = 3;
+            w.team = 1;
+            w.gang = kTreeGang;
+            w.lg_s = 4;
+            w.lds = cap.lds;
+        }
+    }
     return w;
 }
 
@@ -1024,7 +1044,7 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     a.top = p > 1 ? 1u << (ceil_log2(p) - 1) : 0u;
     a.lg_g = lg_g;
     const uint64_t waves = pieces * uint64_t(p);
-    const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, counts != nullptr, width, U, total_bytes, waves});
+    const TreeWalk walk = choose_tree_walk(TreeCall{algo, p, B, any, any && row_bytes % 128 != 0, counts != nullptr, row_bytes % 65536 == 0, width, U, total_bytes, waves});
     a.lg_k = walk.lg_k;
     const uint32_t team = walk.team;
     const int st = walk.store;
@@ -1038,7 +1058,10 @@ int launch_tree(int algo, const void* sendbufs, void* recvbufs, int p, size_t B,
     const uint32_t gang = !in_gangs ? 1u : big ? kTreeBigGang : kTreeGang;
     a.lg_s = walk.lg_s;
     const uint64_t apart = uint64_t(1) << walk.lg_s, per_group = uint64_t(gang) * apart;
-    const uint64_t x_items = in_gangs ? (pieces + per_group - 1) / per_group * apart : pieces;
+    // (the any-alignment form in rows a multiple of a gang's span apart counts a gang's pieces from the boundary of the
+    // address grid below the block: up to a group less one of places ahead of the block's first piece stay empty)
+    const uint64_t places = any && row_bytes % (per_group * 1024) == 0 ? pieces + per_group - 1 : pieces;
+    const uint64_t x_items = in_gangs ? (places + per_group - 1) / per_group * apart : pieces;
     // per workgroup: a gang of 4 may reserve 64 KiB at most (16384 bytes per wavefront: 2 gangs per unit), a gang of 8
     // the unit's whole LDS
     const uint32_t most = big ? kLdsPerUnit : 65536u;

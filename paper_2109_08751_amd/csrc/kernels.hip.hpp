@@ -291,24 +291,44 @@ __global__ __launch_bounds__(TEAM ? 1024 : 64 * GANG) void tree_kernel(const Tre
     if constexpr (ANY) {
         const uint64_t bytes = VAR ? a.counts[b] : a.block_bytes;
         const uint64_t own = reinterpret_cast<uint64_t>(a.recv) + uint64_t(b) * a.row_bytes + offset;
-        // block bytes ahead of the first line boundary -- of the first 1 KiB boundary where the rows are a multiple of
-        // 1 KiB apart, so that the pieces start on such boundaries at every rank (per-slot sizes of 0.5-1.5 MiB on 128
-        // ranks, rows rounded up to 1 KiB, both cuts in turn on the same buffers: 3.00 against 3.13 ms, 3.40 against 3.43
-        // ms; in other rows the same cut costs 0-3 %)
-        const uint64_t to_line = (0 - own) & ((a.row_bytes & 1023u) == 0 ? 1023u : 127u);
-        const uint64_t i = piece_index;
-        const uint64_t lo = i ? to_line + (i - 1) * 1024u : 0;
-        uint64_t hi = to_line + i * 1024u;
-        if (hi > bytes) hi = bytes;
-        uint64_t at = lo;
-        if (lo >= hi) {  // uniform: no bytes ahead of the line, or past the block's end
-            if constexpr (GANG == 1) return;
-            at = hi = 0;  // stays for the barriers, with an empty buffer
+        uint64_t at, hi;
+        bool none;  // uniform: no such piece in this block
+        if ((a.row_bytes & 1023u) == 0) {
+            // Rows a multiple of 1 KiB apart: the pieces are the block's parts in the cells of the 1 KiB grid of
+            // addresses, which are the same cells at every rank (per-slot sizes of 0.5-1.5 MiB on 128 ranks, rows rounded
+            // up to 1 KiB, against the cut below, in turn on the same buffers: 3.00 against 3.13 ms, 3.40 against 3.43 ms).
+            // piece_index counts cells from the block's first one; in gangs, where the rows are a multiple of the GANG <<
+            // lg_s KiB apart that a gang spans, from the start of the group of that many cells that holds it, so that a
+            // gang's pieces lie in one such group of the address grid at every rank.
+            uint64_t cell = own >> 10;
+            if constexpr (GANG > 1) {
+                const uint64_t group = uint64_t(GANG) << a.lg_s;  // cells
+                if ((a.row_bytes & ((group << 10) - 1u)) == 0) cell &= ~(group - 1u);
+            }
+            cell += piece_index;
+            const uint64_t lo = cell << 10 > own ? cell << 10 : own;
+            const uint64_t end = own + bytes, up = (cell + 1) << 10 < end ? (cell + 1) << 10 : end;
+            none = lo >= up;
+            at = none ? 0 : lo - own;
+            hi = none ? 0 : up - own;
+        } else {
+            // other rows: the block bytes ahead of the first line boundary, then 1 KiB pieces (the cells' cut costs 0-3 %
+            // here)
+            const uint64_t to_line = (0 - own) & 127u;
+            const uint64_t i = piece_index;
+            at = i ? to_line + (i - 1) * 1024u : 0;
+            hi = to_line + i * 1024u;
+            if (hi > bytes) hi = bytes;
+            none = at >= hi;
+            if (none) at = hi = 0;
+        }
+        if (none) {
+            if constexpr (GANG == 1) return;  // in a gang it stays for the barriers, with an empty buffer
         }
         offset += at;
         piece_vectors = uint32_t(hi - at) >> 4;
         tail_bytes = uint32_t(hi - at) & 15u;
-        part_of_a_line = i == 0 || hi - at != 1024u;
+        part_of_a_line = hi - at != 1024u || ((own + at) & 127u) != 0;
     } else {
         const uint64_t vectors = VAR ? a.counts[b] / sizeof(V) : a.vpb;
         uint64_t piece_at = uint64_t(piece_index) * uint64_t(64 * U);  // first vector of the piece

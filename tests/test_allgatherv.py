@@ -317,6 +317,39 @@ def test_gpu_allgatherv_forwarders_read_back_at_once():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("algo", ["sparbit", "recursive_doubling"])
+def test_gpu_allgatherv_long_blocks_of_any_size_in_rows_a_multiple_of_64_kib(algo):
+    """Per-slot sizes at 1-byte granularity, blocks of 0.5-1 MiB, some hundred MiB per call: in rows that are a multiple
+    of 64 KiB apart AUTO runs the any-alignment form in gangs whose pieces are counted from the boundaries of the
+    address grid (places ahead of a block's first piece and past its last one stay empty); in rows rounded up to 1 KiB
+    only, as independent wavefronts.  From a base on a 64 KiB boundary and from one 48 bytes past it, in place."""
+    import torch
+    a, oa, p = (sb.SPARBIT, oracle.SPARBIT, 24) if algo == "sparbit" else (sb.RECURSIVE_DOUBLING, oracle.RECURSIVE_DOUBLING, 32)
+    rng = np.random.default_rng(7)
+    counts = rng.integers(512 << 10, (1 << 20) + 1, p).astype(np.uint64)
+    counts[3] = 0
+    counts[5] = 700
+    displs = np.concatenate([[0], np.cumsum(counts[:-1])]).astype(np.uint64)
+    for row_grain, misalign, in_place, gangs in ((65536, 0, False, True), (65536, 48, True, True), (1024, 0, False, False)):
+        row = (int(counts.sum()) + row_grain - 1) // row_grain * row_grain
+        assert p * row > (336 << 20)
+        send = payload(row, p)
+        print("[case] allgatherv, any sizes, long blocks", algo, p, row, misalign, in_place, flush=True)
+        want = np.full((p, row), POISON, dtype=np.uint8)
+        if in_place:
+            for r in range(p):
+                d, c = int(displs[r]), int(counts[r])
+                want[r, d:d + c] = send[d:d + c]
+        oracle.allgatherv(oa, p, counts, displs, row, None if in_place else send, want)
+        got = gpu_allgatherv(torch, a, p, counts, displs, row, send, in_place=in_place, misalign=misalign)
+        name = sb.sparbit_last_launch_info()[0]
+        args = name.rstrip(">").split(", ")  # access type, U, NB, store, look-ahead, sizes, any, walk, team, gang
+        assert "tree_kernel" in name and args[5] == "true" and args[6] == "true", name
+        assert (args[9] == "4" and args[3] == "4") == gangs, name
+        assert np.array_equal(got, want), (algo, row_grain, misalign, in_place)
+
+
+@pytest.mark.gpu
 def test_gpu_allgatherv_block_with_more_tiles_than_the_grid_holds():
     """Eight copies of a block of 4 GiB + 48 B in one launch (DIRECT, p = 8, the other blocks tiny): the looping
     kernel takes over.  Expected state: every receive buffer equals the send layout inside the blocks (the

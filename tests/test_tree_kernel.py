@@ -343,7 +343,9 @@ def test_gangs_of_wavefronts(torch, store, gang):
         assert launched_gangs() == size and launched_doubling_form(), sb.sparbit_last_launch_info()
         assert np.array_equal(got, want), (p, B)
     for p, B, mis in ((9, 4100, 0), (3, 1040, 0), (7, 33 * 1024 + 1, 0), (32, 70 * 1024 + 4, 0), (33, 40 * 1024 + 16, 3), (64, 512, 1),
-                      (128, 3 * 1024 + 1, 0), (16, 200 * 1024 + 8, 0)):
+                      (128, 3 * 1024 + 1, 0), (16, 200 * 1024 + 8, 0),
+                      # rows a multiple of 1 KiB: a gang's pieces counted from a boundary of the address grid
+                      (32, 70 * 1024 + 32, 0), (16, 200 * 1024 + 64, 5), (128, 3 * 1024 + 8, 3), (64, 64 * 1024 + 16, 200), (8, 128 + 1024 * 1024, 64)):
         announce("gangs, any alignment", store, p, B, mis)
         send = workloads.make_send_raw(p, B, seed=p + 1)
         want = oracle_result(sb.SPARBIT, p, B, send)
