@@ -27,7 +27,9 @@
  *   a fifth more on calls of 0.4 GiB and more) is that of blocks whose length
  *   is a multiple of 64 KiB, better of 128 KiB, in a receive buffer that
  *   starts on such a boundary (see "tree_gang" below); other bases on the
- *   128-byte grid keep 0-8 % of it.
+ *   128-byte grid keep 0-8 % of it.  Long blocks of other lengths come to
+ *   within 10 % of it where p * block_bytes (Allgatherv: row_bytes) is a
+ *   multiple of 64 KiB.
  *
  * Every entry point returns SPARBIT_OK (0) or a negative SPARBIT_ERR_* code and
  * never throws.  Work is enqueued on the caller's stream; the call returns

@@ -1088,10 +1088,18 @@ bool auto_takes_tree_form(int algo)
 // from the block's start, 0 = the any-alignment form, -1 = none (the call goes out step by step).  `w` is the
 // access width the call's addresses and lengths allow, `whole_lines` says that every block starts and ends on a
 // 128-byte line as it is, `longest` is the longest block, `asked_for` an explicit SPARBIT_MODE_TREE.
-int tree_form(bool asked_for, int w, bool whole_lines, uint64_t row_bytes, size_t longest, uint64_t total_bytes, int p)
+int tree_form(int algo, bool asked_for, int w, bool whole_lines, uint64_t row_bytes, size_t longest, uint64_t total_bytes, int p)
 {
-    if (w == 16 && whole_lines) return 16;
     const bool longish = longest >= size_t(g_realign_min_bytes.load());
+    if (w == 16 && whole_lines) {
+        // Long blocks on the lines but off the 64 KiB boundaries, in rows that are a multiple of 64 KiB apart: cut from
+        // their starts, a gang's pieces straddle those boundaries; the any-alignment form cuts them by the address grid
+        // and counts a gang's pieces from its boundaries (see choose_tree_walk; p = 128, blocks of 1 MiB + 512 bytes:
+        // 3.02 against 3.27 ms).
+        const bool by_the_grid = g_tree_any_align.load() != 0 && algo != SPARBIT_ALGO_RING && row_bytes % 65536 == 0 &&
+                                 longest % 65536 != 0 && longest >= (size_t(512) << 10) && total_bytes > (uint64_t(336) << 20);
+        if (!by_the_grid) return 16;
+    }
     if (g_tree_any_align.load() != 0 && longish) {
         // Rows a multiple of 128 bytes apart: every rank's copy of a slot lies the same way relative to the lines,
         // so the any-alignment form writes whole lines everywhere (p = 128, B = 1 MiB + 4: 3.23 ms against 5.32 ms
@@ -1368,7 +1376,7 @@ int run_v(const void* sendbufs, void* recvbufs, int p, const size_t* counts, con
     }
     total_bytes *= uint64_t(p);
     // Sparbit as the tree kernel, by the same rules as for equal blocks.
-    const int form = auto_takes_tree_form(algo) ? tree_form(false, width, (bits & 127) == 0, row_bytes, longest, total_bytes, p)
+    const int form = auto_takes_tree_form(algo) ? tree_form(algo, false, width, (bits & 127) == 0, row_bytes, longest, total_bytes, p)
                                                 : -1;
     const bool tree = form >= 0;
     // Equal blocks at their packed positions in rows that are longer than p blocks (padded rows): the equal-block
@@ -1515,7 +1523,7 @@ int run(const void* sendbufs, void* recvbufs, int p, size_t B, int algo, int mod
     if (whole && has_tree_form && (mode == SPARBIT_MODE_TREE || (mode == SPARBIT_MODE_AUTO && auto_takes_tree_form(algo)))) {
         const int w = access_width(sendbufs, recvbufs, nullptr, B);
         const bool whole_lines = ((uintptr_t(recvbufs) | uintptr_t(B)) & 127) == 0;
-        const int form = tree_form(mode == SPARBIT_MODE_TREE, w, whole_lines, uint64_t(p) * B, B, recv_bytes, p);
+        const int form = tree_form(algo, mode == SPARBIT_MODE_TREE, w, whole_lines, uint64_t(p) * B, B, recv_bytes, p);
         if (form >= 0) {
             bool eligible = false;
             const int trc = launch_tree(algo, sendbufs, recvbufs, p, B, size_t(p) * B, nullptr, nullptr, recv_bytes, form,

@@ -301,6 +301,25 @@ def test_where_auto_forms_gangs(torch, algo, p, B, store, gang):
     assert np.array_equal(got, want), (algo, p, B)
 
 
+@pytest.mark.parametrize("algo", ["sparbit", "recursive_doubling", "ring"])
+def test_long_blocks_off_the_64_kib_boundaries_are_cut_by_the_address_grid(torch, algo):
+    """Blocks on the lines whose length is not a multiple of 64 KiB, in rows that are: AUTO cuts them by the 1 KiB grid
+    of addresses (the any-alignment form) and counts a gang's pieces from the grid's 64 KiB boundaries, so the groups
+    at a block's two ends are part empty.  Ring keeps the cut from the block's start.  Every byte against the oracle."""
+    a = {"sparbit": sb.SPARBIT, "ring": sb.RING, "recursive_doubling": sb.RECURSIVE_DOUBLING}[algo]
+    p = 32 if algo == "recursive_doubling" else 24
+    B = (1 << 20) + (8 << 10)
+    assert p * B % 65536 == 0 and B % 65536 != 0
+    announce("cut by the address grid", algo, p, B)
+    send = workloads.make_send_raw(p, B, seed=p + 6)
+    want = oracle_result(a, p, B, send)
+    got = gpu_result(torch, a, p, B, send, sb.MODE_AUTO)
+    name = sb.sparbit_last_launch_info()[0]
+    assert launched_gangs() == 4, name
+    assert launched_any_alignment_form() == (algo != "ring"), name
+    assert np.array_equal(got, want), (algo, p, B)
+
+
 @pytest.mark.parametrize("gang", [1, 8])
 @pytest.mark.parametrize("store", [1, 4])
 def test_gangs_of_wavefronts(torch, store, gang):
