@@ -68,6 +68,11 @@ def test_bad_arguments_are_rejected_on_the_host():
         sb.sparbit_tune("no_such_knob", 1)
     with pytest.raises(sb.SparbitError):
         sb.sparbit_tune("wg_threads", 1000)
+    for value in (2, 3, 5, 16, -2):  # wavefronts per gang: 4 or 8 (1: 4; 0: none; -1: by the call)
+        with pytest.raises(sb.SparbitError):
+            sb.sparbit_tune("tree_gang", value)
+    for value in (0, 1, 4, 8, -1):
+        sb.sparbit_tune("tree_gang", value)
 
 
 ORACLE_ALGO = {sb.SPARBIT: oracle.SPARBIT, sb.RING: oracle.RING,
