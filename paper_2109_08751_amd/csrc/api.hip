@@ -920,8 +920,9 @@ TreeWalk choose_tree_walk(const TreeCall& c)
     const bool on_boundaries = c.B % 65536 == 0;
     w.gang = gang_knob == 1 ? kTreeGang : gang_knob > 1 ? uint32_t(gang_knob) : 0u;
     w.lg_s = apart_knob >= 0 ? uint32_t(apart_knob) : p >= 64 && (c.B >= MiB || c.B % 131072 != 0) ? 4u : 5u;
-    // (The any-alignment form can run in gangs too, by the knob: its pieces are cut relative to the lines, not to such
-    // boundaries, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p = 64, 128 KiB + 4: 125 against 121 us.)
+    // (The any-alignment form in rows that are not a multiple of 64 KiB apart can run in gangs too, by the knob: its
+    // pieces cannot lie on such boundaries at every rank, and gain 0-6 %: p = 128, 1 MiB + 4: 3.18 against 3.23 ms; p =
+    // 64, 128 KiB + 4: 125 against 121 us.  In rows that are: at the end of this function.)
     // Form 1's calls gain where they no longer fit the last-level cache and the blocks are long: from 240 MiB on with
     // blocks of 128 KiB and more, no cap (p = 16 with 1 MiB blocks 43.7 against 47.5 us, p = 8 with 4 MiB 52 against
     // 61-65 us, p = 20 with 768 KiB 58 against 63 us, p = 24 with 512 KiB 48.9 against 52 us, p = 48 with 128 KiB 49.2
