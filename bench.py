@@ -688,6 +688,11 @@ def main():
             dst = torch.empty_like(r_)
             t = time_calls(torch, lambda: dst.copy_(r_, non_blocking=True), stream, 3, 10)
             row["memcpy_d2d"] = {**t, **rates(pc, Bc, t["avg_ms"], "copy")}
+            # floor: PyTorch's fill kernel over the same receive buffers (every delivered byte written once, nothing read)
+            t = time_calls(torch, lambda: dst.fill_(0), stream, 2, 8)
+            row["fill"] = {**t, "write_GBps": pc * pc * Bc / t["avg_ms"] / 1e6,
+                           "frac_of_peak": pc * pc * Bc / t["avg_ms"] / 1e6 / HBM_PEAK_GBPS,
+                           "sparbit_over_fill": row["sparbit"]["avg_ms"] / t["avg_ms"]}
             per[name] = row
             del r_, dst, s_
             torch.cuda.empty_cache()
